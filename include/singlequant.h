@@ -1,0 +1,112 @@
+/*
+ * singlequant.h -- C ABI of the MI355X (gfx950) W4A4 inference hot path of
+ * SingleQuant (arxiv 2511.22316).
+ *
+ * The path of one quantized linear layer, Y ~= X W, is (Sec. 4.2, Eq. 1):
+ *
+ *     X' = X R,  R = G_1 G_2 ... G_P (R1 (x) R2)         online rotation
+ *     (Qx, sx) = int4 codes and per-token steps of X'      Sec. 3.2 quantizer
+ *     Y = dequant( Qx Qw^T ),  Qw = int4 codes of W^T R    offline-rotated weights
+ *
+ * Conventions common to every entry point
+ *   - "device" pointers are HIP device memory on the current device; "host"
+ *     pointers are ordinary host memory that is read before the call returns.
+ *   - The caller owns every buffer.  No entry point allocates, frees or
+ *     synchronises; all work is enqueued on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and the call returns at once.
+ *   - Arguments are validated on the host first.  On any error nothing is
+ *     enqueued and the code of the first failing check is returned.
+ *   - Token rows are row-major; channel k of a token is viewed as entry
+ *     (p, q) of an n1 x n2 matrix with k = p*n2 + q (row-major vectorisation,
+ *     Sec. 4.2 "Kronecker Product").
+ *   - int4 codes are two's-complement nibbles in [-8, 7], two per byte, the
+ *     LOW nibble holding the EVEN channel.
+ *   - NaN or Inf in X gives undefined codes (not checked).
+ */
+#ifndef SINGLEQUANT_H
+#define SINGLEQUANT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SQ_OK = 0,
+    SQ_ERR_NULL = 1,     /* a required pointer is NULL                                  */
+    SQ_ERR_SHAPE = 2,    /* K != n1*n2, K odd, a size <= 0 where > 0 is required, P < 0,
+                            a leading dimension shorter than its row, or a size beyond
+                            the limits below                                            */
+    SQ_ERR_INDEX = 3,    /* a Givens index outside [0, K) or i == j                     */
+    SQ_ERR_ALIGN = 4,    /* a pointer or leading dimension breaks the stated alignment  */
+    SQ_ERR_LAUNCH = 5    /* the HIP runtime refused the launch                          */
+} sq_status;
+
+/* Limits (SQ_ERR_SHAPE beyond them): n1 <= 128, n2 <= 256 and n2 a multiple
+ * of 8, K = n1*n2 <= 32768, P <= 64, K a multiple of 32 for the GEMM. */
+#define SQ_MAX_N1 128
+#define SQ_MAX_N2 256
+#define SQ_MAX_GIVENS 64
+
+/*
+ * sq_rotate_quantize -- online rotation fused with per-token 4-bit quantization.
+ *
+ * For every token row x of X (fp16, read as exact reals):
+ *   1. Givens list (Sec. 4.1; ART, Sec. 4.2), in order p = 0 .. P-1, on the
+ *      K-channel index space:  (x_i, x_j) <- (x_i cos t + x_j sin t,
+ *                                             x_j cos t - x_i sin t)
+ *      i.e. x <- x G(i_p, j_p; t_p) with the 2x2 block of Lemma 1 (App. A.3).
+ *      Pairs may share channels; the order is part of the definition.
+ *   2. Kronecker rotation (Eq. 18):  x' = rvec(R1^T X_mat R2),  X_mat the
+ *      n1 x n2 view of x;  R1, R2 are passed un-transposed.
+ *   3. Quantizer of Sec. 3.2 with a per-token step:  s = max_k |x'_k| / 7
+ *      (s = 1 for an all-zero row), code_k = clamp(floor(x'_k / s + 1/2), -8, 7).
+ * Arithmetic is fp32 or better; x' is never written to memory unless
+ * xrot_dbg is given.
+ *
+ *   X          device, fp16 [T, ldx]; rows 16-byte aligned (ldx % 8 == 0)
+ *   T, K, ldx  tokens, channels (= n1*n2, even), leading dimension >= K
+ *   giv_i/j    host, int32 [P]; giv_theta host, float [P] (radians); P may be 0
+ *              and then the three pointers may be NULL
+ *   R1, R2     device, fp16 [n1,n1] and [n2,n2], row-major, 16-byte aligned
+ *   Q          device out, uint8 [T, K/2], 16-byte aligned
+ *   scales     device out, float [T]
+ *   xrot_dbg   device out float [T, K], or NULL.  For parity checks only: it
+ *              triples the HBM traffic.
+ * T == 0 is legal and enqueues nothing.
+ */
+sq_status sq_rotate_quantize(const void *X, int64_t T, int32_t K, int64_t ldx,
+                             const int32_t *giv_i, const int32_t *giv_j,
+                             const float *giv_theta, int32_t P,
+                             const void *R1, int32_t n1,
+                             const void *R2, int32_t n2,
+                             uint8_t *Q, float *scales, float *xrot_dbg,
+                             void *stream);
+
+/*
+ * sq_w4a4_gemm -- int4 x int4 GEMM with dequantizing epilogue (Eq. 1 evaluated
+ * on the codes; the weight operand is Flat(W~_R) = W^T R of Sec. 4.2, one
+ * K-contiguous row per output channel).
+ *
+ *   acc[t, n] = sum_k Qx[t, k] * Qw[n, k]          exact, int32
+ *   Y[t, n]   = fp16( float(acc[t, n]) * sx[t] * sw[n] )
+ *
+ *   Qx, sx   device, uint8 [T, K/2] and float [T]  (what sq_rotate_quantize wrote)
+ *   Qw, sw   device, uint8 [N, K/2] and float [N]  (per-output-channel codes / steps)
+ *   Y        device out, fp16 [T, ldy], ldy >= N, rows 4-byte aligned (ldy even)
+ *   acc_dbg  device out int32 [T, N], or NULL (parity checks only)
+ * Requires K % 32 == 0, K <= 131072 (int32 accumulators cannot overflow),
+ * Qx, Qw 16-byte aligned.  T == 0 or N == 0 is legal and enqueues nothing.
+ */
+sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T, int32_t K,
+                       const uint8_t *Qw, const float *sw, int32_t N,
+                       void *Y, int64_t ldy, int32_t *acc_dbg, void *stream);
+
+/* Static, human-readable name of a status code. */
+const char *sq_status_string(sq_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SINGLEQUANT_H */

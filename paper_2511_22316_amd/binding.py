@@ -1,0 +1,106 @@
+"""Thin ctypes binding of ``libsinglequant.so`` (declared in ``include/singlequant.h``).
+
+Argument marshalling only: every step of the path runs inside the HIP library.  torch is used
+for device memory and streams.  There is no fallback: if the library has not been built the
+first call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libsinglequant.so")
+_lib = None
+
+SQ_OK = 0
+
+
+class SQError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"singlequant: {text} (status {code})")
+        self.code = code
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2511_22316_amd.build` "
+                "(there is no CPU fallback)")
+        lib = C.CDLL(_LIB_PATH)
+        lib.sq_rotate_quantize.restype = C.c_int
+        lib.sq_rotate_quantize.argtypes = [
+            C.c_void_p, C.c_int64, C.c_int32, C.c_int64,
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+            C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.sq_w4a4_gemm.restype = C.c_int
+        lib.sq_w4a4_gemm.argtypes = [
+            C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
+            C.c_void_p, C.c_void_p, C.c_int32,
+            C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
+        lib.sq_status_string.restype = C.c_char_p
+        lib.sq_status_string.argtypes = [C.c_int]
+        _lib = lib
+    return _lib
+
+
+def sq_status_string(code: int) -> str:
+    return _load().sq_status_string(int(code)).decode()
+
+
+def _check(code: int) -> None:
+    if code != SQ_OK:
+        raise SQError(code, sq_status_string(code))
+
+
+def _dev_ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream_handle(stream) -> Optional[int]:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream or None
+
+
+def _host(a, dtype):
+    return None if a is None else np.ascontiguousarray(a, dtype=dtype)
+
+
+def sq_rotate_quantize(X, giv_i, giv_j, giv_theta, R1, R2, Q, scales, xrot_dbg=None, stream=None) -> None:
+    """X fp16 [T, K] (row stride = X.stride(0)); giv_* host sequences of equal length P;
+    R1 fp16 [n1, n1]; R2 fp16 [n2, n2]; outputs Q uint8 [T, K/2], scales fp32 [T],
+    optional xrot_dbg fp32 [T, K].  All tensors are device tensors owned by the caller."""
+    gi, gj, gt = _host(giv_i, np.int32), _host(giv_j, np.int32), _host(giv_theta, np.float32)
+    P = 0 if gi is None else int(gi.size)
+    T, K = int(X.shape[0]), int(X.shape[1])
+    ldx = int(X.stride(0)) if T > 1 else K
+    code = _load().sq_rotate_quantize(
+        _dev_ptr(X), T, K, ldx,
+        None if gi is None else gi.ctypes.data, None if gj is None else gj.ctypes.data,
+        None if gt is None else gt.ctypes.data, P,
+        _dev_ptr(R1), int(R1.shape[0]), _dev_ptr(R2), int(R2.shape[0]),
+        _dev_ptr(Q), _dev_ptr(scales), _dev_ptr(xrot_dbg), _stream_handle(stream))
+    _check(code)
+
+
+def sq_w4a4_gemm(Qx, sx, Qw, sw, Y, acc_dbg=None, stream=None) -> None:
+    """Qx uint8 [T, K/2], sx fp32 [T], Qw uint8 [N, K/2], sw fp32 [N]; output Y fp16 [T, N]
+    (row stride = Y.stride(0)); optional acc_dbg int32 [T, N]."""
+    T, Kh = int(Qx.shape[0]), int(Qx.shape[1])
+    N = int(Qw.shape[0])
+    ldy = int(Y.stride(0)) if T > 1 else max(N, 1)
+    code = _load().sq_w4a4_gemm(
+        _dev_ptr(Qx), _dev_ptr(sx), T, 2 * Kh, _dev_ptr(Qw), _dev_ptr(sw), N,
+        _dev_ptr(Y), ldy, _dev_ptr(acc_dbg), _stream_handle(stream))
+    _check(code)
