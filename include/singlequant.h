@@ -44,9 +44,10 @@ typedef enum {
 } sq_status;
 
 /* Limits (SQ_ERR_SHAPE beyond them): n1 <= 128, n2 <= 256 and n2 a multiple
- * of 8, K = n1*n2 <= 32768, P <= 64, K a multiple of 32 for the GEMM. */
+ * of 8, K = n1*n2 <= 16384, P <= 64, K a multiple of 32 for the GEMM. */
 #define SQ_MAX_N1 128
 #define SQ_MAX_N2 256
+#define SQ_MAX_K 16384
 #define SQ_MAX_GIVENS 64
 
 /*
@@ -94,7 +95,7 @@ sq_status sq_rotate_quantize(const void *X, int64_t T, int32_t K, int64_t ldx,
  *
  *   Qx, sx   device, uint8 [T, K/2] and float [T]  (what sq_rotate_quantize wrote)
  *   Qw, sw   device, uint8 [N, K/2] and float [N]  (per-output-channel codes / steps)
- *   Y        device out, fp16 [T, ldy], ldy >= N, rows 4-byte aligned (ldy even)
+ *   Y        device out, fp16 [T, ldy], ldy >= N
  *   acc_dbg  device out int32 [T, N], or NULL (parity checks only)
  * Requires K % 32 == 0, K <= 131072 (int32 accumulators cannot overflow),
  * Qx, Qw 16-byte aligned.  T == 0 or N == 0 is legal and enqueues nothing.

@@ -1,0 +1,44 @@
+"""Build ``libsinglequant.so`` in-tree with hipcc for gfx950 (cross-compiles without a GPU).
+
+    python -m paper_2511_22316_amd.build
+"""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_ROOT = os.path.dirname(_HERE)
+_CSRC = os.path.join(_HERE, "csrc")
+_OUT = os.path.join(_HERE, "libsinglequant.so")
+
+SOURCES = ["sq_rotate_quantize.hip", "sq_w4a4_gemm.hip", "sq_status.cpp"]
+
+# packed-fp32 VALU forms are switched off for every HIP translation unit of this library
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Wno-unused-command-line-argument"]
+
+
+def build(verbose: bool = False, extra_flags=()) -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, *FLAGS, *extra_flags, "-I", os.path.join(_ROOT, "include"), "-I", _CSRC,
+           "-o", _OUT] + ["-x" if False else s for s in []]
+    for s in SOURCES:
+        path = os.path.join(_CSRC, s)
+        cmd += (["-x", "hip", path] if s.endswith(".cpp") else [path])
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    noise = "is not a recognized feature for this target"
+    err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+    if res.returncode != 0:
+        raise RuntimeError(f"hipcc failed:\n{err}")
+    if verbose and err.strip():
+        print(err, file=sys.stderr)
+    return _OUT
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

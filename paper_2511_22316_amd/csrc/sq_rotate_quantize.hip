@@ -1,0 +1,151 @@
+// sq_rotate_quantize: online rotation (Givens list, then Kronecker product, Sec. 4.1-4.2, Eq. 18)
+// fused with the per-token 4-bit rounding quantizer of Sec. 3.2.  gfx950 only.
+#include "sq_common.h"
+
+#include <math.h>
+
+namespace sq {
+
+// ------------------------------------------------------------------------------------------
+// Generic kernel: any (n1, n2) with n2 % 8 == 0.  One workgroup per token, the token row and
+// the intermediate V_mat R2 live in LDS as fp32, contractions are plain fp32 FMAs.
+//   stage 0  x <- x G_1 ... G_P                 (one lane, in list order: pairs may overlap)
+//   stage A  Z = X_mat R2                       (n1 x n2) (n2 x n2)
+//   stage B  Y = R1^T Z                         (n1 x n1)^T (n1 x n2)
+//   stage Q  s = max|Y| / 7, codes = floor(Y / s + 1/2), two nibbles per byte
+// ------------------------------------------------------------------------------------------
+constexpr int kGenThreads = 256;
+
+__global__ __launch_bounds__(kGenThreads) void rotate_quantize_generic_kernel(
+    const __half *__restrict__ X, int64_t ldx, int K, int n1, int n2, GivensList giv,
+    const __half *__restrict__ R1, const __half *__restrict__ R2, uint8_t *__restrict__ Q,
+    float *__restrict__ scales, float *__restrict__ xrot)
+{
+    extern __shared__ float smem[];
+    float *xs = smem;          // [K]  token row, then reused for Y
+    float *zs = smem + K;      // [K]  Z = X_mat R2
+    __shared__ float red[kGenThreads / kWave];
+
+    const int tid = threadIdx.x;
+    const int64_t t = blockIdx.x;
+    const __half *xrow = X + t * ldx;
+
+    for (int c = tid; c < K / 8; c += kGenThreads) {
+        const uint4 raw = *reinterpret_cast<const uint4 *>(xrow + c * 8);
+        const __half *h = reinterpret_cast<const __half *>(&raw);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) xs[c * 8 + u] = __half2float(h[u]);
+    }
+    __syncthreads();
+
+    if (tid == 0) {
+        for (int p = 0; p < giv.count; ++p) {
+            const float a = xs[giv.i[p]], b = xs[giv.j[p]];
+            xs[giv.i[p]] = a * giv.c[p] + b * giv.s[p];
+            xs[giv.j[p]] = b * giv.c[p] - a * giv.s[p];
+        }
+    }
+    __syncthreads();
+
+    // stage A: each thread makes 4 consecutive output columns of one row of Z
+    const int n2q = n2 / 4;
+    for (int o = tid; o < n1 * n2q; o += kGenThreads) {
+        const int p = o / n2q, q0 = (o % n2q) * 4;
+        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+        const float *xr = xs + p * n2;
+        for (int q = 0; q < n2; ++q) {
+            const float xv = xr[q];
+            const uint2 raw = *reinterpret_cast<const uint2 *>(R2 + (int64_t)q * n2 + q0);
+            const __half *h = reinterpret_cast<const __half *>(&raw);
+            a0 = fmaf(xv, __half2float(h[0]), a0);
+            a1 = fmaf(xv, __half2float(h[1]), a1);
+            a2 = fmaf(xv, __half2float(h[2]), a2);
+            a3 = fmaf(xv, __half2float(h[3]), a3);
+        }
+        float *zr = zs + p * n2 + q0;
+        zr[0] = a0; zr[1] = a1; zr[2] = a2; zr[3] = a3;
+    }
+    __syncthreads();
+
+    // stage B: Y[p', q'] = sum_p R1[p, p'] Z[p, q'];  written over xs
+    float amax = 0.f;
+    for (int o = tid; o < n1 * n2q; o += kGenThreads) {
+        const int po = o / n2q, q0 = (o % n2q) * 4;
+        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+        for (int p = 0; p < n1; ++p) {
+            const float r = __half2float(R1[(int64_t)p * n1 + po]);
+            const float *zr = zs + p * n2 + q0;
+            a0 = fmaf(r, zr[0], a0);
+            a1 = fmaf(r, zr[1], a1);
+            a2 = fmaf(r, zr[2], a2);
+            a3 = fmaf(r, zr[3], a3);
+        }
+        float *yr = xs + po * n2 + q0;
+        yr[0] = a0; yr[1] = a1; yr[2] = a2; yr[3] = a3;
+        amax = fmaxf(amax, fmaxf(fmaxf(fabsf(a0), fabsf(a1)), fmaxf(fabsf(a2), fabsf(a3))));
+    }
+    amax = wave_max(amax);
+    if ((tid & (kWave - 1)) == 0) red[tid / kWave] = amax;
+    __syncthreads();
+    amax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+
+    const float step = (amax == 0.f) ? 1.0f : amax / 7.0f;
+    if (tid == 0) scales[t] = step;
+
+    uint32_t *qrow = reinterpret_cast<uint32_t *>(Q + t * (int64_t)(K / 2));
+    for (int c = tid; c < K / 8; c += kGenThreads) {
+        uint32_t word = 0;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            float v = floorf(xs[c * 8 + u] / step + 0.5f);
+            v = fminf(fmaxf(v, -8.0f), 7.0f);
+            word |= (static_cast<uint32_t>(static_cast<int>(v)) & 0xFu) << (4 * u);
+        }
+        qrow[c] = word;
+    }
+    if (xrot != nullptr) {
+        float *orow = xrot + t * (int64_t)K;
+        for (int k = tid; k < K; k += kGenThreads) orow[k] = xs[k];
+    }
+}
+
+}  // namespace sq
+
+extern "C" sq_status sq_rotate_quantize(const void *X, int64_t T, int32_t K, int64_t ldx,
+                                        const int32_t *giv_i, const int32_t *giv_j,
+                                        const float *giv_theta, int32_t P, const void *R1,
+                                        int32_t n1, const void *R2, int32_t n2, uint8_t *Q,
+                                        float *scales, float *xrot_dbg, void *stream)
+{
+    if (T < 0 || K <= 0 || n1 <= 0 || n2 <= 0 || P < 0) return SQ_ERR_SHAPE;
+    if (n1 > SQ_MAX_N1 || n2 > SQ_MAX_N2 || P > SQ_MAX_GIVENS) return SQ_ERR_SHAPE;
+    if ((int64_t)n1 * n2 != K || (n2 % 8) != 0 || K > SQ_MAX_K || ldx < K) return SQ_ERR_SHAPE;
+    if (T > 0x7fffffff) return SQ_ERR_SHAPE;
+    if (P > 0 && (!giv_i || !giv_j || !giv_theta)) return SQ_ERR_NULL;
+    if (!R1 || !R2) return SQ_ERR_NULL;
+    if (T > 0 && (!X || !Q || !scales)) return SQ_ERR_NULL;
+    sq::GivensList giv;
+    giv.count = P;
+    for (int p = 0; p < P; ++p) {
+        if (giv_i[p] < 0 || giv_i[p] >= K || giv_j[p] < 0 || giv_j[p] >= K || giv_i[p] == giv_j[p])
+            return SQ_ERR_INDEX;
+        giv.i[p] = giv_i[p];
+        giv.j[p] = giv_j[p];
+        giv.c[p] = (float)cos((double)giv_theta[p]);
+        giv.s[p] = (float)sin((double)giv_theta[p]);
+    }
+    if ((ldx % 8) != 0 || ((uintptr_t)X & 15) || ((uintptr_t)Q & 15) || ((uintptr_t)R1 & 15) ||
+        ((uintptr_t)R2 & 15) || ((uintptr_t)scales & 3) || ((uintptr_t)xrot_dbg & 3))
+        return SQ_ERR_ALIGN;
+    if (T == 0) return SQ_OK;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const size_t lds = sizeof(float) * 2 * (size_t)K;
+    if (!sq::allow_large_lds(reinterpret_cast<const void *>(sq::rotate_quantize_generic_kernel)))
+        return SQ_ERR_LAUNCH;
+    hipLaunchKernelGGL(sq::rotate_quantize_generic_kernel, dim3((unsigned)T), dim3(sq::kGenThreads),
+                       lds, st, static_cast<const __half *>(X), ldx, K, n1, n2, giv,
+                       static_cast<const __half *>(R1), static_cast<const __half *>(R2), Q, scales,
+                       xrot_dbg);
+    return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}

@@ -1,0 +1,91 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, it exports every symbol the
+header declares, and argument validation returns the documented codes before anything is
+enqueued (the device pointers below are never dereferenced)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2511_22316_amd as sq
+from paper_2511_22316_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(sq.library_path()):
+        from paper_2511_22316_amd import build
+        build.build()
+    return binding._load()
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "singlequant.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(sq_[a-z0-9_]+)\s*\(", header))
+    assert {"sq_rotate_quantize", "sq_w4a4_gemm", "sq_status_string"} <= declared
+    for name in declared:
+        assert hasattr(lib, name), f"{name} is declared in singlequant.h but not exported"
+
+
+def test_status_strings(lib):
+    texts = {sq.sq_status_string(c) for c in range(6)}
+    assert len(texts) == 6 and sq.sq_status_string(0) == "ok"
+    assert sq.sq_status_string(99) == "unknown status"
+
+
+FAKE = 0x1000          # 16-byte aligned, never dereferenced: validation fails first
+
+
+def _rq(lib, T=4, K=64, ldx=64, gi=(1,), gj=(2,), gt=(0.1,), n1=8, n2=8, X=FAKE, R1=FAKE, R2=FAKE,
+        Q=FAKE, s=FAKE):
+    gi_a, gj_a = np.asarray(gi, np.int32), np.asarray(gj, np.int32)
+    gt_a = np.asarray(gt, np.float32)
+    return lib.sq_rotate_quantize(X, T, K, ldx, gi_a.ctypes.data, gj_a.ctypes.data, gt_a.ctypes.data,
+                                  len(gi_a), R1, n1, R2, n2, Q, s, None, None)
+
+
+def test_rotate_quantize_argument_errors(lib):
+    assert _rq(lib, K=63) == 2                      # K != n1*n2
+    assert _rq(lib, n1=4, n2=16, K=65) == 2
+    assert _rq(lib, T=-1) == 2
+    assert _rq(lib, ldx=32) == 2                    # leading dimension shorter than a row
+    assert _rq(lib, K=36, n1=9, n2=4, ldx=40) == 2  # n2 not a multiple of 8
+    assert _rq(lib, K=129 * 8, n1=129, n2=8, ldx=129 * 8) == 2
+    assert _rq(lib, gi=(64,)) == 3                  # index out of range
+    assert _rq(lib, gi=(-1,)) == 3
+    assert _rq(lib, gi=(5,), gj=(5,)) == 3          # i == j
+    assert _rq(lib, X=None) == 1
+    assert _rq(lib, R1=None) == 1
+    assert _rq(lib, Q=None) == 1
+    assert _rq(lib, X=FAKE + 2) == 4
+    assert _rq(lib, ldx=68) == 4                    # rows not 16-byte aligned
+    assert _rq(lib, T=0) == 0                       # nothing to do, nothing enqueued
+    many = tuple(range(65))
+    assert _rq(lib, gi=many, gj=tuple(i + 1 for i in many), gt=(0.0,) * 65, K=128, n1=8, n2=16, ldx=128) == 2
+
+
+def _gemm(lib, T=4, K=64, N=8, ldy=8, Qx=FAKE, sx=FAKE, Qw=FAKE, sw=FAKE, Y=FAKE):
+    return lib.sq_w4a4_gemm(Qx, sx, T, K, Qw, sw, N, Y, ldy, None, None)
+
+
+def test_gemm_argument_errors(lib):
+    assert _gemm(lib, K=48) == 2                    # K not a multiple of 32
+    assert _gemm(lib, K=0) == 2
+    assert _gemm(lib, T=-1) == 2
+    assert _gemm(lib, ldy=6) == 2
+    assert _gemm(lib, K=262144) == 2
+    assert _gemm(lib, Qx=None) == 1
+    assert _gemm(lib, Y=None) == 1
+    assert _gemm(lib, Qw=FAKE + 8) == 4
+    assert _gemm(lib, T=0) == 0
+    assert _gemm(lib, N=0, ldy=0) == 0
+
+
+def test_binding_raises_on_error(lib):
+    with pytest.raises(sq.SQError) as e:
+        binding._check(lib.sq_w4a4_gemm(FAKE, FAKE, 4, 48, FAKE, FAKE, 8, FAKE, 8, None, None))
+    assert e.value.code == 2

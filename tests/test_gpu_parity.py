@@ -1,0 +1,246 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on the same
+seeded inputs.  Element by element at sizes the oracle finishes in seconds; sampled rows,
+sampled elements and exact checksums at the full benchmark sizes."""
+import numpy as np
+import pytest
+
+from paper_2511_22316_amd import synth
+from parity_util import (Y_ROW_TOL, check_codes, check_rotation, codes_of, half_ulp_distance,
+                         run_gemm, run_rotate_quantize)
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle_rq(oracle, L, X=None):
+    X = L.X if X is None else X
+    xr = oracle.rotate(X, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)
+    Q, s = oracle.quantize_rows(xr)
+    return xr, Q, s
+
+
+# ------------------------------------------------------------------ rotate + quantize -----
+
+@pytest.mark.parametrize("name,T", [("tiny", 16), ("attn_proj", 77), ("mlp_down", 40), ("decode", 8),
+                                    ("large_prefill", 33)])
+def test_rotate_quantize_elementwise(oracle, name, T):
+    print(f"case rotate_quantize {name} T={T}", flush=True)
+    L = synth.layer(synth.CONFIGS[name], T)
+    Qg, sg, xg = run_rotate_quantize(L)
+    xo, Qo, so = _oracle_rq(oracle, L)
+    check_rotation(xg, xo)
+    check_codes(Qg, sg, Qo, so)
+    # the quantizer alone, decided in the kernel's precision: the oracle's fp32 quantizer fed
+    # with the GPU's own rotated rows must give the GPU's codes (up to 1-ulp ties in x/s + 1/2)
+    Qf, sf = oracle.quantize_rows(xg)
+    assert np.array_equal(sf, sg)
+    d = np.abs(codes_of(Qf) - codes_of(Qg))
+    assert d.max() <= 1 and np.count_nonzero(d) <= 1e-5 * d.size + 1
+
+
+def test_rotate_quantize_full_attn_proj(oracle):
+    print("case rotate_quantize attn_proj full", flush=True)
+    L = synth.layer(synth.CONFIGS["attn_proj"])
+    Qg, sg, xg = run_rotate_quantize(L)
+    xo, Qo, so = _oracle_rq(oracle, L)
+    check_rotation(xg, xo)
+    check_codes(Qg, sg, Qo, so)
+    # without the debug output the codes must be the same bytes
+    Qg2, sg2, _ = run_rotate_quantize(L, want_xrot=False)
+    assert np.array_equal(Qg, Qg2) and np.array_equal(sg, sg2)
+
+
+@pytest.mark.parametrize("name", ["mlp_down", "large_prefill"])
+def test_rotate_quantize_full_size_sampled_rows(oracle, name):
+    print(f"case rotate_quantize {name} full size, sampled rows", flush=True)
+    cfg = synth.CONFIGS[name]
+    L = synth.layer(cfg)
+    Qg, sg, _ = run_rotate_quantize(L, want_xrot=False)
+    rows = np.unique(np.concatenate([[0, 1, cfg.T - 1], np.random.default_rng(1).integers(0, cfg.T, 45)]))
+    xo, Qo, so = _oracle_rq(oracle, L, L.X[rows])
+    check_codes(Qg[rows], sg[rows], Qo, so)
+    # properties that hold for every row: full use of the range, |code| <= 7
+    q = codes_of(Qg)
+    assert np.all(np.max(np.abs(q), axis=1) == 7)
+
+
+def test_rotate_quantize_edge_cases(oracle):
+    print("case rotate_quantize edge cases", flush=True)
+    import torch
+    import paper_2511_22316_amd as sq
+    cfg = synth.CONFIGS["tiny"]
+    L = synth.layer(cfg)
+    # an all-zero token, a token that is exactly representable after rotation by identity
+    X = L.X.copy()
+    X[3] = 0
+    Qg, sg, xg = run_rotate_quantize(L, X)
+    xo, Qo, so = _oracle_rq(oracle, L, X)
+    assert sg[3] == 1.0 and np.all(Qg[3] == 0) and np.all(xg[3] == 0)
+    check_rotation(np.delete(xg, 3, 0), np.delete(xo, 3, 0))
+    check_codes(Qg, sg, Qo, so)
+    # no Givens pairs at all
+    L0 = synth.Layer(cfg, L.X, L.giv_i[:0], L.giv_j[:0], L.giv_theta[:0], L.R1, L.R2, L.R1_f64, L.R2_f64)
+    Qg, sg, xg = run_rotate_quantize(L0)
+    xo, Qo, so = _oracle_rq(oracle, L0)
+    check_rotation(xg, xo)
+    check_codes(Qg, sg, Qo, so)
+    # T = 0 enqueues nothing and succeeds
+    e = torch.empty((0, cfg.K), dtype=torch.float16, device="cuda")
+    sq.sq_rotate_quantize(e, L.giv_i, L.giv_j, L.giv_theta, torch.from_numpy(L.R1).cuda(),
+                          torch.from_numpy(L.R2).cuda(),
+                          torch.empty((0, cfg.K // 2), dtype=torch.uint8, device="cuda"),
+                          torch.empty((0,), dtype=torch.float32, device="cuda"))
+    # a strided X (ldx > K) reads the right rows
+    wide = torch.zeros((cfg.T, cfg.K + 64), dtype=torch.float16, device="cuda")
+    wide[:, : cfg.K] = torch.from_numpy(L.X).cuda()
+    Q = torch.empty((cfg.T, cfg.K // 2), dtype=torch.uint8, device="cuda")
+    s = torch.empty((cfg.T,), dtype=torch.float32, device="cuda")
+    sq.sq_rotate_quantize(wide[:, : cfg.K], L.giv_i, L.giv_j, L.giv_theta, torch.from_numpy(L.R1).cuda(),
+                          torch.from_numpy(L.R2).cuda(), Q, s)
+    torch.cuda.synchronize()
+    Qref, sref, _ = run_rotate_quantize(L, want_xrot=False)
+    assert np.array_equal(Q.cpu().numpy(), Qref) and np.array_equal(s.cpu().numpy(), sref)
+
+
+def test_rotate_quantize_identity_rotation_is_exact(oracle):
+    """R1 = I, R2 = I, no Givens: the rotated row is the fp16 input itself, bit for bit."""
+    print("case rotate_quantize identity", flush=True)
+    cfg = synth.CONFIGS["tiny"]
+    L = synth.layer(cfg)
+    Li = synth.Layer(cfg, L.X, L.giv_i[:0], L.giv_j[:0], L.giv_theta[:0],
+                     np.eye(cfg.n1, dtype=np.float16), np.eye(cfg.n2, dtype=np.float16), None, None)
+    Qg, sg, xg = run_rotate_quantize(Li)
+    assert np.array_equal(xg, L.X.astype(np.float32))
+    Qo, so = oracle.quantize_rows(L.X.astype(np.float64))
+    check_codes(Qg, sg, Qo, so)
+
+
+# ------------------------------------------------------------------------------ GEMM ------
+
+@pytest.mark.parametrize("T,K,N", [(1, 32, 1), (16, 512, 512), (77, 96, 300), (130, 288, 257),
+                                   (8, 1024, 520), (300, 2048, 130)])
+def test_gemm_random_codes_bit_exact(oracle, T, K, N):
+    print(f"case gemm random codes T={T} K={K} N={N}", flush=True)
+    g = np.random.default_rng(T * 7 + K + N)
+    Qx = synth.random_codes(T, K, 100 + T)        # all 16 codes, -8 included
+    Qw = synth.random_codes(N, K, 200 + N)
+    sx = g.uniform(0.05, 4.0, T).astype(np.float32)
+    sw = g.uniform(1e-4, 5e-3, N).astype(np.float32)
+    Yg, accg = run_gemm(Qx, sx, Qw, sw)
+    Yo, acco = oracle.gemm(Qx, sx, Qw, sw)
+    assert np.array_equal(accg, acco)
+    assert half_ulp_distance(Yg, Yo).max() <= 1
+    # extreme codes: every product is (-8)(-8)
+    Qm = np.full((T, K // 2), 0x88, np.uint8)
+    Qn = np.full((N, K // 2), 0x88, np.uint8)
+    _, accm = run_gemm(Qm, sx, Qn, sw)
+    assert np.all(accm == 64 * K)
+
+
+def test_gemm_strided_output_and_empty(oracle):
+    print("case gemm strided output / empty", flush=True)
+    import torch
+    import paper_2511_22316_amd as sq
+    T, K, N = 40, 256, 72
+    Qx, Qw = synth.random_codes(T, K, 1), synth.random_codes(N, K, 2)
+    sx = np.full(T, 0.5, np.float32)
+    sw = np.full(N, 0.25, np.float32)
+    Ywide = torch.full((T, N + 10), -1.0, dtype=torch.float16, device="cuda")
+    sq.sq_w4a4_gemm(torch.from_numpy(Qx).cuda(), torch.from_numpy(sx).cuda(), torch.from_numpy(Qw).cuda(),
+                    torch.from_numpy(sw).cuda(), Ywide[:, :N])
+    torch.cuda.synchronize()
+    Yo, _ = oracle.gemm(Qx, sx, Qw, sw)
+    got = Ywide.cpu().numpy()
+    assert np.array_equal(got[:, :N], Yo) and np.all(got[:, N:] == -1.0)
+    sq.sq_w4a4_gemm(torch.empty((0, K // 2), dtype=torch.uint8, device="cuda"),
+                    torch.empty((0,), dtype=torch.float32, device="cuda"),
+                    torch.from_numpy(Qw).cuda(), torch.from_numpy(sw).cuda(),
+                    torch.empty((0, N), dtype=torch.float16, device="cuda"))
+
+
+# --------------------------------------------------------------- the whole layer ----------
+
+def _gpu_weights(L, Wt):
+    """Offline weight path on the GPU: the rows of W^T take the same transform and the same
+    quantizer as token rows (Sec. 4.2, Flat(W~_R) = W^T R)."""
+    Q, s, _ = run_rotate_quantize(L, Wt, want_xrot=False)
+    return Q, s
+
+
+@pytest.mark.parametrize("name", ["tiny", "decode_small"])
+def test_layer_end_to_end(oracle, name):
+    print(f"case layer end to end {name}", flush=True)
+    if name == "tiny":
+        cfg, N = synth.CONFIGS["tiny"], 512
+    else:
+        cfg, N = synth.CONFIGS["decode"], 300
+    L = synth.layer(cfg)
+    Wt = synth.weights_t(cfg, N)
+    # oracle pipeline
+    xo, Qxo, sxo = _oracle_rq(oracle, L)
+    Qwo, swo = oracle.prepare_weights(Wt, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)
+    Yo, acco = oracle.gemm(Qxo, sxo, Qwo, swo)
+    # GPU GEMM on the oracle's codes: exact accumulators, Y within one fp16 ulp
+    Yg1, accg1 = run_gemm(Qxo, sxo, Qwo, swo)
+    assert np.array_equal(accg1, acco) and half_ulp_distance(Yg1, Yo).max() <= 1
+    # GPU pipeline end to end (its own codes on both sides)
+    Qxg, sxg, _ = run_rotate_quantize(L, want_xrot=False)
+    Qwg, swg = _gpu_weights(L, Wt)
+    check_codes(Qwg, swg, Qwo, swo)
+    Yg, _ = run_gemm(Qxg, sxg, Qwg, swg)
+    d = Yg.astype(np.float64) - Yo.astype(np.float64)
+    rel = np.linalg.norm(d, axis=1) / np.linalg.norm(Yo.astype(np.float64), axis=1)
+    assert rel.max() <= Y_ROW_TOL, f"fp16 Y: worst row error {rel.max():.3e}"
+
+
+@pytest.mark.parametrize("name", ["attn_proj", "mlp_down", "decode", "large_prefill"])
+def test_gemm_full_size_checksums_and_samples(oracle, name):
+    """Full benchmark shapes, the launch configuration the benchmark times: exact int64 checksum
+    invariants over every accumulator, sampled accumulators from the oracle, and Y recomputed
+    from the accumulators on sampled rows."""
+    print(f"case gemm full size {name}", flush=True)
+    import torch
+    import paper_2511_22316_amd as sq
+    cfg = synth.CONFIGS[name]
+    L = synth.layer(cfg)
+    Qx, sx, _ = run_rotate_quantize(L, want_xrot=False)
+    T, K, N = cfg.T, cfg.K, cfg.N
+    dR1, dR2 = torch.from_numpy(L.R1).cuda(), torch.from_numpy(L.R2).cuda()
+    Qw_d = torch.empty((N, K // 2), dtype=torch.uint8, device="cuda")
+    sw_d = torch.empty((N,), dtype=torch.float32, device="cuda")
+    step = 4096
+    for lo in range(0, N, step):                      # weights drawn and prepared in slabs
+        hi = min(N, lo + step)
+        Wt = torch.from_numpy(synth.weight_rows_t(cfg, np.arange(lo, hi))).cuda()
+        sq.sq_rotate_quantize(Wt, L.giv_i, L.giv_j, L.giv_theta, dR1, dR2, Qw_d[lo:hi], sw_d[lo:hi])
+    torch.cuda.synchronize()
+    Qw, sw = Qw_d.cpu().numpy(), sw_d.cpu().numpy()
+    Y_d = torch.empty((T, N), dtype=torch.float16, device="cuda")
+    acc_d = torch.empty((T, N), dtype=torch.int32, device="cuda")
+    sq.sq_w4a4_gemm(torch.from_numpy(Qx).cuda(), torch.from_numpy(sx).cuda(), Qw_d, sw_d, Y_d, acc_d)
+    torch.cuda.synchronize()
+    col_sum = acc_d.sum(dim=0, dtype=torch.int64).cpu().numpy()
+    row_sum = acc_d.sum(dim=1, dtype=torch.int64).cpu().numpy()
+    # sums of codes are small integers: float64 matrix products are exact here
+    cx = codes_of(Qx).astype(np.float64)
+    cw = codes_of(Qw).astype(np.float64)
+    assert np.array_equal(col_sum, (cx.sum(axis=0) @ cw.T).astype(np.int64))
+    assert np.array_equal(row_sum, (cx @ cw.sum(axis=0)).astype(np.int64))
+    g = np.random.default_rng(5)
+    ts = np.concatenate([[0, T - 1], g.integers(0, T, 30)])
+    ns = np.concatenate([[0, N - 1], g.integers(0, N, 30)])
+    acc_s = acc_d[torch.from_numpy(ts).cuda()][:, torch.from_numpy(ns).cuda()].cpu().numpy()
+    for a, t in enumerate(ts):
+        for b, n in enumerate(ns):
+            assert acc_s[a, b] == oracle.gemm_acc_at(Qx, Qw, int(t), int(n))
+    rows = torch.from_numpy(ts).cuda()
+    acc_rows = acc_d[rows].cpu().numpy().astype(np.float64)
+    want = (acc_rows * sx[ts, None].astype(np.float64) * sw[None, :].astype(np.float64)).astype(np.float16)
+    assert half_ulp_distance(Y_d[rows].cpu().numpy(), want).max() <= 1
+    # the run without the debug output writes the same Y
+    Y2 = torch.empty_like(Y_d)
+    sq.sq_w4a4_gemm(torch.from_numpy(Qx).cuda(), torch.from_numpy(sx).cuda(), Qw_d, sw_d, Y2)
+    torch.cuda.synchronize()
+    assert torch.equal(Y2, Y_d)
+    # weight codes of sampled output channels against the oracle's offline path
+    Qwo, swo = oracle.prepare_weights(synth.weight_rows_t(cfg, ns), L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)
+    check_codes(Qw[ns], sw[ns], Qwo, swo)
