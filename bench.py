@@ -1,0 +1,208 @@
+#!/usr/bin/env python3
+"""Benchmark of the W4A4 hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic layer: sq_rotate_quantize on X, then
+sq_w4a4_gemm against weights that were rotated and quantized beforehand (the offline phase).
+The headline workload is the attention-projection shape T=2048, K=N=4096.  Inputs are resident in
+HBM before the clock starts, and the step cycles through a ring of buffer sets larger than the
+256 MB last-level cache so that "HBM" numbers are not cache numbers.
+
+Prints ONE JSON line: layer time (us), the per-kernel rates, the roofline of the dominant kernel
+(the GEMM: int8 MFMA) and of the rotate+quantize kernel (HBM), and the CPU oracle timed on this
+box's host cores beside them.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
+INT8_MFMA_PEAK_TOPS = 5000.0    # MI355X dense int8 matrix peak
+RING_BYTES = 640 << 20          # > 2x the 256 MB Infinity Cache
+
+
+def rq_bytes(T: int, K: int) -> float:
+    """Algorithmic HBM bytes of rotate+quantize: fp16 row in, nibble codes and one fp32 step out."""
+    return 2.5 * T * K + 4.0 * T
+
+
+def gemm_ops(T: int, K: int, N: int) -> float:
+    return 2.0 * T * K * N
+
+
+class LayerBuffers:
+    """Ring of device buffer sets for one layer shape."""
+
+    def __init__(self, cfg, torch, sq, synth, sets=None):
+        self.cfg, self.torch, self.sq = cfg, torch, sq
+        dev = torch.device("cuda:0")
+        L = synth.layer(cfg)
+        self.L = L
+        T, K, N = cfg.T, cfg.K, cfg.N
+        per_set = 2 * T * K + T * K // 2 + 2 * T * N + N * K // 2
+        self.sets = sets or max(2, min(16, -(-RING_BYTES // per_set)))
+        self.R1 = torch.from_numpy(L.R1).to(dev)
+        self.R2 = torch.from_numpy(L.R2).to(dev)
+        X0 = torch.from_numpy(L.X).to(dev)
+        # offline phase: W^T rows get the same transform and quantizer (Sec. 4.2), on the GPU
+        Qw0 = torch.empty((N, K // 2), dtype=torch.uint8, device=dev)
+        sw0 = torch.empty((N,), dtype=torch.float32, device=dev)
+        slab = 4096
+        for lo in range(0, N, slab):
+            hi = min(N, lo + slab)
+            Wt = torch.from_numpy(synth.weight_rows_t(cfg, np.arange(lo, hi))).to(dev)
+            sq.sq_rotate_quantize(Wt, L.giv_i, L.giv_j, L.giv_theta, self.R1, self.R2, Qw0[lo:hi], sw0[lo:hi])
+        torch.cuda.synchronize()
+        self.X, self.Qw, self.sw, self.Q, self.s, self.Y = [], [], [], [], [], []
+        for i in range(self.sets):
+            # other sets: the same rows in another order (same distribution, other addresses)
+            self.X.append(X0 if i == 0 else torch.roll(X0, shifts=7 * i, dims=0).contiguous())
+            self.Qw.append(Qw0 if i == 0 else torch.roll(Qw0, shifts=5 * i, dims=0).contiguous())
+            self.sw.append(sw0 if i == 0 else torch.roll(sw0, shifts=5 * i, dims=0).contiguous())
+            self.Q.append(torch.empty((T, K // 2), dtype=torch.uint8, device=dev))
+            self.s.append(torch.empty((T,), dtype=torch.float32, device=dev))
+            self.Y.append(torch.empty((T, N), dtype=torch.float16, device=dev))
+        torch.cuda.synchronize()
+
+    def rotate_quantize(self, i):
+        L = self.L
+        self.sq.sq_rotate_quantize(self.X[i], L.giv_i, L.giv_j, L.giv_theta, self.R1, self.R2, self.Q[i], self.s[i])
+
+    def gemm(self, i):
+        self.sq.sq_w4a4_gemm(self.Q[i], self.s[i], self.Qw[i], self.sw[i], self.Y[i])
+
+    def step(self, i):
+        self.rotate_quantize(i)
+        self.gemm(i)
+
+
+def timed(torch, fn, sets, steps, warmup):
+    """(wall ms per call, event ms per call): events are recorded on the stream the kernels use."""
+    for w in range(warmup):
+        fn(w % sets)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for k in range(steps):
+        fn(k % sets)
+    e1.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3 / steps
+    return wall, e0.elapsed_time(e1) / steps
+
+
+def measure_layer(cfg, torch, sq, synth, steps, warmup):
+    B = LayerBuffers(cfg, torch, sq, synth)
+    T, K, N = cfg.T, cfg.K, cfg.N
+    wall_ms, ev_ms = timed(torch, B.step, B.sets, steps, warmup)
+    _, rq_ms = timed(torch, B.rotate_quantize, B.sets, steps, warmup)
+    _, gm_ms = timed(torch, B.gemm, B.sets, steps, warmup)
+    out = {
+        "workload": cfg.name, "T": T, "K": K, "N": N, "n1": cfg.n1, "n2": cfg.n2, "givens_pairs": cfg.P,
+        "layer_us": wall_ms * 1e3, "layer_us_events": ev_ms * 1e3,
+        "rotate_quant_us": rq_ms * 1e3, "gemm_us": gm_ms * 1e3,
+        "rotate_quant_GBps": rq_bytes(T, K) / (rq_ms * 1e-3) / 1e9,
+        "gemm_int_TOPS": gemm_ops(T, K, N) / (gm_ms * 1e-3) / 1e12,
+        "gemm_weight_stream_GBps": (N * K / 2) / (gm_ms * 1e-3) / 1e9,
+        "ring_sets": B.sets,
+    }
+    del B
+    torch.cuda.empty_cache()
+    return out
+
+
+def cpu_baseline(cfg, synth):
+    """The CPU oracle, as it stands, on this machine's host cores: rotate+quantize of every token and
+    the integer GEMM on the first 512 tokens (scaled linearly in T)."""
+    import oracle
+    oracle.build()
+    L = synth.layer(cfg)
+    Ts = min(cfg.T, 512)
+    Wt = synth.weights_t(cfg)
+    Qw, sw = oracle.prepare_weights(Wt, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)   # offline, untimed
+    t0 = time.perf_counter()
+    Qx, sx = oracle.quantize_rows(oracle.rotate(L.X, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2))
+    t_rq = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    oracle.gemm(Qx[:Ts], sx[:Ts], Qw, sw)
+    t_gemm = (time.perf_counter() - t0) * (cfg.T / Ts)
+    return {
+        "value": (t_rq + t_gemm) * 1e6, "unit": "us", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": f"rotate+quantize of all {cfg.T} tokens timed in full; GEMM timed on the first {Ts} tokens "
+                  f"x all {cfg.N} outputs and scaled by {cfg.T / Ts:g}",
+        "rotate_quant_GBps": rq_bytes(cfg.T, cfg.K) / t_rq / 1e9,
+        "gemm_int_TOPS": gemm_ops(cfg.T, cfg.K, cfg.N) / t_gemm / 1e12,
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="attn_proj", help="layer shape for the headline number")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the other layer shapes")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2511_22316_amd as sq
+    from paper_2511_22316_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    if not os.path.exists(sq.library_path()):
+        from paper_2511_22316_amd import build
+        build.build()
+
+    cfg = synth.CONFIGS[args.workload]
+    head = measure_layer(cfg, torch, sq, synth, args.steps, args.warmup)
+    extra = {}
+    if not args.no_extra:
+        for name, st in (("mlp_down", max(10, args.steps // 4)), ("decode", args.steps),
+                         ("large_prefill", max(5, args.steps // 20))):
+            if name != args.workload:
+                extra[name] = measure_layer(synth.CONFIGS[name], torch, sq, synth, st, max(2, args.warmup // 4))
+
+    gemm_tops = head["gemm_int_TOPS"]
+    result = {
+        "metric": "layer time, rotate+quant then W4A4 GEMM, T=2048 K=N=4096 (also: rotate+quant HBM GB/s, GEMM int TOPS)",
+        "value": head["layer_us"], "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["layer_us"] / 1e3, "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int4 codes on int8 MFMA, int32 accumulate; fp32 rotation",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: T={cfg.T} K={cfg.K} ({cfg.n1}x{cfg.n2}) N={cfg.N}, {cfg.P} Givens pairs",
+                   "ring_sets": head["ring_sets"]},
+        "rotate_quant_GBps": head["rotate_quant_GBps"], "gemm_int_TOPS": gemm_tops,
+        "rotate_quant_us": head["rotate_quant_us"], "gemm_us": head["gemm_us"],
+        "roofline": {"kernel": "w4a4_gemm_kernel", "bound": "mfma", "achieved": gemm_tops,
+                     "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": gemm_tops / INT8_MFMA_PEAK_TOPS,
+                     "traffic": None},
+        "roofline_rotate_quant": {"kernel": "rotate_quantize", "bound": "hbm", "achieved": head["rotate_quant_GBps"],
+                                  "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                  "frac": head["rotate_quant_GBps"] / HBM_PEAK_GBPS, "traffic": None},
+        "other_workloads": extra,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, synth)
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
