@@ -18,13 +18,13 @@ SOURCES = ["sq_rotate_quantize.hip", "sq_w4a4_gemm.hip", "sq_status.cpp"]
 # packed-fp32 VALU forms are switched off for every HIP translation unit of this library
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wno-unused-command-line-argument"]
+         "-Wno-unused-command-line-argument", "-Wno-inline-asm"]
 
 
 def build(verbose: bool = False, extra_flags=()) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, *FLAGS, *extra_flags, "-I", os.path.join(_ROOT, "include"), "-I", _CSRC,
-           "-o", _OUT] + ["-x" if False else s for s in []]
+           "-o", _OUT]
     for s in SOURCES:
         path = os.path.join(_CSRC, s)
         cmd += (["-x", "hip", path] if s.endswith(".cpp") else [path])

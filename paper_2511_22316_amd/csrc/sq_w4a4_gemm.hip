@@ -12,9 +12,11 @@
 // does not see.
 #include "sq_common.h"
 
+#include <stdlib.h>
+
 namespace sq {
 
-// LDS tile of one operand: ROWS rows of BKB bytes (2*BKB codes), stored as 16-byte chunks.
+// LDS tile of one operand: rows of BKB bytes (2*BKB codes), stored as 16-byte chunks.
 // Chunk c of row r sits at chunk slot r*CPR + (c ^ swz(r)): 8 consecutive rows then touch 8
 // different 16-byte bank groups both for the row-major writes and for the MFMA-fragment reads.
 template <int BKB>
@@ -33,17 +35,332 @@ __device__ __forceinline__ void widen_chunk(const uint4 w, v4i &first, v4i &seco
     second = v4i{(int)((w.z << 4) & m), (int)(w.z & m), (int)((w.w << 4) & m), (int)(w.w & m)};
 }
 
-// Block tile (WM*FM*32) x (WN*FN*32), WM*WN waves, each wave FM x FN fragments of 32x32.
-// K is walked in tiles of 2*BKB codes: global -> registers (prefetch of the next tile while the
-// current one is multiplied) -> LDS (still packed) -> registers -> widen -> MFMA.
-template <int WM, int WN, int FM, int FN, int BKB>
-__global__ __launch_bounds__(WM *WN *kWave) void w4a4_gemm_kernel(
+// 16 bytes per lane from global memory straight into LDS at lds_addr + lane * 16 (lds_addr is
+// wave-uniform).  Issued from inline assembly so that the compiler does not serialise later LDS
+// reads of *other* stages behind it; completion is tracked by hand with wait_vmcnt below.
+__device__ __forceinline__ void load_to_lds_16(const void *gptr, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(gptr), "s"(lds_addr)
+                 : "memory", "m0");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// s_barrier without the memory fence of __syncthreads (which would wait for every outstanding
+// global -> LDS load).  The wave's own LDS reads are drained first.
+__device__ __forceinline__ void block_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// The same load, issued only if a < b (both wave-uniform).  The branch lives inside the assembly
+// so that the surrounding loop body stays one basic block for the instruction scheduler.
+__device__ __forceinline__ void load_to_lds_16_if(const void *gptr, uint32_t lds_addr, int a, int b)
+{
+    asm volatile("s_cmp_lt_i32 %2, %3\n\t"
+                 "s_cbranch_scc0 .Lsq_skip_load_%=\n\t"
+                 "s_mov_b32 m0, %1\n\t"
+                 "s_nop 0\n\t"
+                 "global_load_lds_dwordx4 %0, off\n"
+                 ".Lsq_skip_load_%=:"
+                 :
+                 : "v"(gptr), "s"(lds_addr), "s"(a), "s"(b)
+                 : "memory", "m0", "scc");
+}
+
+// Wait until at most N global loads are outstanding if a < b, else until none is; then drain the
+// wave's LDS reads and meet the other waves at the barrier.  Branch inside the assembly as above.
+template <int N>
+__device__ __forceinline__ void wait_loads_and_barrier(int a, int b)
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    asm volatile("s_cmp_lt_i32 %0, %1\n\t"
+                 "s_cbranch_scc1 .Lsq_keep_%=\n\t"
+                 "s_waitcnt vmcnt(0)\n"
+                 ".Lsq_keep_%=:\n\t"
+                 "s_waitcnt vmcnt(%2) lgkmcnt(0)\n\t"
+                 "s_barrier"
+                 :
+                 : "s"(a), "s"(b), "n"(N)
+                 : "memory", "scc");
+}
+
+// XCD-contiguous ids, then groups of 8 row-tiles walked column by column: the tiles resident on
+// one XCD at a time share a few row panels and a few column panels in its L2.
+__device__ __forceinline__ void tile_of_workgroup(int tiles_m, int tiles_n, int &bm, int &bn)
+{
+    const int id = xcd_contiguous_id(blockIdx.x, tiles_m * tiles_n);
+    constexpr int GM = 8;
+    const int group = id / (GM * tiles_n);
+    const int gm = min(GM, tiles_m - group * GM);
+    const int in_group = id - group * GM * tiles_n;
+    bm = group * GM + in_group % gm;
+    bn = in_group / gm;
+}
+
+// Epilogue of one wave.  32x32 accumulator layout: lane holds column (lane % 32); register e
+// holds row 8 * (e / 4) + 4 * (lane / 32) + e % 4.
+template <int FM, int FN>
+__device__ __forceinline__ void store_tile(const v16i (&acc)[FM][FN], int row_base, int col_base,
+                                           int lane, const float *__restrict__ sx,
+                                           const float *__restrict__ sw, int T, int N,
+                                           __half *__restrict__ Y, int64_t ldy,
+                                           int32_t *__restrict__ acc_dbg)
+{
+    const int frow = lane & 31, fhalf = lane >> 5;
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+        const int n = col_base + j * 32 + frow;
+        if (n >= N) continue;
+        const float swn = sw[n];
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int t = row_base + i * 32 + 8 * (e / 4) + 4 * fhalf + (e % 4);
+                if (t >= T) continue;
+                const int a = acc[i][j][e] >> 8;
+                Y[(int64_t)t * ldy + n] = __float2half_rn((float)a * sx[t] * swn);
+                if (acc_dbg != nullptr) acc_dbg[(int64_t)t * N + n] = a;
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Main kernel (K % (2*BKB) == 0).  Block tile (WM*FM*32) x (WN*FN*32), WM x WN waves, each FM x FN
+// fragments of 32x32.  K is walked in tiles of 2*BKB codes (BKB bytes per row).  Tiles go from
+// global memory straight into LDS (global_load_lds, 16 bytes per lane, no register staging)
+// through a ring of three stages, two tiles ahead of the one being multiplied.  The epilogue
+// stages the fp16 tile in LDS and writes it out in full 16-byte, row-contiguous stores.
+// ------------------------------------------------------------------------------------------
+template <int WM, int WN, int FM, int FN, int BKB, int OCC>
+__global__ __launch_bounds__(WM *WN *kWave, OCC) void w4a4_gemm_kernel(
+    const uint8_t *__restrict__ Qx, const float *__restrict__ sx, int T, int Kb,
+    const uint8_t *__restrict__ Qw, const float *__restrict__ sw, int N, __half *__restrict__ Y,
+    int64_t ldy, int32_t *__restrict__ acc_dbg, int tiles_m, int tiles_n, int vec_store)
+{
+    constexpr int NS = 3;
+    constexpr int NW = WM * WN, NT = NW * kWave;
+    constexpr int CPR = BKB / 16;                 // 16-byte chunks per tile row
+    constexpr int STEPS = CPR / 2;                // steps of 64 codes per tile
+    constexpr int RPL = kWave / CPR;              // tile rows filled by one wave-wide load
+    constexpr int BM = WM * FM * 32, BN = WN * FN * 32;
+    constexpr int A_SLOTS = BM * CPR, B_SLOTS = BN * CPR, STAGE_SLOTS = A_SLOTS + B_SLOTS;
+    constexpr int A_LOADS = BM / RPL / NW, B_LOADS = BN / RPL / NW;   // loads per wave per tile
+    constexpr int LOADS = A_LOADS + B_LOADS;
+    static_assert((BM / RPL) % NW == 0 && (BN / RPL) % NW == 0, "loads must split evenly over waves");
+    static_assert(STEPS == 2 || STEPS == 4, "tile rows of 64 or 128 bytes");
+
+    extern __shared__ uint4 smem[];
+
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int wm = wave / WN, wn = wave % WN;
+    int bm, bn;
+    tile_of_workgroup(tiles_m, tiles_n, bm, bn);
+    const int row0 = bm * BM, col0 = bn * BN;
+
+    // Global -> LDS.  One wave-wide load fills 64 consecutive chunk slots = RPL rows x CPR chunks;
+    // lane l lands in slot base + l, i.e. row l/CPR, physical chunk l%CPR, which holds the logical
+    // chunk (l%CPR) ^ swizzle(row).  Wave w issues the loads for row groups w, w+NW, w+2NW, ...
+    const int lrow = lane / CPR;
+    const int lchunk = (lane % CPR) ^ (CPR == 8 ? (lrow & 7) : ((lrow >> 1) & 3));
+    const uint8_t *a_src[A_LOADS];
+    const uint8_t *b_src[B_LOADS];
+#pragma unroll
+    for (int g = 0; g < A_LOADS; ++g)   // rows past the end are clamped: their products are never stored
+        a_src[g] = Qx + (int64_t)min(row0 + RPL * (wave + NW * g) + lrow, T - 1) * Kb + lchunk * 16;
+#pragma unroll
+    for (int g = 0; g < B_LOADS; ++g)
+        b_src[g] = Qw + (int64_t)min(col0 + RPL * (wave + NW * g) + lrow, N - 1) * Kb + lchunk * 16;
+
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)smem;
+    const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
+    // loads of tile kt into ring stage `stage`, issued only if kt < limit
+    auto issue_tile = [&](int kt, int stage, int limit) {
+        const uint32_t sa = lds_base + (uint32_t)stage * (STAGE_SLOTS * 16) + wave_u * 1024;
+        const uint32_t sb = sa + A_SLOTS * 16;
+        const int kb0 = kt * BKB;
+#pragma unroll
+        for (int g = 0; g < A_LOADS; ++g) load_to_lds_16_if(a_src[g] + kb0, sa + g * NW * 1024, kt, limit);
+#pragma unroll
+        for (int g = 0; g < B_LOADS; ++g) load_to_lds_16_if(b_src[g] + kb0, sb + g * NW * 1024, kt, limit);
+    };
+
+    v16i acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
+
+    const int ktiles = Kb / BKB;
+    const int frow = lane & 31, fhalf = lane >> 5;
+
+    // LDS byte offsets of this lane's fragment chunks inside a stage, per step s (the step picks
+    // logical chunk 2s + fhalf; the swizzle depends on row % 8 = frow % 8 for every fragment).
+    constexpr int STAGE_BYTES = STAGE_SLOTS * 16, FRAG_BYTES = 32 * BKB;
+    int a_off[STEPS], b_off[STEPS];
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) {
+        a_off[s] = lds_chunk_slot<BKB>(wm * FM * 32 + frow, 2 * s + fhalf) * 16;
+        b_off[s] = A_SLOTS * 16 + lds_chunk_slot<BKB>(wn * FN * 32 + frow, 2 * s + fhalf) * 16;
+    }
+    const char *lds = reinterpret_cast<const char *>(smem);
+
+    // Software pipeline over the steps (one step = 64 codes of K = two MFMAs per fragment pair):
+    //   raw        chunks of step s+1, read from LDS during step s-1
+    //   frag[1-C]  widened operands of step s+1, made from raw during step s
+    //   frag[C]    widened operands of step s, fed to the MFMAs of step s
+    // so every step interleaves its MFMAs with the widening VALU work of the next step and the
+    // LDS reads of the step after that.
+    uint4 raw[FM + FN];
+    v4i frag[2][FM + FN][2];
+
+    auto read_step = [&](int stage_byte, int s) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+            raw[i] = *reinterpret_cast<const uint4 *>(lds + stage_byte + a_off[s] + i * FRAG_BYTES);
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+            raw[FM + j] = *reinterpret_cast<const uint4 *>(lds + stage_byte + b_off[s] + j * FRAG_BYTES);
+    };
+    // One step, written in the order it should issue: each MFMA on frag[C] is followed by the
+    // widening of a few dwords of raw into frag[1-C] (three VALU ops per dword), and a chunk of
+    // raw is refilled from (stage_byte, s_read) as soon as its last dword has been widened.
+    // The scheduling barriers keep the compiler from regrouping the units.
+    constexpr int NMFMA = 2 * FM * FN, NDW = 4 * (FM + FN);
+#define SQ_GEMM_STEP(C, stage_byte, s_read)                                                          \
+    do {                                                                                             \
+        _Pragma("unroll") for (int m = 0; m < NMFMA; ++m) {                                          \
+            const int u = m / (FM * FN), i = (m / FN) % FM, j = m % FN;                              \
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(frag[C][i][u], frag[C][FM + j][u],     \
+                                                              acc[i][j], 0, 0, 0);                   \
+            _Pragma("unroll") for (int d = m * NDW / NMFMA; d < (m + 1) * NDW / NMFMA; ++d) {        \
+                const int c = d >> 2, w = d & 3;                                                     \
+                const uint32_t x = (w == 0) ? raw[c].x : (w == 1) ? raw[c].y : (w == 2) ? raw[c].z : raw[c].w; \
+                frag[1 - (C)][c][w >> 1][2 * (w & 1)] = (int)((x << 4) & 0xF0F0F0F0u);               \
+                frag[1 - (C)][c][w >> 1][2 * (w & 1) + 1] = (int)(x & 0xF0F0F0F0u);                  \
+                if (w == 3) {                                                                        \
+                    const int off = (c < FM) ? a_off[s_read] + c * FRAG_BYTES                        \
+                                             : b_off[s_read] + (c - FM) * FRAG_BYTES;                \
+                    raw[c] = *reinterpret_cast<const uint4 *>(lds + (stage_byte) + off);             \
+                }                                                                                    \
+            }                                                                                        \
+            __builtin_amdgcn_sched_barrier(0);                                                       \
+        }                                                                                            \
+    } while (0)
+    // Between two tiles.  Loads complete in order, so tile kt+1 has landed once only the loads of
+    // tile kt+2 (if it exists) are outstanding.  After the barrier every wave's share of tile kt+1
+    // is in LDS and nobody reads tile kt any more (all its reads were issued, and the barrier
+    // drains them), so its stage can take tile kt+3.
+#define SQ_GEMM_TURN()                                                                               \
+    do {                                                                                             \
+        wait_loads_and_barrier<LOADS>(kt + 2, ktiles);                                               \
+        issue_tile(kt + 3, st_cur, ktiles);                                                          \
+    } while (0)
+
+    // prologue: tiles 0 and 1 in flight, wait for tile 0, start tile 2, first fragments ready
+    issue_tile(0, 0, ktiles);
+    issue_tile(1, 1, ktiles);
+    wait_loads_and_barrier<LOADS>(1, ktiles);
+    issue_tile(2, 2, ktiles);
+    read_step(0, 0);
+#pragma unroll
+    for (int c = 0; c < FM + FN; ++c) widen_chunk(raw[c], frag[0][c][0], frag[0][c][1]);
+    read_step(0, 1);
+
+    int st_cur = 0;                 // ring stage of tile kt
+    for (int kt = 0; kt < ktiles; ++kt) {
+        const int st_next = (st_cur + 1 == NS) ? 0 : st_cur + 1;
+        const int cur_byte = st_cur * STAGE_BYTES, next_byte = st_next * STAGE_BYTES;
+        // the LDS reads run two steps ahead of the MFMAs, so the last two steps of a tile already
+        // read the next tile (for the very last tile they read a stale stage; never used)
+        if constexpr (STEPS == 4) {
+            SQ_GEMM_STEP(0, cur_byte, 2);
+            SQ_GEMM_STEP(1, cur_byte, 3);
+            SQ_GEMM_TURN();
+            SQ_GEMM_STEP(0, next_byte, 0);
+            SQ_GEMM_STEP(1, next_byte, 1);
+        } else {
+            SQ_GEMM_TURN();
+            SQ_GEMM_STEP(0, next_byte, 0);
+            SQ_GEMM_STEP(1, next_byte, 1);
+        }
+        st_cur = st_next;
+    }
+#undef SQ_GEMM_STEP
+#undef SQ_GEMM_TURN
+
+    // ---- epilogue ------------------------------------------------------------------------
+    // 32x32 accumulator layout: lane holds column (lane % 32); register e holds row
+    // 8 * (e / 4) + 4 * (lane / 32) + e % 4.  The accumulators carry a factor 256, which is a
+    // power of two and is folded into the token step.
+    constexpr int YS = BN * 2 + 16;      // LDS row stride of the staged fp16 tile, bytes
+    static_assert(BM * YS <= kMaxDynamicLds, "staged output tile must fit in LDS");
+    wait_vmcnt<0>();
+    block_barrier();                     // the ring is dead: reuse it for the output tile
+    char *ys = reinterpret_cast<char *>(smem);
+    float swn[FN];
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+        const int n = col0 + (wn * FN + j) * 32 + frow;
+        swn[j] = (n < N) ? sw[n] : 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int tl = (wm * FM + i) * 32 + 8 * (e / 4) + 4 * fhalf + (e % 4);
+            const int t = row0 + tl;
+            const float sxt = (t < T) ? sx[t] * 0.00390625f : 0.f;
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const int nl = (wn * FN + j) * 32 + frow;
+                *reinterpret_cast<__half *>(ys + tl * YS + nl * 2) =
+                    __float2half_rn((float)acc[i][j][e] * sxt * swn[j]);
+                if (acc_dbg != nullptr && t < T && col0 + nl < N)
+                    acc_dbg[(int64_t)t * N + col0 + nl] = acc[i][j][e] >> 8;
+            }
+        }
+    }
+    __syncthreads();
+    constexpr int CPRY = BN / 8;         // 16-byte chunks per output row
+    for (int idx = tid; idx < BM * CPRY; idx += NT) {
+        const int tl = idx / CPRY, ch = idx % CPRY;
+        const int t = row0 + tl, n0 = col0 + ch * 8;
+        if (t >= T || n0 >= N) continue;
+        const uint4 v = *reinterpret_cast<const uint4 *>(ys + tl * YS + ch * 16);
+        __half *dst = Y + (int64_t)t * ldy + n0;
+        if (vec_store && n0 + 8 <= N) {
+            *reinterpret_cast<uint4 *>(dst) = v;
+        } else {
+            const __half *h = reinterpret_cast<const __half *>(&v);
+            for (int u = 0; u < 8 && n0 + u < N; ++u) dst[u] = h[u];
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Generic kernel: any K % 32 == 0 (zero-fills the last partial K tile).  Tiles are staged through
+// registers; used only for shapes the main kernel does not take.
+// ------------------------------------------------------------------------------------------
+template <int FM, int FN, int BKB>
+__global__ __launch_bounds__(256) void w4a4_gemm_generic_kernel(
     const uint8_t *__restrict__ Qx, const float *__restrict__ sx, int T, int Kb,
     const uint8_t *__restrict__ Qw, const float *__restrict__ sw, int N, __half *__restrict__ Y,
     int64_t ldy, int32_t *__restrict__ acc_dbg, int tiles_m, int tiles_n)
 {
-    constexpr int NT = WM * WN * kWave;
-    constexpr int BM = WM * FM * 32, BN = WN * FN * 32;
+    constexpr int NT = 256;
+    constexpr int BM = 64 * FM, BN = 64 * FN;
     constexpr int CPR = BKB / 16;
     constexpr int A_CHUNKS = BM * CPR, B_CHUNKS = BN * CPR;
     constexpr int A_PER = A_CHUNKS / NT, B_PER = B_CHUNKS / NT;
@@ -53,20 +370,11 @@ __global__ __launch_bounds__(WM *WN *kWave) void w4a4_gemm_kernel(
     __shared__ uint4 sB[B_CHUNKS];
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    const int wm = wave / WN, wn = wave % WN;
-
-    // XCD-contiguous ids, then groups of 8 row-tiles walked column by column: the 32 tiles that
-    // are resident on one XCD share a few row panels and a few column panels in its L2.
-    const int id = xcd_contiguous_id(blockIdx.x, tiles_m * tiles_n);
-    constexpr int GM = 8;
-    const int group = id / (GM * tiles_n);
-    const int gm = min(GM, tiles_m - group * GM);
-    const int in_group = id - group * GM * tiles_n;
-    const int bm = group * GM + in_group % gm, bn = in_group / gm;
-
+    const int wm = wave >> 1, wn = wave & 1;
+    int bm, bn;
+    tile_of_workgroup(tiles_m, tiles_n, bm, bn);
     const int row0 = bm * BM, col0 = bn * BN;
 
-    // global-load assignment: chunk g*NT + tid of the tile -> (row, chunk-in-row)
     const uint8_t *a_src[A_PER];
     const uint8_t *b_src[B_PER];
     int a_slot[A_PER], b_slot[B_PER], a_off[A_PER], b_off[B_PER];
@@ -136,37 +444,35 @@ __global__ __launch_bounds__(WM *WN *kWave) void w4a4_gemm_kernel(
         }
     }
 
-    // epilogue.  32x32 accumulator layout: lane holds column (lane % 32); register e holds row
-    // 8 * (e / 4) + 4 * (lane / 32) + e % 4.
-#pragma unroll
-    for (int j = 0; j < FN; ++j) {
-        const int n = col0 + (wn * FN + j) * 32 + frow;
-        if (n >= N) continue;
-        const float swn = sw[n];
-#pragma unroll
-        for (int i = 0; i < FM; ++i) {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int t = row0 + (wm * FM + i) * 32 + 8 * (e / 4) + 4 * fhalf + (e % 4);
-                if (t >= T) continue;
-                const int a = acc[i][j][e] >> 8;
-                Y[(int64_t)t * ldy + n] = __float2half_rn((float)a * sx[t] * swn);
-                if (acc_dbg != nullptr) acc_dbg[(int64_t)t * N + n] = a;
-            }
-        }
-    }
+    store_tile<FM, FN>(acc, row0 + wm * FM * 32, col0 + wn * FN * 32, lane, sx, sw, T, N, Y, ldy, acc_dbg);
 }
 
-template <int WM, int WN, int FM, int FN, int BKB>
-static sq_status launch_gemm(const uint8_t *Qx, const float *sx, int T, int K, const uint8_t *Qw,
+template <int WM, int WN, int FM, int FN, int BKB, int OCC>
+static sq_status launch_main(const uint8_t *Qx, const float *sx, int T, int K, const uint8_t *Qw,
                              const float *sw, int N, __half *Y, int64_t ldy, int32_t *acc_dbg,
                              hipStream_t st)
 {
     constexpr int BM = WM * FM * 32, BN = WN * FN * 32;
+    constexpr size_t ring = (size_t)3 * (BM + BN) * BKB, out_tile = (size_t)BM * (BN * 2 + 16);
+    constexpr size_t lds = ring > out_tile ? ring : out_tile;   // the epilogue reuses the ring
+    static_assert(lds <= (size_t)kMaxDynamicLds, "ring does not fit in LDS");
+    auto kernel = w4a4_gemm_kernel<WM, WN, FM, FN, BKB, OCC>;
+    if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return SQ_ERR_LAUNCH;
     const int tiles_m = (T + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    hipLaunchKernelGGL((w4a4_gemm_kernel<WM, WN, FM, FN, BKB>), dim3((unsigned)(tiles_m * tiles_n)),
-                       dim3(WM * WN * kWave), 0, st, Qx, sx, T, K / 2, Qw, sw, N, Y, ldy, acc_dbg,
-                       tiles_m, tiles_n);
+    const int vec_store = (((uintptr_t)Y & 15) == 0 && (ldy % 8) == 0) ? 1 : 0;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3(WM * WN * kWave), lds, st, Qx,
+                       sx, T, K / 2, Qw, sw, N, Y, ldy, acc_dbg, tiles_m, tiles_n, vec_store);
+    return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+static sq_status launch_generic(const uint8_t *Qx, const float *sx, int T, int K, const uint8_t *Qw,
+                                const float *sw, int N, __half *Y, int64_t ldy, int32_t *acc_dbg,
+                                hipStream_t st)
+{
+    constexpr int FM = 2, FN = 2, BM = 64 * FM, BN = 64 * FN;
+    const int tiles_m = (T + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    hipLaunchKernelGGL((w4a4_gemm_generic_kernel<FM, FN, 64>), dim3((unsigned)(tiles_m * tiles_n)),
+                       dim3(256), 0, st, Qx, sx, T, K / 2, Qw, sw, N, Y, ldy, acc_dbg, tiles_m, tiles_n);
     return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
@@ -184,6 +490,23 @@ extern "C" sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T,
         ((uintptr_t)sx & 3) || ((uintptr_t)sw & 3) || ((uintptr_t)acc_dbg & 3))
         return SQ_ERR_ALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    return sq::launch_gemm<2, 2, 2, 4, 128>(Qx, sx, (int)T, K, Qw, sw, N, static_cast<__half *>(Y),
-                                            ldy, acc_dbg, st);
+    __half *Yh = static_cast<__half *>(Y);
+    if ((K % 256) != 0) return sq::launch_generic(Qx, sx, (int)T, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
+    // Tile choice.  Both variants run eight waves per CU (two per SIMD): the VALU work of widening
+    // nibbles issues nearly twice as fast from two waves as from one.  Large problems take 256x256
+    // tiles (64x128 per wave: fewer VALU ops per MFMA); smaller ones take 128x256 tiles so that
+    // every CU gets work.  SQ_GEMM_TILE=0..6 overrides the choice (tuning aid).
+    static const int forced = [] { const char *e = getenv("SQ_GEMM_TILE"); return e ? atoi(e) : -1; }();
+    const int Ti = (int)T;
+    int choice = forced;
+    if (choice < 0) choice = ((int64_t)((Ti + 255) / 256) * ((N + 255) / 256) >= 512) ? 4 : 1;
+    switch (choice) {
+        case 0: return sq::launch_main<2, 2, 2, 4, 128, 1>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
+        case 2: return sq::launch_main<2, 2, 2, 2, 64, 2>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
+        case 3: return sq::launch_main<2, 2, 4, 4, 64, 1>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
+        case 4: return sq::launch_main<4, 2, 2, 4, 64, 1>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
+        case 5: return sq::launch_main<2, 2, 2, 2, 128, 1>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
+        case 6: return sq::launch_main<2, 4, 2, 2, 64, 1>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
+        default: return sq::launch_main<2, 4, 2, 2, 128, 1>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
+    }
 }
