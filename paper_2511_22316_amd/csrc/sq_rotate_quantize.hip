@@ -1,8 +1,11 @@
 // sq_rotate_quantize: online rotation (Givens list, then Kronecker product, Sec. 4.1-4.2, Eq. 18)
 // fused with the per-token 4-bit rounding quantizer of Sec. 3.2.  gfx950 only.
 #include "sq_common.h"
+#include "sq_rotq_plan.h"
 
 #include <math.h>
+#include <stdlib.h>
+#include <string.h>
 
 namespace sq {
 
@@ -109,6 +112,57 @@ __global__ __launch_bounds__(kGenThreads) void rotate_quantize_generic_kernel(
     }
 }
 
+// Regroup the Givens list into levels of mutually disjoint pairs (see RotqPlan).  Returns false
+// if the list touches more distinct values of channel % n2 than the matrix-core kernel repairs.
+static bool build_rotq_plan(const GivensList &giv, int n2, RotqPlan &plan)
+{
+    memset(&plan, 0, sizeof(plan));
+    int slot_level[kRotqMaxSlots];
+    int pair_level[SQ_MAX_GIVENS], pair_si[SQ_MAX_GIVENS], pair_sj[SQ_MAX_GIVENS];
+    auto slot_of = [&](int ch) {
+        for (int s = 0; s < plan.n_slots; ++s)
+            if (plan.chan[s] == ch) return s;
+        const int s = plan.n_slots++;
+        plan.chan[s] = (uint16_t)ch;
+        slot_level[s] = 0;
+        const int q = ch % n2;
+        int qs = 0;
+        while (qs < plan.n_qslots && plan.qlist[qs] != q) ++qs;
+        if (qs == plan.n_qslots) {
+            if (plan.n_qslots == kRotqMaxQSlots) return -1;
+            plan.qlist[plan.n_qslots++] = (uint16_t)q;
+        }
+        plan.qslot[s] = (uint8_t)qs;
+        return s;
+    };
+    int levels = 0;
+    for (int p = 0; p < giv.count; ++p) {
+        const int si = slot_of(giv.i[p]), sj = slot_of(giv.j[p]);
+        if (si < 0 || sj < 0) return false;
+        const int lv = 1 + (slot_level[si] > slot_level[sj] ? slot_level[si] : slot_level[sj]);
+        slot_level[si] = slot_level[sj] = lv;
+        pair_level[p] = lv - 1;
+        pair_si[p] = si;
+        pair_sj[p] = sj;
+        if (lv > levels) levels = lv;
+    }
+    plan.n_levels = levels;
+    int pos = 0;
+    for (int lv = 0; lv < levels; ++lv) {          // stable: list order is kept inside a level
+        plan.level_begin[lv] = (uint8_t)pos;
+        for (int p = 0; p < giv.count; ++p)
+            if (pair_level[p] == lv) {
+                plan.pair_i[pos] = (uint8_t)pair_si[p];
+                plan.pair_j[pos] = (uint8_t)pair_sj[p];
+                plan.c[pos] = giv.c[p];
+                plan.s[pos] = giv.s[p];
+                ++pos;
+            }
+    }
+    plan.level_begin[levels] = (uint8_t)pos;
+    return true;
+}
+
 }  // namespace sq
 
 extern "C" sq_status sq_rotate_quantize(const void *X, int64_t T, int32_t K, int64_t ldx,
@@ -140,6 +194,17 @@ extern "C" sq_status sq_rotate_quantize(const void *X, int64_t T, int32_t K, int
     if (T == 0) return SQ_OK;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
+    // matrix-core kernel for the shapes it covers (n2 in {32, 64, 128}, n1 <= 96); the plain-FMA
+    // kernel takes every other shape.  SQ_ROTQ_GENERIC=1 forces the latter (tuning aid).
+    static const bool force_generic = [] { const char *e = getenv("SQ_ROTQ_GENERIC"); return e && e[0] == '1'; }();
+    sq::RotqPlan plan;
+    if (!force_generic && sq::build_rotq_plan(giv, n2, plan)) {
+        sq_status status = SQ_OK;
+        if (sq::rotq_mfma_dispatch(static_cast<const __half *>(X), ldx, (int)T, n1, n2, plan,
+                                   static_cast<const __half *>(R1), static_cast<const __half *>(R2), Q,
+                                   scales, xrot_dbg, st, &status))
+            return status;
+    }
     const size_t lds = sizeof(float) * 2 * (size_t)K;
     if (!sq::allow_large_lds(reinterpret_cast<const void *>(sq::rotate_quantize_generic_kernel)))
         return SQ_ERR_LAUNCH;

@@ -1,0 +1,44 @@
+// Launch-time plan for the Givens list (ART pairs, Sec. 4.1-4.2) of sq_rotate_quantize: it travels
+// by value in the kernel-argument block.
+#pragma once
+
+#include <stdint.h>
+
+#include "singlequant.h"
+
+namespace sq {
+
+constexpr int kRotqMaxSlots = 2 * SQ_MAX_GIVENS;   // distinct channels a list can touch
+constexpr int kRotqMaxQSlots = 64;                 // distinct q = channel % n2 the MFMA kernel repairs
+
+// The list is regrouped into levels: a pair goes one level after the latest earlier pair that
+// shares a channel with it.  Pairs of one level touch disjoint channels, and every dependency
+// points to an earlier level, so applying level after level equals applying the list in order.
+struct RotqPlan {
+    int32_t n_slots;                          // touched channels
+    int32_t n_levels;
+    int32_t n_qslots;                         // distinct values of channel % n2 among them
+    uint16_t chan[kRotqMaxSlots];             // slot -> channel
+    uint8_t qslot[kRotqMaxSlots];             // slot -> index into qlist
+    uint16_t qlist[kRotqMaxQSlots];           // q-slot -> q
+    uint8_t level_begin[SQ_MAX_GIVENS + 1];   // pairs [level_begin[l], level_begin[l+1]) form level l
+    uint8_t pair_i[SQ_MAX_GIVENS];            // slots of the pair, in level order
+    uint8_t pair_j[SQ_MAX_GIVENS];
+    float c[SQ_MAX_GIVENS];                   // cos, sin of the pair's angle
+    float s[SQ_MAX_GIVENS];
+};
+
+}  // namespace sq
+
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+
+namespace sq {
+
+// Matrix-core kernel (sq_rotq_mfma.hip).  Returns false if it does not cover (n1, n2); otherwise
+// launches on `st` and stores the launch status.
+bool rotq_mfma_dispatch(const __half *X, int64_t ldx, int T, int n1, int n2, const RotqPlan &plan,
+                        const __half *R1, const __half *R2, uint8_t *Q, float *scales, float *xrot,
+                        hipStream_t st, sq_status *status);
+
+}  // namespace sq
