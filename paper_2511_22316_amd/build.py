@@ -18,7 +18,7 @@ SOURCES = ["sq_rotate_quantize.hip", "sq_rotq_mfma.hip", "sq_w4a4_gemm.hip", "sq
 # packed-fp32 VALU forms are switched off for every HIP translation unit of this library
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wno-unused-command-line-argument", "-Wno-inline-asm"]
+         "-Wno-unused-command-line-argument", "-Wno-inline-asm", "-fno-honor-nans"]
 
 
 def build(verbose: bool = False, extra_flags=()) -> str:

@@ -39,11 +39,21 @@ __device__ __forceinline__ int xcd_contiguous_id(int wg, int nwg)
     return xcd * q + (xcd < r ? xcd : r) + local;
 }
 
+// Maximum of a non-negative value over the 64 lanes, returned in every lane.  Cross-lane steps
+// use DPP modifiers (register-file speed) rather than LDS permutes.
 __device__ __forceinline__ float wave_max(float v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
-    return v;
+#define SQ_DPP_MAX(ctrl, row_mask)                                                                   \
+    v = fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(                              \
+                     0, __builtin_bit_cast(int, v), ctrl, row_mask, 0xF, false)))
+    SQ_DPP_MAX(0xB1, 0xF);     // quad_perm [1,0,3,2]
+    SQ_DPP_MAX(0x4E, 0xF);     // quad_perm [2,3,0,1]
+    SQ_DPP_MAX(0x141, 0xF);    // row_half_mirror
+    SQ_DPP_MAX(0x140, 0xF);    // row_mirror: every lane holds the maximum of its row of 16
+    SQ_DPP_MAX(0x142, 0xA);    // row_bcast:15 into rows 1 and 3
+    SQ_DPP_MAX(0x143, 0xC);    // row_bcast:31 into rows 2 and 3: lane 63 holds the wave maximum
+#undef SQ_DPP_MAX
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
 // gfx950 has 160 KiB of LDS per workgroup; HIP needs an opt-in above 64 KiB of dynamic LDS.
