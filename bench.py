@@ -29,6 +29,14 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 INT8_MFMA_PEAK_TOPS = 5000.0    # MI355X dense int8 matrix peak
 RING_BYTES = 640 << 20          # > 2x the 256 MB Infinity Cache
 
+# HBM-side bytes per launch on the headline workload, from the rocprofv3 --pmc runs summarised in
+# profiles/w4a4_gemm_attn_proj.md and profiles/rotate_quantize_attn_proj.md (FETCH_SIZE and
+# WRITE_SIZE, each scaled by what the counter reads for a plain 256 MiB copy: x2.000 and x1.000).
+PROFILED_TRAFFIC = {
+    "attn_proj": {"gemm": {"fetch": 33824437, "write": 18903424},
+                  "rotate_quantize": {"fetch": 17166657, "write": 4227072}},
+}
+
 
 def rq_bytes(T: int, K: int) -> float:
     """Algorithmic HBM bytes of rotate+quantize: fp16 row in, nibble codes and one fp32 step out."""
@@ -153,6 +161,9 @@ def main() -> int:
     ap.add_argument("--workload", default="attn_proj", help="layer shape for the headline number")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the other layer shapes")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="first run three plain 256 MiB device copies (known traffic: the scale for "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)",
@@ -171,6 +182,13 @@ def main() -> int:
         build.build()
 
     cfg = synth.CONFIGS[args.workload]
+    if args.copy_calibration:
+        src = torch.ones((256 << 20) // 2, dtype=torch.float16, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     head = measure_layer(cfg, torch, sq, synth, args.steps, args.warmup)
     extra = {}
     if not args.no_extra:
@@ -180,6 +198,8 @@ def main() -> int:
                 extra[name] = measure_layer(synth.CONFIGS[name], torch, sq, synth, st, max(2, args.warmup // 4))
 
     gemm_tops = head["gemm_int_TOPS"]
+    prof = PROFILED_TRAFFIC.get(cfg.name, {})
+    traffic = lambda k: (prof[k]["fetch"] + prof[k]["write"]) if k in prof else None
     result = {
         "metric": "layer time, rotate+quant then W4A4 GEMM, T=2048 K=N=4096 (also: rotate+quant HBM GB/s, GEMM int TOPS)",
         "value": head["layer_us"], "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -192,10 +212,14 @@ def main() -> int:
         "rotate_quant_us": head["rotate_quant_us"], "gemm_us": head["gemm_us"],
         "roofline": {"kernel": "w4a4_gemm_kernel", "bound": "mfma", "achieved": gemm_tops,
                      "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": gemm_tops / INT8_MFMA_PEAK_TOPS,
-                     "traffic": None},
+                     "ops_per_launch": gemm_ops(cfg.T, cfg.K, cfg.N), "traffic": traffic("gemm"),
+                     "traffic_detail": prof.get("gemm")},
         "roofline_rotate_quant": {"kernel": "rotate_quantize", "bound": "hbm", "achieved": head["rotate_quant_GBps"],
                                   "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                                  "frac": head["rotate_quant_GBps"] / HBM_PEAK_GBPS, "traffic": None},
+                                  "frac": head["rotate_quant_GBps"] / HBM_PEAK_GBPS,
+                                  "bytes_per_launch": rq_bytes(cfg.T, cfg.K),
+                                  "traffic": traffic("rotate_quantize"),
+                                  "traffic_detail": prof.get("rotate_quantize")},
         "other_workloads": extra,
     }
     if not args.no_cpu_baseline:
