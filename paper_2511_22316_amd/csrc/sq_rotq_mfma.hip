@@ -13,14 +13,16 @@
 //
 // Token rows stream from HBM straight into a ring of three LDS tiles (global_load_lds), two rows
 // ahead of the one being multiplied; two workgroups share a CU, so four rows per CU are in flight.
+// The loop is rotated so that the MFMAs of stage A of the NEXT token are issued between the VALU
+// instructions that quantize the current one, and the hi/lo split of the next stage-B step
+// between the MFMAs of the current step.
 //
 // Givens list (ART): the touched channels (at most 2P) are rotated in fp32 on a small LDS array,
 // level by level (pairs of one level share no channel, so lanes work in parallel while the list
 // order is kept).  A rotated value v goes back as hi = fp16(v) into the token tile and
 // lo = fp16(v - hi) into a small side tile; stage A contracts the side tile against the matching
 // rows of R2 in a few extra MFMA steps, so the fp16 rounding of hi is repaired to ~21 bits.
-// The first wave of a token does this for the NEXT token while the other waves finish the
-// current one.
+// The first wave of a token does this for the next token.
 #include "sq_common.h"
 #include "sq_rotq_plan.h"
 
@@ -64,6 +66,13 @@ __device__ __forceinline__ void split_pair(float z0, float z1, uint32_t &hi, uin
     lo = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(r0, r1));
 }
 
+__device__ __forceinline__ float max_abs16(const v16f &a, float m)
+{
+#pragma unroll
+    for (int e = 0; e < 16; e += 2) m = fmaxf(m, fmaxf(fabsf(a[e]), fabsf(a[e + 1])));
+    return m;
+}
+
 }  // namespace
 
 template <int N1, int N2>
@@ -79,30 +88,21 @@ struct RotqShape {
     static constexpr int LPT = (ROW_CHUNKS + 63) / 64;    // wave-wide loads per token row
     static constexpr int NSX = 3;                 // ring of token tiles
     static constexpr int TILE_BYTES = N1P * N2 * 2;
-    static constexpr int LO_ROW_BYTES = kRotqMaxQSlots * 2;           // 64 q-slots of fp16
-    static constexpr int LO_BYTES = N1P * LO_ROW_BYTES;
+    static constexpr int LO_STEP_BYTES = N1P * 32;        // side tile: [step][row p][16 fp16]
     static constexpr int OUT_UNITS = N2 / 4;      // 2-byte units (4 codes) per output row p'
     static constexpr int OUT_BYTES = OUT_UNITS * N1P * 2;             // staged as [unit][p']
-    // LDS map (bytes)
     static constexpr int OFF_X = 0;                                   // [TPP][NSX][TILE]
-    static constexpr int OFF_LO = OFF_X + TPP * NSX * TILE_BYTES;     // [TPP][2][LO]
-    static constexpr int OFF_ZERO_END = OFF_LO + TPP * 2 * LO_BYTES;
-    static constexpr int OFF_GV = OFF_ZERO_END;                       // [TPP][128] float
-    static constexpr int OFF_RED = OFF_GV + TPP * kRotqMaxSlots * 4;  // [TPP][4] float
-    static constexpr int OFF_OUT = OFF_RED + TPP * 4 * 4;             // [TPP][OUT]
-    static constexpr int WORK_BYTES = OFF_OUT + TPP * OUT_BYTES;
-    // the prologue stages R2 and then R1 at the start of LDS
-    static constexpr int PRO_BYTES = (N2 * N2 > N1 * N1 ? N2 * N2 : N1 * N1) * 2;
-    static constexpr int LDS_BYTES = WORK_BYTES > PRO_BYTES ? WORK_BYTES : PRO_BYTES;
-    static constexpr int OCC = (2 * LDS_BYTES <= 158 * 1024) ? 2 : 1;   // workgroups per CU
+    static constexpr int OFF_LO = TPP * NSX * TILE_BYTES;             // [TPP][2][qsteps][LO_STEP]
+    // after the side tiles (runtime size): [TPP][128] float, [TPP][4] float, [TPP][OUT]
+    static constexpr int TAIL_BYTES = TPP * (kRotqMaxSlots * 4 + 16 + OUT_BYTES);
+    static constexpr int lds_bytes(int qsteps) { return OFF_LO + TPP * 2 * qsteps * LO_STEP_BYTES + TAIL_BYTES; }
     static_assert(N2 == 32 || N2 == 64 || N2 == 128, "one to four waves per token");
     static_assert(N1P <= 96, "at most three row blocks");
     static_assert(2 * LPT < 64, "outstanding loads must fit the vmcnt counter");
-    static_assert(PRO_BYTES <= OFF_ZERO_END, "prologue staging lies inside the tile ring");
 };
 
-template <int N1, int N2>
-__global__ __launch_bounds__(256, (RotqShape<N1, N2>::OCC)) void rotate_quantize_mfma_kernel(
+template <int N1, int N2, int OCC>
+__global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
     const __half *__restrict__ X, int64_t ldx, int T, RotqPlan plan,
     const __half *__restrict__ R1, const __half *__restrict__ R2, uint8_t *__restrict__ Q,
     float *__restrict__ scales, float *__restrict__ xrot)
@@ -110,7 +110,7 @@ __global__ __launch_bounds__(256, (RotqShape<N1, N2>::OCC)) void rotate_quantize
     using S = RotqShape<N1, N2>;
     constexpr int N1P = S::N1P, MB = S::MB, NCB = S::NCB, TPP = S::TPP, KSA = S::KSA, KSB = S::KSB;
     constexpr int CPRX = S::CPRX, LPT = S::LPT, NSX = S::NSX, K = N1 * N2;
-    constexpr int QS_STEPS = kRotqMaxQSlots / 16;
+    constexpr int QS_MAX = kRotqMaxQSlots / 16;
     extern __shared__ uint4 smem_u4[];
     char *lds = reinterpret_cast<char *>(smem_u4);
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)smem_u4;
@@ -120,33 +120,70 @@ __global__ __launch_bounds__(256, (RotqShape<N1, N2>::OCC)) void rotate_quantize
     const int l32 = lane & 31, g = lane >> 5;
     const bool lead = (cb == 0);                             // this wave loads and Givens-rotates its token
 
-    // ---- prologue: R2 and R1 as MFMA operands in registers ---------------------------------
+    const int qsteps = (plan.n_qslots + 15) / 16;            // extra MFMA steps that repair the Givens rounding
+    const int lo_bytes = qsteps * S::LO_STEP_BYTES;          // one side tile
+    const int off_gv = S::OFF_LO + TPP * 2 * lo_bytes;
+    const int off_red = off_gv + TPP * kRotqMaxSlots * 4;
+    const int off_out = off_red + TPP * 16;
+
+    const int groups = (T + TPP - 1) / TPP;
+    const int stride = gridDim.x;
+    const int g0 = blockIdx.x;
+    // does this wave's token exist in group grp (the last group may be partial)?
+    auto has_row = [&](int grp) { return (int64_t)grp * TPP + tok_slot < T; };
+    // lead wave: all loads of its token row of group `grp` into ring slot `slot`
+    auto issue_row = [&](int grp, int slot) {
+        if (has_row(grp)) {
+            const __half *row = X + ((int64_t)grp * TPP + tok_slot) * ldx;
+            const uint32_t dst0 = lds_base + S::OFF_X + (tok_slot * NSX + slot) * S::TILE_BYTES;
+#pragma unroll
+            for (int part = 0; part < LPT; ++part) {
+                const int c = part * 64 + lane;
+                if (c < S::ROW_CHUNKS) {
+                    const int r = c / CPRX, pc = c % CPRX;
+                    dma_16(row + r * N2 + ((pc ^ swz<CPRX>(r)) * 8),
+                           __builtin_amdgcn_readfirstlane(dst0 + part * 1024));
+                }
+            }
+        }
+    };
+
+    // ---- prologue -------------------------------------------------------------------------
+    // the first three rows leave for LDS before anything else, so their latency hides the rest
+    if (lead) {
+        issue_row(g0, 0);
+        issue_row(g0 + stride, 1);
+        issue_row(g0 + 2 * stride, 2);
+    }
+    // zeros where nothing is ever loaded: padding rows p >= N1 of every ring tile, and the side tiles
+    if (N1P > N1) {
+        constexpr int PAD_CHUNKS = (N1P - N1) * CPRX;
+        for (int c = tid; c < TPP * NSX * PAD_CHUNKS; c += 256) {
+            const int tile = c / PAD_CHUNKS, r = c % PAD_CHUNKS;
+            *reinterpret_cast<uint4 *>(lds + S::OFF_X + tile * S::TILE_BYTES + (N1 * CPRX + r) * 16) = uint4{0, 0, 0, 0};
+        }
+    }
+    for (int c = tid; c < TPP * 2 * lo_bytes / 16; c += 256)
+        *reinterpret_cast<uint4 *>(lds + S::OFF_LO + c * 16) = uint4{0, 0, 0, 0};
+
     // R2 (stage A, operand B): lane holds column q' = 32cb + l32, step ks, element e <-> row
-    // q = 16ks + 8g + e.  Staged through LDS so that the global reads are coalesced.
-    v8h r2f[KSA], r2x[QS_STEPS], r1f[MB][KSB];
+    // q = 16ks + 8g + e.  R1 (stage B, operand B): lane holds column p' = 32nb + l32; step ks,
+    // element e <-> row p = 16ks + 8(e/4) + 4g + e%4, which is where stage A leaves row p of Z in
+    // this lane.  Read straight from global memory (L2-resident after the first workgroup).
+    v8h r2f[KSA], r2x[QS_MAX], r1f[MB][KSB];
     {
-        __half *tmp = reinterpret_cast<__half *>(lds);
-        for (int c = tid; c < N2 * N2 / 8; c += 256)
-            reinterpret_cast<uint4 *>(tmp)[c] = reinterpret_cast<const uint4 *>(R2)[c];
-        __syncthreads();
         const int qo = 32 * cb + l32;
 #pragma unroll
         for (int ks = 0; ks < KSA; ++ks)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) r2f[ks][e] = (_Float16)tmp[(16 * ks + 8 * g + e) * N2 + qo];
-        // rows of R2 that pair with the q-slots of the Givens side tile
+            for (int e = 0; e < 8; ++e) r2f[ks][e] = (_Float16)R2[(16 * ks + 8 * g + e) * N2 + qo];
 #pragma unroll
-        for (int x = 0; x < QS_STEPS; ++x)
+        for (int x = 0; x < QS_MAX; ++x)
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const int qs = 16 * x + 8 * g + e;
-                r2x[x][e] = (qs < plan.n_qslots) ? (_Float16)tmp[plan.qlist[qs] * N2 + qo] : (_Float16)0.f;
+                r2x[x][e] = (qs < plan.n_qslots) ? (_Float16)R2[plan.qlist[qs] * N2 + qo] : (_Float16)0.f;
             }
-        __syncthreads();
-        // R1 (stage B, operand B): lane holds column p' = 32nb + l32; step ks, element e <-> row
-        // p = 16ks + 8(e/4) + 4g + e%4, which is where stage A leaves row p of Z in this lane.
-        for (int c = tid; c < N1 * N1; c += 256) tmp[c] = R1[c];
-        __syncthreads();
 #pragma unroll
         for (int nb = 0; nb < MB; ++nb)
 #pragma unroll
@@ -154,12 +191,8 @@ __global__ __launch_bounds__(256, (RotqShape<N1, N2>::OCC)) void rotate_quantize
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const int p = 16 * ks + 8 * (e / 4) + 4 * g + (e % 4), po = 32 * nb + l32;
-                    r1f[nb][ks][e] = (p < N1 && po < N1) ? (_Float16)tmp[p * N1 + po] : (_Float16)0.f;
+                    r1f[nb][ks][e] = (p < N1 && po < N1) ? (_Float16)R1[p * N1 + po] : (_Float16)0.f;
                 }
-        __syncthreads();
-        // tiles start as zeros: padding rows (p >= N1) and unused side-tile slots stay zero
-        for (int c = tid; c < S::OFF_ZERO_END / 16; c += 256) smem_u4[c] = uint4{0, 0, 0, 0};
-        __syncthreads();
     }
 
     // lane l owns pair l of the level-sorted Givens list: its slots, angle and level
@@ -186,45 +219,15 @@ __global__ __launch_bounds__(256, (RotqShape<N1, N2>::OCC)) void rotate_quantize
         if (s < plan.n_slots) {
             const int ch = plan.chan[s], p = ch / N2, q = ch % N2, qs = plan.qslot[s];
             gs_tile[u] = (p * CPRX + ((q >> 3) ^ swz<CPRX>(p))) * 16 + (q & 7) * 2;
-            gs_lo[u] = (p * 8 + ((qs >> 3) ^ (p & 7))) * 16 + (qs & 7) * 2;
+            gs_lo[u] = (qs >> 4) * S::LO_STEP_BYTES + p * 32 + (qs & 15) * 2;
         }
     }
-
-    // LDS byte offsets of this lane's operand chunks inside a tile (row block 0): the swizzle
-    // only touches the low bits of the chunk index, so four offsets cover every step
-    constexpr int NJ = KSA < 4 ? KSA : 4;
-    int a_off[NJ], lo_off[QS_STEPS];
-#pragma unroll
-    for (int j = 0; j < NJ; ++j) a_off[j] = (l32 * CPRX + ((2 * j + g) ^ swz<CPRX>(l32))) * 16;
-#pragma unroll
-    for (int x = 0; x < QS_STEPS; ++x) lo_off[x] = (l32 * 8 + ((2 * x + g) ^ (l32 & 7))) * 16;
-
-    const int groups = (T + TPP - 1) / TPP;
-    const int stride = gridDim.x;
-    // does this wave's token exist in group grp (the last group may be partial)?
-    auto has_row = [&](int grp) { return (int64_t)grp * TPP + tok_slot < T; };
-    // lead wave: all loads of its token row of group `grp` into ring slot `slot`
-    auto issue_row = [&](int grp, int slot) {
-        if (has_row(grp)) {
-            const __half *row = X + ((int64_t)grp * TPP + tok_slot) * ldx;
-            const uint32_t dst0 = lds_base + S::OFF_X + (tok_slot * NSX + slot) * S::TILE_BYTES;
-#pragma unroll
-            for (int part = 0; part < LPT; ++part) {
-                const int c = part * 64 + lane;
-                if (c < S::ROW_CHUNKS) {
-                    const int r = c / CPRX, pc = c % CPRX;
-                    dma_16(row + r * N2 + ((pc ^ swz<CPRX>(r)) * 8),
-                           __builtin_amdgcn_readfirstlane(dst0 + part * 1024));
-                }
-            }
-        }
-    };
     // lead wave: Givens list on the tile in ring slot `slot`, side tile `lo_sel`
     auto givens = [&](int slot, int lo_sel) {
         if (plan.n_slots == 0) return;
         char *xt = lds + S::OFF_X + (tok_slot * NSX + slot) * S::TILE_BYTES;
-        char *lo_t = lds + S::OFF_LO + (tok_slot * 2 + lo_sel) * S::LO_BYTES;
-        float *gv = reinterpret_cast<float *>(lds + S::OFF_GV) + tok_slot * kRotqMaxSlots;
+        char *lo_t = lds + S::OFF_LO + (tok_slot * 2 + lo_sel) * lo_bytes;
+        float *gv = reinterpret_cast<float *>(lds + off_gv) + tok_slot * kRotqMaxSlots;
 #pragma unroll
         for (int u = 0; u < 2; ++u)
             if (gs_tile[u] >= 0) gv[lane + 64 * u] = __half2float(*reinterpret_cast<const __half *>(xt + gs_tile[u]));
@@ -247,61 +250,79 @@ __global__ __launch_bounds__(256, (RotqShape<N1, N2>::OCC)) void rotate_quantize
             }
     };
 
-    // ---- pipeline prologue: three rows in flight, first one rotated -------------------------
-    const int g0 = blockIdx.x;
+    // LDS byte offsets of this lane's operand chunks inside a tile (row block 0): the swizzle
+    // only touches the low bits of the chunk index, so four offsets cover every step
+    constexpr int NJ = KSA < 4 ? KSA : 4;
+    int a_off[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) a_off[j] = (l32 * CPRX + ((2 * j + g) ^ swz<CPRX>(l32))) * 16;
+    const int lo_off = (l32 * 2 + g) * 16;
+
+    // stage A of the token in ring slot `slot` / side tile `lo_sel`; after every UNIT_EVERY MFMAs
+    // one unit of `between(u)` is issued (the quantization of the previous token, or nothing)
+    v16f accz[MB], accy[MB];
+    constexpr int NMA = MB * KSA;
+    auto stage_a = [&](int slot, int lo_sel, auto between) {
+        const char *xt = lds + S::OFF_X + (tok_slot * NSX + slot) * S::TILE_BYTES;
+        auto a_at = [&](int m) {
+            const int mb = m / KSA, ks = m % KSA;
+            return *reinterpret_cast<const v8h *>(xt + a_off[ks % 4] + (ks / 4) * 128 + mb * (32 * CPRX * 16));
+        };
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) accz[mb][e] = 0.f;
+        v8h a0 = a_at(0), a1 = a_at(NMA > 1 ? 1 : 0);
+#pragma unroll
+        for (int m = 0; m < NMA; ++m) {
+            const v8h a2 = a_at(m + 2 < NMA ? m + 2 : NMA - 1);     // operand reads run two MFMAs ahead
+            accz[m / KSA] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, r2f[m % KSA], accz[m / KSA], 0, 0, 0);
+            between(m);
+            __builtin_amdgcn_sched_barrier(0);
+            a0 = a1;
+            a1 = a2;
+        }
+        const char *lo_t = lds + S::OFF_LO + (tok_slot * 2 + lo_sel) * lo_bytes;
+#pragma unroll
+        for (int x = 0; x < QS_MAX; ++x) {
+            if (x < qsteps) {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    const v8h a = *reinterpret_cast<const v8h *>(lo_t + x * S::LO_STEP_BYTES + mb * 1024 + lo_off);
+                    accz[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, r2x[x], accz[mb], 0, 0, 0);
+                }
+            }
+        }
+    };
+
+    // ---- pipeline prologue: first row rotated, its stage A done -------------------------------
+    __syncthreads();                       // zeros are in place before the first side-tile writes
     if (lead) {
-        issue_row(g0, 0);
-        issue_row(g0 + stride, 1);
-        issue_row(g0 + 2 * stride, 2);
         if (has_row(g0 + 2 * stride)) wait_loads_le<2 * LPT>();
         else if (has_row(g0 + stride)) wait_loads_le<LPT>();
         else wait_loads_le<0>();
         givens(0, 0);
     }
     __syncthreads();
+    stage_a(0, 0, [](int) {});
 
     int slot = 0, it = 0;
     for (int grp = g0; grp < groups; grp += stride, ++it) {
         const int t = grp * TPP + tok_slot;
         const bool live = t < T;
         const int slot1 = (slot + 1 == NSX) ? 0 : slot + 1;
-        const char *xt = lds + S::OFF_X + (tok_slot * NSX + slot) * S::TILE_BYTES;
-        const char *lo_t = lds + S::OFF_LO + (tok_slot * 2 + (it & 1)) * S::LO_BYTES;
-
-        // ---- stage A: Z = X_mat R2 (+ side tile x matching rows of R2) ---------------------
-        v16f accz[MB];
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) accz[mb][e] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < KSA; ++ks) {
-                const v8h a = *reinterpret_cast<const v8h *>(xt + a_off[ks % 4] + (ks / 4) * 128 + mb * (32 * CPRX * 16));
-                accz[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, r2f[ks], accz[mb], 0, 0, 0);
-            }
-#pragma unroll
-            for (int x = 0; x < QS_STEPS; ++x) {
-                if (16 * x < plan.n_qslots) {
-                    const v8h a = *reinterpret_cast<const v8h *>(lo_t + lo_off[x] + mb * (32 * 8 * 16));
-                    accz[mb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, r2x[x], accz[mb], 0, 0, 0);
-                }
-            }
-        }
 
         // ---- power-of-two prescale of this wave's columns so that hi/lo fit fp16 -------------
         // Stage B contracts over rows p within a column, so a per-wave factor commutes with it.
         float zmax = 0.f;
 #pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-            for (int e = 0; e < 16; e += 2) zmax = fmaxf(zmax, fmaxf(fabsf(accz[mb][e]), fabsf(accz[mb][e + 1])));
+        for (int mb = 0; mb < MB; ++mb) zmax = max_abs16(accz[mb], zmax);
         zmax = wave_max(zmax);
-        float fz = 1.0f, fz_inv = 1.0f;          // Z * fz in [2^13, 2^14) at its largest entry
-        const bool rescale = !(zmax >= 1.0f && zmax < 16384.0f) && zmax > 0.f;
-        if (rescale) {
+        float fz_inv = 1.0f;                     // Z * fz in [2^13, 2^14) at its largest entry
+        if (!(zmax >= 1.0f && zmax < 16384.0f) && zmax > 0.f) {
             const int ez = (int)((__float_as_uint(zmax) >> 23) & 0xFF) - 127;
             const int sh = max(-100, min(100, 13 - ez));
-            fz = __uint_as_float((uint32_t)(127 + sh) << 23);
+            const float fz = __uint_as_float((uint32_t)(127 + sh) << 23);
             fz_inv = __uint_as_float((uint32_t)(127 - sh) << 23);
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb)
@@ -309,49 +330,65 @@ __global__ __launch_bounds__(256, (RotqShape<N1, N2>::OCC)) void rotate_quantize
                 for (int e = 0; e < 16; ++e) accz[mb][e] *= fz;
         }
 
-        // ---- stage B: Y^T = Z^T R1, Z = hi + lo -------------------------------------------
-        v16f accy[MB];
+        // ---- stage B: Y^T = Z^T R1, Z = hi + lo; the split of step ks+1 is issued between the
+        // MFMAs of step ks -----------------------------------------------------------------
 #pragma unroll
         for (int nb = 0; nb < MB; ++nb)
 #pragma unroll
             for (int e = 0; e < 16; ++e) accy[nb][e] = 0.f;
+        v4u zh, zl, zh_n, zl_n;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            uint32_t hi, lo;
+            split_pair(accz[0][2 * e], accz[0][2 * e + 1], hi, lo);
+            zh[e] = hi;
+            zl[e] = lo;
+        }
 #pragma unroll
         for (int ks = 0; ks < KSB; ++ks) {
-            const int mb = ks >> 1, r0 = 8 * (ks & 1);
-            v4u zhu, zlu;
+            const v8h zhv = __builtin_bit_cast(v8h, zh), zlv = __builtin_bit_cast(v8h, zl);
+            constexpr int NMB = 2 * MB;          // MFMAs of this step
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                uint32_t hi, lo;
-                split_pair(accz[mb][r0 + 2 * e], accz[mb][r0 + 2 * e + 1], hi, lo);
-                zhu[e] = hi;
-                zlu[e] = lo;
-            }
-            const v8h zh = __builtin_bit_cast(v8h, zhu), zl = __builtin_bit_cast(v8h, zlu);
+            for (int j = 0; j < (NMB > 4 ? NMB : 4); ++j) {
+                if (j < NMB)
+                    accy[j / 2] = __builtin_amdgcn_mfma_f32_32x32x16_f16((j & 1) ? zlv : zhv, r1f[j / 2][ks], accy[j / 2], 0, 0, 0);
+                if (ks + 1 < KSB) {
+                    // pairs of the next step: 4 pairs spread over the MFMAs (all after the last if fewer)
+                    const int per = (4 + NMB - 1) / NMB;
 #pragma unroll
-            for (int nb = 0; nb < MB; ++nb) {
-                accy[nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(zh, r1f[nb][ks], accy[nb], 0, 0, 0);
-                accy[nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(zl, r1f[nb][ks], accy[nb], 0, 0, 0);
+                    for (int e = j * per; e < (j + 1) * per && e < 4; ++e) {
+                        if (j < NMB || true) {
+                            const int ks1 = ks + 1, mb1 = ks1 >> 1, r1 = 8 * (ks1 & 1);
+                            uint32_t hi, lo;
+                            split_pair(accz[mb1][r1 + 2 * e], accz[mb1][r1 + 2 * e + 1], hi, lo);
+                            zh_n[e] = hi;
+                            zl_n[e] = lo;
+                        }
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
+            zh = zh_n;
+            zl = zl_n;
         }
 
         // ---- per-token step: wave maximum now, token maximum after the barrier --------------
         float amax = 0.f;
 #pragma unroll
-        for (int nb = 0; nb < MB; ++nb)
-#pragma unroll
-            for (int e = 0; e < 16; e += 2) amax = fmaxf(amax, fmaxf(fabsf(accy[nb][e]), fabsf(accy[nb][e + 1])));
+        for (int nb = 0; nb < MB; ++nb) amax = max_abs16(accy[nb], amax);
         amax = wave_max(amax) * fz_inv;        // padded rows and columns of Y are exact zeros
-        float *red = reinterpret_cast<float *>(lds + S::OFF_RED) + tok_slot * 4;
+        float *red = reinterpret_cast<float *>(lds + off_red) + tok_slot * 4;
         if (lane == 0) red[cb] = amax;
 
         // ---- lead wave: the next row has landed (rows complete in order; only the row after it
-        // may still be in flight) -> rotate its touched channels while the others catch up
+        // may still be in flight) -> rotate its touched channels
         if (lead) {
             if (has_row(grp + 2 * stride)) wait_loads_le<LPT>();
             else wait_loads_le<0>();
             if (has_row(grp + stride)) givens(slot1, (it + 1) & 1);
         }
-        __syncthreads();     // B2: maxima visible; tile `slot` is no longer read; next tile rotated
+        __syncthreads();     // B2: maxima visible; next tile rotated; copy-out of the last token done
+        // stage A of this token ran an iteration ago, so its ring slot is free for the row after next
         if (lead) issue_row(grp + 3 * stride, slot);
 
         amax = red[0];
@@ -360,26 +397,6 @@ __global__ __launch_bounds__(256, (RotqShape<N1, N2>::OCC)) void rotate_quantize
         const float step = (amax == 0.f) ? 1.0f : amax / 7.0f;
         const float inv = fz_inv / step;       // codes = Y / step with Y = accy * fz_inv
         if (live && lead && lane == 0) scales[t] = step;
-
-        // ---- codes -> LDS staging.  A lane holds column p' = 32nb + l32 of Y^T and, per register
-        // group rg, four consecutive q' = 32cb + 8rg + 4g + (0..3): one 2-byte unit of the row.
-        // Staged as [unit][p'] so that the 32 lanes of a store hit 32 consecutive halfwords.
-        uint16_t *outq = reinterpret_cast<uint16_t *>(lds + S::OFF_OUT + tok_slot * S::OUT_BYTES);
-#pragma unroll
-        for (int nb = 0; nb < MB; ++nb) {
-            const int po = 32 * nb + l32;
-#pragma unroll
-            for (int rg = 0; rg < 4; ++rg) {
-                uint32_t w = 0;
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    // floor(v + 1/2) + 8 = trunc(v + 8.5) for v in [-8, 7.5); two's-complement nibble = that ^ 8
-                    const uint32_t c = (uint32_t)fmaf(accy[nb][4 * rg + u], inv, 8.5f);
-                    w |= c << (4 * u);
-                }
-                outq[(8 * cb + 2 * rg + g) * N1P + po] = (uint16_t)(w ^ 0x8888u);
-            }
-        }
         if (xrot != nullptr && live) {
 #pragma unroll
             for (int nb = 0; nb < MB; ++nb) {
@@ -392,6 +409,30 @@ __global__ __launch_bounds__(256, (RotqShape<N1, N2>::OCC)) void rotate_quantize
                 }
             }
         }
+
+        // ---- codes of this token, issued between the stage-A MFMAs of the next one ------------
+        // A lane holds column p' = 32nb + l32 of Y^T and, per register group rg, four consecutive
+        // q' = 32cb + 8rg + 4g + (0..3): one 2-byte unit of the code row.  Staged as [unit][p'] so
+        // that the 32 lanes of a store hit 32 consecutive halfwords.
+        uint16_t *outq = reinterpret_cast<uint16_t *>(lds + off_out + tok_slot * S::OUT_BYTES);
+        constexpr int NU = 4 * MB;               // quantization units of 4 codes
+        auto quant_unit = [&](int u) {
+            const int nb = u / 4, rg = u % 4;
+            uint32_t w = 0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                // floor(v + 1/2) + 8 = trunc(v + 8.5) for v in [-8, 7.5); two's-complement nibble = that ^ 8
+                const uint32_t c = (uint32_t)fmaf(accy[nb][4 * rg + k], inv, 8.5f);
+                w |= c << (4 * k);
+            }
+            outq[(8 * cb + 2 * rg + g) * N1P + 32 * nb + l32] = (uint16_t)(w ^ 0x8888u);
+        };
+        stage_a(slot1, (it + 1) & 1, [&](int m) {
+            // NU units spread over the NMA MFMAs
+#pragma unroll
+            for (int u = 0; u < NU; ++u)
+                if (u * NMA / NU == m) quant_unit(u);
+        });
         __syncthreads();     // B3: staged codes complete
 
         // ---- copy-out: 16 bytes (8 units of one row p') per lane, coalesced along the row -----
@@ -401,7 +442,7 @@ __global__ __launch_bounds__(256, (RotqShape<N1, N2>::OCC)) void rotate_quantize
             const int ts = c / ROW_OUT_CHUNKS, cc = c % ROW_OUT_CHUNKS;
             const int tt = grp * TPP + ts;
             const int po = cc / CH_PER_P, u0 = (cc % CH_PER_P) * 8;
-            const uint16_t *src = reinterpret_cast<const uint16_t *>(lds + S::OFF_OUT + ts * S::OUT_BYTES) + u0 * N1P + po;
+            const uint16_t *src = reinterpret_cast<const uint16_t *>(lds + off_out + ts * S::OUT_BYTES) + u0 * N1P + po;
             uint4 v;
             v.x = src[0] | ((uint32_t)src[N1P] << 16);
             v.y = src[2 * N1P] | ((uint32_t)src[3 * N1P] << 16);
@@ -420,13 +461,17 @@ static sq_status launch_rotq_mfma(const __half *X, int64_t ldx, int T, const Rot
                                   float *xrot, hipStream_t st)
 {
     using S = RotqShape<N1, N2>;
-    auto kernel = rotate_quantize_mfma_kernel<N1, N2>;
+    constexpr int OCC = (S::MB <= 2) ? 2 : 1;               // register budget: 256 per wave at two per SIMD
+    const int qsteps = (plan.n_qslots + 15) / 16;
+    const int lds = S::lds_bytes(qsteps);
+    if (lds > kMaxDynamicLds) return SQ_ERR_SHAPE;
+    auto kernel = rotate_quantize_mfma_kernel<N1, N2, OCC>;
     if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return SQ_ERR_LAUNCH;
     const int groups = (T + S::TPP - 1) / S::TPP;
-    const int resident = 256 * S::OCC;                      // workgroups the chip holds at once
+    const int per_cu = (OCC == 2 && 2 * lds <= 158 * 1024) ? 2 : 1;      // workgroups a CU holds
+    const int resident = 256 * per_cu;
     const int grid = groups < resident ? groups : resident;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), S::LDS_BYTES, st, X, ldx, T, plan, R1, R2, Q,
-                       scales, xrot);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), lds, st, X, ldx, T, plan, R1, R2, Q, scales, xrot);
     return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
