@@ -181,6 +181,19 @@ __global__ __launch_bounds__(WM *WN *kWave, OCC) void w4a4_gemm_kernel(
     for (int g = 0; g < B_LOADS; ++g)
         b_src[g] = Qw + (int64_t)min(col0 + RPL * (wave + NW * g) + lrow, N - 1) * Kb + lchunk * 16;
 
+    // The block's dequantization steps are parked in LDS behind the ring and the staged output
+    // tile, so that the epilogue does not wait on global memory: sx * 2^-8 for the BM tokens (the
+    // accumulators carry a factor 256), then sw for the BN output channels; 0 past the edges.
+    constexpr int SCALE_BYTE = (3 * STAGE_SLOTS * 16 > BM * (BN * 2 + 16)) ? 3 * STAGE_SLOTS * 16
+                                                                           : BM * (BN * 2 + 16);
+    float *scale_lds = reinterpret_cast<float *>(reinterpret_cast<char *>(smem) + SCALE_BYTE);
+    for (int r = tid; r < BM + BN; r += NT) {
+        float v;
+        if (r < BM) v = (row0 + r < T) ? sx[row0 + r] * 0.00390625f : 0.f;
+        else v = (col0 + r - BM < N) ? sw[col0 + r - BM] : 0.f;
+        scale_lds[r] = v;
+    }
+
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)smem;
     const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
     // loads of tile kt into ring stage `stage`, issued only if kt < limit
@@ -302,8 +315,7 @@ __global__ __launch_bounds__(WM *WN *kWave, OCC) void w4a4_gemm_kernel(
 
     // ---- epilogue ------------------------------------------------------------------------
     // 32x32 accumulator layout: lane holds column (lane % 32); register e holds row
-    // 8 * (e / 4) + 4 * (lane / 32) + e % 4.  The accumulators carry a factor 256, which is a
-    // power of two and is folded into the token step.
+    // 8 * (e / 4) + 4 * (lane / 32) + e % 4, i.e. four runs of four consecutive tokens.
     constexpr int YS = BN * 2 + 16;      // LDS row stride of the staged fp16 tile, bytes
     static_assert(BM * YS <= kMaxDynamicLds, "staged output tile must fit in LDS");
     wait_vmcnt<0>();
@@ -311,26 +323,37 @@ __global__ __launch_bounds__(WM *WN *kWave, OCC) void w4a4_gemm_kernel(
     char *ys = reinterpret_cast<char *>(smem);
     float swn[FN];
 #pragma unroll
-    for (int j = 0; j < FN; ++j) {
-        const int n = col0 + (wn * FN + j) * 32 + frow;
-        swn[j] = (n < N) ? sw[n] : 0.f;
-    }
+    for (int j = 0; j < FN; ++j) swn[j] = scale_lds[BM + (wn * FN + j) * 32 + frow];
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int tl = (wm * FM + i) * 32 + 8 * (e / 4) + 4 * fhalf + (e % 4);
-            const int t = row0 + tl;
-            const float sxt = (t < T) ? sx[t] * 0.00390625f : 0.f;
+        for (int q = 0; q < 4; ++q) {
+            const int tl0 = (wm * FM + i) * 32 + 8 * q + 4 * fhalf;
+            const float4 s4 = *reinterpret_cast<const float4 *>(scale_lds + tl0);
+            const float sxt[4] = {s4.x, s4.y, s4.z, s4.w};
 #pragma unroll
-            for (int j = 0; j < FN; ++j) {
-                const int nl = (wn * FN + j) * 32 + frow;
-                *reinterpret_cast<__half *>(ys + tl * YS + nl * 2) =
-                    __float2half_rn((float)acc[i][j][e] * sxt * swn[j]);
-                if (acc_dbg != nullptr && t < T && col0 + nl < N)
-                    acc_dbg[(int64_t)t * N + col0 + nl] = acc[i][j][e] >> 8;
+            for (int r = 0; r < 4; ++r) {
+#pragma unroll
+                for (int j = 0; j < FN; ++j) {
+                    const int nl = (wn * FN + j) * 32 + frow;
+                    *reinterpret_cast<__half *>(ys + (tl0 + r) * YS + nl * 2) =
+                        __float2half_rn((float)acc[i][j][4 * q + r] * sxt[r] * swn[j]);
+                }
             }
         }
+    }
+    if (acc_dbg != nullptr) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int t = row0 + (wm * FM + i) * 32 + 8 * (e / 4) + 4 * fhalf + (e % 4);
+#pragma unroll
+                for (int j = 0; j < FN; ++j) {
+                    const int n = col0 + (wn * FN + j) * 32 + frow;
+                    if (t < T && n < N) acc_dbg[(int64_t)t * N + n] = acc[i][j][e] >> 8;
+                }
+            }
     }
     __syncthreads();
     constexpr int CPRY = BN / 8;         // 16-byte chunks per output row
@@ -454,7 +477,8 @@ static sq_status launch_main(const uint8_t *Qx, const float *sx, int T, int K, c
 {
     constexpr int BM = WM * FM * 32, BN = WN * FN * 32;
     constexpr size_t ring = (size_t)3 * (BM + BN) * BKB, out_tile = (size_t)BM * (BN * 2 + 16);
-    constexpr size_t lds = ring > out_tile ? ring : out_tile;   // the epilogue reuses the ring
+    // the epilogue reuses the ring for the output tile; the scales sit behind both
+    constexpr size_t lds = (ring > out_tile ? ring : out_tile) + (size_t)(BM + BN) * 4;
     static_assert(lds <= (size_t)kMaxDynamicLds, "ring does not fit in LDS");
     auto kernel = w4a4_gemm_kernel<WM, WN, FM, FN, BKB, OCC>;
     if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return SQ_ERR_LAUNCH;
