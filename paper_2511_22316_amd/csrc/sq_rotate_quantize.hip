@@ -147,6 +147,7 @@ static bool build_rotq_plan(const GivensList &giv, int n2, RotqPlan &plan)
         if (lv > levels) levels = lv;
     }
     plan.n_levels = levels;
+    memset(plan.pair_level, 0xFF, sizeof(plan.pair_level));
     int pos = 0;
     for (int lv = 0; lv < levels; ++lv) {          // stable: list order is kept inside a level
         plan.level_begin[lv] = (uint8_t)pos;
@@ -154,6 +155,7 @@ static bool build_rotq_plan(const GivensList &giv, int n2, RotqPlan &plan)
             if (pair_level[p] == lv) {
                 plan.pair_i[pos] = (uint8_t)pair_si[p];
                 plan.pair_j[pos] = (uint8_t)pair_sj[p];
+                plan.pair_level[pos] = (uint8_t)lv;
                 plan.c[pos] = giv.c[p];
                 plan.s[pos] = giv.s[p];
                 ++pos;

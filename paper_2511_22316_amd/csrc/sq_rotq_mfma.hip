@@ -26,6 +26,8 @@
 #include "sq_common.h"
 #include "sq_rotq_plan.h"
 
+#include <type_traits>
+
 namespace sq {
 
 namespace {
@@ -149,11 +151,158 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
     };
 
     // ---- prologue -------------------------------------------------------------------------
-    // the first three rows leave for LDS before anything else, so their latency hides the rest
+    // Memory latencies are overlapped in this order: the first token row leaves for LDS, then the
+    // plan entries of this lane and the rotation blocks are requested, and only when those have
+    // been consumed do rows two and three follow (loads complete in order, so anything issued
+    // before the blocks would have to land before them).
+    if (lead) issue_row(g0, 0);
+
+    // This lane's plan entries are requested now and used after the rotation blocks are built.
+    // Lane l owns pair l of the level-sorted Givens list (its slots, angle and level) and two of
+    // the touched channels (slots l and l + 64) for the gather / scatter around the list.
+    const int my_level_raw = plan.pair_level[lane];
+    const int my_si = plan.pair_i[lane], my_sj = plan.pair_j[lane];
+    const float my_c = plan.c[lane], my_s = plan.s[lane];
+    const int my_chan[2] = {plan.chan[lane], plan.chan[lane + 64]};
+    const int my_qslot[2] = {plan.qslot[lane], plan.qslot[lane + 64]};
+
+    // R2 (stage A, operand B): lane holds column q' = 32cb + l32, step ks, element e <-> row
+    // q = 16ks + 8g + e.  R1 (stage B, operand B): lane holds column p' = 32nb + l32; step ks,
+    // element e <-> row p = 16ks + 8(e/4) + 4g + e%4, which is where stage A leaves row p of Z in
+    // this lane.
+    //
+    // Both are columns of a row-major matrix, which a lane cannot fetch with wide loads.  The
+    // matrix cores transpose instead: a 32x32 block of R is loaded as operand A (lane = row,
+    // eight consecutive columns = 16 contiguous bytes) and multiplied by slices of the identity,
+    // which is exact; the product arrives in the accumulator layout (lane = column, registers =
+    // rows 8(e/4) + 4g + e%4).  That is the row order stage B wants.  Stage A wants rows 8g + e
+    // per step, which is the same order with bits 2 and 3 of the row swapped, so the lanes of
+    // operand A fetch their rows in that swapped order.
+    v8h r2f[KSA], r2x[QS_MAX], r1f[MB][KSB];
+    {
+        v8h sel[2];                       // identity slices: B[k][n] = (16kk + k == n), k = 8g + e
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sel[kk][e] = (16 * kk + 8 * g + e == l32) ? (_Float16)1.f : (_Float16)0.f;
+        // All loads are unconditional (clamped addresses, zeros selected afterwards) and the code
+        // is free of branches, so the requests leave together and one memory round trip covers
+        // them all.
+        // Elements BASE + 8g .. +7 of a row of NC columns as a 16-byte load.  A chunk that reaches
+        // past the end of the row is fetched from NC-8 and shifted down; the elements behind the
+        // end are zero.
+        auto chunk = [&](const __half *row, auto base_c, auto nc_c) {
+            constexpr int BASE = decltype(base_c)::value, NC = decltype(nc_c)::value;
+            static_assert(NC >= 8, "a row holds at least one chunk");
+            constexpr int COL0 = BASE < NC - 8 ? BASE : NC - 8, COL1 = BASE + 8 < NC - 8 ? BASE + 8 : NC - 8;
+            constexpr int OVER0 = BASE - COL0 > 8 ? 8 : BASE - COL0;           // elements to shift out
+            constexpr int OVER1 = BASE + 8 - COL1 > 8 ? 8 : BASE + 8 - COL1;
+            const int col = g ? COL1 : COL0;
+            const v8h v = *reinterpret_cast<const v8h *>(__builtin_assume_aligned(row + col, 4));
+            if constexpr (OVER0 == 0 && OVER1 == 0) {
+                return v;
+            } else {
+                v8h lo_g, hi_g;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    lo_g[e] = (e + OVER0 < 8) ? v[(e + OVER0) & 7] : (_Float16)0.f;
+                    hi_g[e] = (e + OVER1 < 8) ? v[(e + OVER1) & 7] : (_Float16)0.f;
+                }
+                return g ? hi_g : lo_g;
+            }
+        };
+        auto zero_unless = [&](bool keep, const v8h v) {
+            const v4u w = __builtin_bit_cast(v4u, v);
+            const v4u z = {keep ? w[0] : 0u, keep ? w[1] : 0u, keep ? w[2] : 0u, keep ? w[3] : 0u};
+            return __builtin_bit_cast(v8h, z);
+        };
+        // 32 rows x 32 columns -> accumulator layout
+        auto block_t = [&](const v8h a0, const v8h a1) {
+            v16f c;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) c[e] = 0.f;
+            c = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, sel[0], c, 0, 0, 0);
+            return __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, sel[1], c, 0, 0, 0);
+        };
+        auto to_frag = [&](const v16f &c, int s) {      // registers 8s .. 8s+7, exact in fp16
+            v4u w;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                w[e] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(c[8 * s + 2 * e], c[8 * s + 2 * e + 1]));
+            return __builtin_bit_cast(v8h, w);
+        };
+        const int lsw = (l32 & 0x13) | ((l32 & 4) << 1) | ((l32 & 8) >> 1);
+        const __half *r2col = R2 + 32 * cb;
+        using C0 = std::integral_constant<int, 0>;
+        using C16 = std::integral_constant<int, 16>;
+        using CN2 = std::integral_constant<int, N2>;
+        using CN1 = std::integral_constant<int, N1>;
+        v8h raw2[N2 / 32][2], rawx[QS_MAX / 2][2], raw1[MB][MB][2];
+        int qrow[QS_MAX / 2];
+#pragma unroll
+        for (int xb = 0; xb < QS_MAX / 2; ++xb) qrow[xb] = plan.qlist[32 * xb + lsw];   // 0 behind the end
+#pragma unroll
+        for (int blk = 0; blk < N2 / 32; ++blk) {
+            raw2[blk][0] = chunk(r2col + (32 * blk + lsw) * N2, C0{}, CN2{});
+            raw2[blk][1] = chunk(r2col + (32 * blk + lsw) * N2, C16{}, CN2{});
+        }
+#pragma unroll
+        for (int nb = 0; nb < MB; ++nb)
+#pragma unroll
+            for (int blk = 0; blk < MB; ++blk) {
+                const __half *row = R1 + min(32 * blk + l32, N1 - 1) * N1;
+                if (nb == 0) {
+                    raw1[0][blk][0] = chunk(row, std::integral_constant<int, 0>{}, CN1{});
+                    raw1[0][blk][1] = chunk(row, std::integral_constant<int, 16>{}, CN1{});
+                } else if (nb == 1) {
+                    raw1[nb][blk][0] = chunk(row, std::integral_constant<int, 32>{}, CN1{});
+                    raw1[nb][blk][1] = chunk(row, std::integral_constant<int, 48>{}, CN1{});
+                } else {
+                    raw1[nb][blk][0] = chunk(row, std::integral_constant<int, 64>{}, CN1{});
+                    raw1[nb][blk][1] = chunk(row, std::integral_constant<int, 80>{}, CN1{});
+                }
+            }
+#pragma unroll
+        for (int xb = 0; xb < QS_MAX / 2; ++xb) {       // after the others: the row numbers come out of the plan
+            rawx[xb][0] = chunk(r2col + qrow[xb] * N2, C0{}, CN2{});
+            rawx[xb][1] = chunk(r2col + qrow[xb] * N2, C16{}, CN2{});
+        }
+        __builtin_amdgcn_sched_barrier(0);              // every request is out before the first use
+#pragma unroll
+        for (int blk = 0; blk < N2 / 32; ++blk) {
+            const v16f c = block_t(raw2[blk][0], raw2[blk][1]);
+            r2f[2 * blk] = to_frag(c, 0);
+            r2f[2 * blk + 1] = to_frag(c, 1);
+        }
+#pragma unroll
+        for (int nb = 0; nb < MB; ++nb)
+#pragma unroll
+            for (int blk = 0; blk < MB; ++blk) {
+                const bool keep = 32 * blk + l32 < N1;
+                const v16f c = block_t(zero_unless(keep, raw1[nb][blk][0]), zero_unless(keep, raw1[nb][blk][1]));
+                r1f[nb][2 * blk] = to_frag(c, 0);
+                r1f[nb][2 * blk + 1] = to_frag(c, 1);
+            }
+#pragma unroll
+        for (int xb = 0; xb < QS_MAX / 2; ++xb) {
+            const bool keep = 32 * xb + lsw < plan.n_qslots;
+            const v16f c = block_t(zero_unless(keep, rawx[xb][0]), zero_unless(keep, rawx[xb][1]));
+            r2x[2 * xb] = to_frag(c, 0);
+            r2x[2 * xb + 1] = to_frag(c, 1);
+        }
+    }
+
     if (lead) {
-        issue_row(g0, 0);
         issue_row(g0 + stride, 1);
         issue_row(g0 + 2 * stride, 2);
+    }
+    const int my_level = (my_level_raw == 0xFF) ? -1 : my_level_raw;
+    int gs_tile[2], gs_lo[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int p = my_chan[u] / N2, q = my_chan[u] % N2, qs = my_qslot[u];
+        gs_tile[u] = (lane + 64 * u < plan.n_slots) ? (p * CPRX + ((q >> 3) ^ swz<CPRX>(p))) * 16 + (q & 7) * 2 : -1;
+        gs_lo[u] = (qs >> 4) * S::LO_STEP_BYTES + p * 32 + (qs & 15) * 2;
     }
     // zeros where nothing is ever loaded: padding rows p >= N1 of every ring tile, and the side tiles
     if (N1P > N1) {
@@ -166,62 +315,6 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
     for (int c = tid; c < TPP * 2 * lo_bytes / 16; c += 256)
         *reinterpret_cast<uint4 *>(lds + S::OFF_LO + c * 16) = uint4{0, 0, 0, 0};
 
-    // R2 (stage A, operand B): lane holds column q' = 32cb + l32, step ks, element e <-> row
-    // q = 16ks + 8g + e.  R1 (stage B, operand B): lane holds column p' = 32nb + l32; step ks,
-    // element e <-> row p = 16ks + 8(e/4) + 4g + e%4, which is where stage A leaves row p of Z in
-    // this lane.  Read straight from global memory (L2-resident after the first workgroup).
-    v8h r2f[KSA], r2x[QS_MAX], r1f[MB][KSB];
-    {
-        const int qo = 32 * cb + l32;
-#pragma unroll
-        for (int ks = 0; ks < KSA; ++ks)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) r2f[ks][e] = (_Float16)R2[(16 * ks + 8 * g + e) * N2 + qo];
-#pragma unroll
-        for (int x = 0; x < QS_MAX; ++x)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int qs = 16 * x + 8 * g + e;
-                r2x[x][e] = (qs < plan.n_qslots) ? (_Float16)R2[plan.qlist[qs] * N2 + qo] : (_Float16)0.f;
-            }
-#pragma unroll
-        for (int nb = 0; nb < MB; ++nb)
-#pragma unroll
-            for (int ks = 0; ks < KSB; ++ks)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int p = 16 * ks + 8 * (e / 4) + 4 * g + (e % 4), po = 32 * nb + l32;
-                    r1f[nb][ks][e] = (p < N1 && po < N1) ? (_Float16)R1[p * N1 + po] : (_Float16)0.f;
-                }
-    }
-
-    // lane l owns pair l of the level-sorted Givens list: its slots, angle and level
-    int my_level = -1, my_si = 0, my_sj = 0;
-    float my_c = 1.f, my_s = 0.f;
-    {
-        const int n_pairs = plan.level_begin[plan.n_levels];
-        if (lane < n_pairs) {
-            my_si = plan.pair_i[lane];
-            my_sj = plan.pair_j[lane];
-            my_c = plan.c[lane];
-            my_s = plan.s[lane];
-            for (int lv = 0; lv < plan.n_levels; ++lv)
-                if (lane >= plan.level_begin[lv]) my_level = lv;
-        }
-    }
-    // per-lane gather / scatter addresses of the touched channels (two slots per lane)
-    int gs_tile[2], gs_lo[2];
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-        const int s = lane + 64 * u;
-        gs_tile[u] = -1;
-        gs_lo[u] = 0;
-        if (s < plan.n_slots) {
-            const int ch = plan.chan[s], p = ch / N2, q = ch % N2, qs = plan.qslot[s];
-            gs_tile[u] = (p * CPRX + ((q >> 3) ^ swz<CPRX>(p))) * 16 + (q & 7) * 2;
-            gs_lo[u] = (qs >> 4) * S::LO_STEP_BYTES + p * 32 + (qs & 15) * 2;
-        }
-    }
     // lead wave: Givens list on the tile in ring slot `slot`, side tile `lo_sel`
     auto givens = [&](int slot, int lo_sel) {
         if (plan.n_slots == 0) return;

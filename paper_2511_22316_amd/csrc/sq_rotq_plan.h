@@ -24,6 +24,7 @@ struct RotqPlan {
     uint8_t level_begin[SQ_MAX_GIVENS + 1];   // pairs [level_begin[l], level_begin[l+1]) form level l
     uint8_t pair_i[SQ_MAX_GIVENS];            // slots of the pair, in level order
     uint8_t pair_j[SQ_MAX_GIVENS];
+    uint8_t pair_level[SQ_MAX_GIVENS];        // level of the pair, 0xFF behind the end of the list
     float c[SQ_MAX_GIVENS];                   // cos, sin of the pair's angle
     float s[SQ_MAX_GIVENS];
 };
