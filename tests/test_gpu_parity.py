@@ -117,7 +117,10 @@ def test_rotate_quantize_identity_rotation_is_exact(oracle):
 # ------------------------------------------------------------------------------ GEMM ------
 
 @pytest.mark.parametrize("T,K,N", [(1, 32, 1), (16, 512, 512), (77, 96, 300), (130, 288, 257),
-                                   (8, 1024, 520), (300, 2048, 130)])
+                                   (8, 1024, 520), (300, 2048, 130),
+                                   # at most 32 tokens: the decode-shaped kernel in its three launch
+                                   # shapes, one K slice only / ragged channel tails / T = 32
+                                   (1, 256, 33), (32, 768, 8200), (31, 512, 24600), (33, 512, 300)])
 def test_gemm_random_codes_bit_exact(oracle, T, K, N):
     print(f"case gemm random codes T={T} K={K} N={N}", flush=True)
     g = np.random.default_rng(T * 7 + K + N)
