@@ -101,6 +101,46 @@ def test_rotate_quantize_edge_cases(oracle):
     assert np.array_equal(Q.cpu().numpy(), Qref) and np.array_equal(s.cpu().numpy(), sref)
 
 
+@pytest.mark.parametrize("kind", ["chain_21", "star_16", "star_17", "disjoint_64", "repeat_pair", "two_trees_64",
+                                  "many_q"])
+@pytest.mark.parametrize("name", ["tiny", "attn_proj"])
+def test_rotate_quantize_givens_list_shapes(oracle, name, kind):
+    """Lists of different dependency structure: a chain (every pair waits for the one before), stars
+    (one channel in every pair), 64 independent pairs, a pair repeated back to back, trees that
+    use the longest list, and channels that fall on many different columns of the n1 x n2 view."""
+    print(f"case rotate_quantize givens list {name} {kind}", flush=True)
+    cfg = synth.CONFIGS[name]
+    L = synth.layer(cfg, 12)
+    K = cfg.K
+    kinds = ["chain_21", "star_16", "star_17", "disjoint_64", "repeat_pair", "two_trees_64", "many_q"]
+    g = np.random.default_rng(1000 * kinds.index(kind) + K)
+    ch = g.permutation(K)
+    if kind == "chain_21":          # 21 channels, every pair depends on the one before
+        gi, gj = ch[:20], ch[1:21]
+    elif kind == "star_16":         # 15 pairs through one channel
+        gi, gj = np.full(15, ch[0]), ch[1:16]
+    elif kind == "star_17":
+        gi, gj = np.full(16, ch[0]), ch[1:17]
+    elif kind == "disjoint_64":     # 64 pairs, 128 distinct channels: one level
+        gi, gj = ch[:64], ch[64:128]
+    elif kind == "repeat_pair":     # same two channels three times, then swapped
+        gi, gj = np.array([ch[0], ch[0], ch[0], ch[1]]), np.array([ch[1], ch[1], ch[1], ch[0]])
+    elif kind == "two_trees_64":    # two groups of 16 channels and a few small ones, 64 pairs in all
+        a = [(ch[0], ch[1 + k % 15]) for k in range(30)] + [(ch[20], ch[21 + k % 15]) for k in range(30)]
+        a += [(ch[40], ch[41]), (ch[42], ch[43]), (ch[41], ch[44]), (ch[43], ch[45])]
+        gi, gj = np.array([x for x, _ in a]), np.array([y for _, y in a])
+    else:                           # 32 pairs whose 64 channels sit in 64 different columns if n2 allows
+        cols = g.permutation(cfg.n2)[: min(64, cfg.n2)]
+        chans = np.array([g.integers(0, cfg.n1) * cfg.n2 + c for c in cols])
+        gi, gj = chans[: len(chans) // 2], chans[len(chans) // 2: 2 * (len(chans) // 2)]
+    gt = g.uniform(-3.1, 3.1, len(gi)).astype(np.float32)
+    L2 = synth.Layer(cfg, L.X, gi.astype(np.int32), gj.astype(np.int32), gt, L.R1, L.R2, L.R1_f64, L.R2_f64)
+    Qg, sg, xg = run_rotate_quantize(L2)
+    xo, Qo, so = _oracle_rq(oracle, L2)
+    check_rotation(xg, xo)
+    check_codes(Qg, sg, Qo, so)
+
+
 def test_rotate_quantize_identity_rotation_is_exact(oracle):
     """R1 = I, R2 = I, no Givens: the rotated row is the fp16 input itself, bit for bit."""
     print("case rotate_quantize identity", flush=True)
