@@ -103,7 +103,8 @@ struct RotqShape {
     static_assert(2 * LPT < 64, "outstanding loads must fit the vmcnt counter");
 };
 
-template <int N1, int N2, int OCC>
+// QS_MAX: repair steps of 16 q-slots each the kernel holds rotation rows for (4 or 8).
+template <int N1, int N2, int OCC, int QS_MAX>
 __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
     const __half *__restrict__ X, int64_t ldx, int T, RotqPlan plan,
     const __half *__restrict__ R1, const __half *__restrict__ R2, uint8_t *__restrict__ Q,
@@ -112,7 +113,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
     using S = RotqShape<N1, N2>;
     constexpr int N1P = S::N1P, MB = S::MB, NCB = S::NCB, TPP = S::TPP, KSA = S::KSA, KSB = S::KSB;
     constexpr int CPRX = S::CPRX, LPT = S::LPT, NSX = S::NSX, K = N1 * N2;
-    constexpr int QS_MAX = kRotqMaxQSlots / 16;
+    static_assert(QS_MAX == 4 || QS_MAX == 8, "64 or 128 q-slots");
     extern __shared__ uint4 smem_u4[];
     char *lds = reinterpret_cast<char *>(smem_u4);
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)smem_u4;
@@ -548,17 +549,17 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
     wait_loads_le<0>();
 }
 
-template <int N1, int N2>
-static sq_status launch_rotq_mfma(const __half *X, int64_t ldx, int T, const RotqPlan &plan,
-                                  const __half *R1, const __half *R2, uint8_t *Q, float *scales,
-                                  float *xrot, hipStream_t st)
+template <int N1, int N2, int QS_MAX>
+static sq_status launch_rotq_mfma_qs(const __half *X, int64_t ldx, int T, const RotqPlan &plan,
+                                     const __half *R1, const __half *R2, uint8_t *Q, float *scales,
+                                     float *xrot, hipStream_t st)
 {
     using S = RotqShape<N1, N2>;
     constexpr int OCC = (S::MB <= 2) ? 2 : 1;               // register budget: 256 per wave at two per SIMD
     const int qsteps = (plan.n_qslots + 15) / 16;
     const int lds = S::lds_bytes(qsteps);
     if (lds > kMaxDynamicLds) return SQ_ERR_SHAPE;
-    auto kernel = rotate_quantize_mfma_kernel<N1, N2, OCC>;
+    auto kernel = rotate_quantize_mfma_kernel<N1, N2, OCC, QS_MAX>;
     if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return SQ_ERR_LAUNCH;
     const int groups = (T + S::TPP - 1) / S::TPP;
     const int per_cu = (OCC == 2 && 2 * lds <= 158 * 1024) ? 2 : 1;      // workgroups a CU holds
@@ -566,6 +567,19 @@ static sq_status launch_rotq_mfma(const __half *X, int64_t ldx, int T, const Rot
     const int grid = groups < resident ? groups : resident;
     hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), lds, st, X, ldx, T, plan, R1, R2, Q, scales, xrot);
     return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+// A list touches at most min(2P, n2) distinct columns q: more than 64 only if n2 is 128.
+template <int N1, int N2>
+static sq_status launch_rotq_mfma(const __half *X, int64_t ldx, int T, const RotqPlan &plan,
+                                  const __half *R1, const __half *R2, uint8_t *Q, float *scales,
+                                  float *xrot, hipStream_t st)
+{
+    if constexpr (N2 > 64) {
+        if (plan.n_qslots > 64)
+            return launch_rotq_mfma_qs<N1, N2, 8>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st);
+    }
+    return launch_rotq_mfma_qs<N1, N2, 4>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st);
 }
 
 // Picks the instantiation for (n1, n2); returns false if this kernel does not cover the shape.

@@ -9,7 +9,7 @@
 namespace sq {
 
 constexpr int kRotqMaxSlots = 2 * SQ_MAX_GIVENS;   // distinct channels a list can touch
-constexpr int kRotqMaxQSlots = 64;                 // distinct q = channel % n2 the MFMA kernel repairs
+constexpr int kRotqMaxQSlots = 128;                // distinct q = channel % n2 the MFMA kernel repairs
 
 // The list is regrouped into levels: a pair goes one level after the latest earlier pair that
 // shares a channel with it.  Pairs of one level touch disjoint channels, and every dependency

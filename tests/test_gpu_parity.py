@@ -141,6 +141,25 @@ def test_rotate_quantize_givens_list_shapes(oracle, name, kind):
     check_codes(Qg, sg, Qo, so)
 
 
+@pytest.mark.parametrize("name", ["decode", "mlp_down"])
+def test_rotate_quantize_givens_list_touching_every_column(oracle, name):
+    """64 pairs whose 128 channels fall on 128 different columns of the n1 x 128 view: the most
+    columns a list can touch."""
+    print(f"case rotate_quantize givens list wide {name}", flush=True)
+    cfg = synth.CONFIGS[name]
+    assert cfg.n2 == 128
+    L = synth.layer(cfg, 10)
+    g = np.random.default_rng(77 + cfg.n1)
+    chans = np.array([g.integers(0, cfg.n1) * cfg.n2 + q for q in g.permutation(cfg.n2)])
+    gi, gj = chans[:64].astype(np.int32), chans[64:].astype(np.int32)
+    gt = g.uniform(-3.1, 3.1, 64).astype(np.float32)
+    L2 = synth.Layer(cfg, L.X, gi, gj, gt, L.R1, L.R2, L.R1_f64, L.R2_f64)
+    Qg, sg, xg = run_rotate_quantize(L2)
+    xo, Qo, so = _oracle_rq(oracle, L2)
+    check_rotation(xg, xo)
+    check_codes(Qg, sg, Qo, so)
+
+
 def test_rotate_quantize_identity_rotation_is_exact(oracle):
     """R1 = I, R2 = I, no Givens: the rotated row is the fp16 input itself, bit for bit."""
     print("case rotate_quantize identity", flush=True)
