@@ -357,17 +357,29 @@ __global__ __launch_bounds__(WM *WN *kWave, OCC) void w4a4_gemm_kernel(
     }
     __syncthreads();
     constexpr int CPRY = BN / 8;         // 16-byte chunks per output row
-    for (int idx = tid; idx < BM * CPRY; idx += NT) {
-        const int tl = idx / CPRY, ch = idx % CPRY;
-        const int t = row0 + tl, n0 = col0 + ch * 8;
-        if (t >= T || n0 >= N) continue;
-        const uint4 v = *reinterpret_cast<const uint4 *>(ys + tl * YS + ch * 16);
-        __half *dst = Y + (int64_t)t * ldy + n0;
-        if (vec_store && n0 + 8 <= N) {
-            *reinterpret_cast<uint4 *>(dst) = v;
-        } else {
-            const __half *h = reinterpret_cast<const __half *>(&v);
-            for (int u = 0; u < 8 && n0 + u < N; ++u) dst[u] = h[u];
+    constexpr int ROUNDS = BM * CPRY / NT, BATCH = 4;
+    static_assert((BM * CPRY) % (NT * BATCH) == 0, "copy-out rounds come in batches of four");
+    for (int r0 = 0; r0 < ROUNDS; r0 += BATCH) {       // four LDS reads in flight, then their stores
+        uint4 v[BATCH];
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int idx = (r0 + u) * NT + tid;
+            v[u] = *reinterpret_cast<const uint4 *>(ys + (idx / CPRY) * YS + (idx % CPRY) * 16);
+        }
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            const int idx = (r0 + u) * NT + tid;
+            const int t = row0 + idx / CPRY, n0 = col0 + (idx % CPRY) * 8;
+            if (t >= T || n0 >= N) continue;
+            __half *dst = Y + (int64_t)t * ldy + n0;
+            if (vec_store && n0 + 8 <= N) {
+                *reinterpret_cast<uint4 *>(dst) = v[u];
+            } else {
+                const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e)          // register-only: no addressable copy of the chunk
+                    if (n0 + e < N) reinterpret_cast<uint16_t *>(dst)[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+            }
         }
     }
 }
