@@ -104,6 +104,32 @@ sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T, int32_t K,
                        const uint8_t *Qw, const float *sw, int32_t N,
                        void *Y, int64_t ldy, int32_t *acc_dbg, void *stream);
 
+/*
+ * sq_prepare_weights -- offline weight path of Sec. 4.2: the rotation that is
+ * applied to the activations online is folded into the weights,
+ * W~ = R^T W with R = G_1 ... G_P (R1 (x) R2), stored as Flat(W~_R) = W^T R, one
+ * K-contiguous row per output channel, and quantized per output channel with
+ * the quantizer of Sec. 3.2 (round to nearest, step = row maximum / 7).
+ * Row n of W^T goes through exactly the steps sq_rotate_quantize applies to a
+ * token row, so (X R)(R^T W) = X W holds up to the two quantizations.
+ *
+ *   W          device, fp16 [K, ldw], W[k, n] = weight from input channel k to
+ *              output channel n (the layout of y = x W); ldw >= N
+ *   workspace  device, N * K fp16 values, 16-byte aligned: receives W^T.
+ *              Caller-owned; may be released once the stream has passed the call.
+ *   Qw, sw     device out, uint8 [N, K/2] (16-byte aligned) and float [N]:
+ *              the weight operand of sq_w4a4_gemm
+ * Givens list, R1, R2 as in sq_rotate_quantize; the same shape limits apply.
+ * N == 0 is legal and enqueues nothing.
+ */
+sq_status sq_prepare_weights(const void *W, int32_t K, int32_t N, int64_t ldw,
+                             const int32_t *giv_i, const int32_t *giv_j,
+                             const float *giv_theta, int32_t P,
+                             const void *R1, int32_t n1,
+                             const void *R2, int32_t n2,
+                             void *workspace, uint8_t *Qw, float *sw,
+                             void *stream);
+
 /* Static, human-readable name of a status code. */
 const char *sq_status_string(sq_status status);
 

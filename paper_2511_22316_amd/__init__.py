@@ -8,6 +8,7 @@ from . import synth  # noqa: F401
 from .binding import (  # noqa: F401
     SQError,
     library_path,
+    sq_prepare_weights,
     sq_rotate_quantize,
     sq_w4a4_gemm,
     sq_status_string,

@@ -48,6 +48,12 @@ def _load():
             C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
             C.c_void_p, C.c_void_p, C.c_int32,
             C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
+        lib.sq_prepare_weights.restype = C.c_int
+        lib.sq_prepare_weights.argtypes = [
+            C.c_void_p, C.c_int32, C.c_int32, C.c_int64,
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+            C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.sq_status_string.restype = C.c_char_p
         lib.sq_status_string.argtypes = [C.c_int]
         _lib = lib
@@ -103,4 +109,22 @@ def sq_w4a4_gemm(Qx, sx, Qw, sw, Y, acc_dbg=None, stream=None) -> None:
     code = _load().sq_w4a4_gemm(
         _dev_ptr(Qx), _dev_ptr(sx), T, 2 * Kh, _dev_ptr(Qw), _dev_ptr(sw), N,
         _dev_ptr(Y), ldy, _dev_ptr(acc_dbg), _stream_handle(stream))
+    _check(code)
+
+
+def sq_prepare_weights(W, giv_i, giv_j, giv_theta, R1, R2, workspace, Qw, sw, stream=None) -> None:
+    """W fp16 [K, N] (row stride = W.stride(0)); workspace fp16 with at least N*K elements;
+    outputs Qw uint8 [N, K/2], sw fp32 [N].  Givens list and R1, R2 as in sq_rotate_quantize."""
+    gi, gj, gt = _host(giv_i, np.int32), _host(giv_j, np.int32), _host(giv_theta, np.float32)
+    P = 0 if gi is None else int(gi.size)
+    K, N = int(W.shape[0]), int(W.shape[1])
+    ldw = int(W.stride(0)) if K > 1 else max(N, 1)
+    if workspace is not None and workspace.numel() < N * K:
+        raise ValueError("workspace holds fewer than N*K elements")
+    code = _load().sq_prepare_weights(
+        _dev_ptr(W), K, N, ldw,
+        None if gi is None else gi.ctypes.data, None if gj is None else gj.ctypes.data,
+        None if gt is None else gt.ctypes.data, P,
+        _dev_ptr(R1), int(R1.shape[0]), _dev_ptr(R2), int(R2.shape[0]),
+        _dev_ptr(workspace), _dev_ptr(Qw), _dev_ptr(sw), _stream_handle(stream))
     _check(code)

@@ -26,7 +26,7 @@ def test_library_exports_every_declared_symbol(lib):
     header = open(os.path.join(ROOT, "include", "singlequant.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(sq_[a-z0-9_]+)\s*\(", header))
-    assert {"sq_rotate_quantize", "sq_w4a4_gemm", "sq_status_string"} <= declared
+    assert {"sq_rotate_quantize", "sq_w4a4_gemm", "sq_prepare_weights", "sq_status_string"} <= declared
     for name in declared:
         assert hasattr(lib, name), f"{name} is declared in singlequant.h but not exported"
 
@@ -89,3 +89,26 @@ def test_binding_raises_on_error(lib):
     with pytest.raises(sq.SQError) as e:
         binding._check(lib.sq_w4a4_gemm(FAKE, FAKE, 4, 48, FAKE, FAKE, 8, FAKE, 8, None, None))
     assert e.value.code == 2
+
+
+def _pw(lib, K=64, N=8, ldw=8, gi=(1,), gj=(2,), gt=(0.1,), n1=8, n2=8, W=FAKE, ws=FAKE, R1=FAKE, R2=FAKE,
+        Qw=FAKE, sw=FAKE):
+    gi_a, gj_a = np.asarray(gi, np.int32), np.asarray(gj, np.int32)
+    gt_a = np.asarray(gt, np.float32)
+    return lib.sq_prepare_weights(W, K, N, ldw, gi_a.ctypes.data, gj_a.ctypes.data, gt_a.ctypes.data,
+                                  len(gi_a), R1, n1, R2, n2, ws, Qw, sw, None)
+
+
+def test_prepare_weights_argument_errors(lib):
+    assert _pw(lib, N=-1) == 2
+    assert _pw(lib, ldw=4) == 2                     # leading dimension shorter than a row
+    assert _pw(lib, K=63) == 2                      # K != n1*n2 (the row kernel's check)
+    assert _pw(lib, gi=(64,)) == 3
+    assert _pw(lib, W=None) == 1
+    assert _pw(lib, ws=None) == 1
+    assert _pw(lib, R2=None) == 1
+    assert _pw(lib, Qw=None) == 1
+    assert _pw(lib, ws=FAKE + 8) == 4
+    assert _pw(lib, W=FAKE + 1) == 4
+    assert _pw(lib, Qw=FAKE + 4) == 4
+    assert _pw(lib, N=0) == 0                       # nothing to do, nothing enqueued

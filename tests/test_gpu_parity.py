@@ -306,3 +306,40 @@ def test_gemm_full_size_checksums_and_samples(oracle, name):
     # weight codes of sampled output channels against the oracle's offline path
     Qwo, swo = oracle.prepare_weights(synth.weight_rows_t(cfg, ns), L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)
     check_codes(Qw[ns], sw[ns], Qwo, swo)
+
+
+# ------------------------------------------------------------------ offline weight path -----
+
+@pytest.mark.parametrize("name,N", [("tiny", 512), ("tiny", 130), ("attn_proj", 200)])
+def test_prepare_weights_matches_oracle(oracle, name, N):
+    """sq_prepare_weights on W [K, N] against the oracle's weight path on the rows of W^T; then
+    the codes it wrote feed sq_w4a4_gemm and the accumulators are the oracle's, bit for bit."""
+    print(f"case prepare_weights {name} N={N}", flush=True)
+    import torch
+    import paper_2511_22316_amd as sq
+    cfg = synth.CONFIGS[name]
+    L = synth.layer(cfg, 16)
+    Wt = synth.weights_t(cfg, N)                          # [N, K] fp16
+    W = torch.from_numpy(np.ascontiguousarray(Wt.T)).cuda()    # [K, N]
+    wide = torch.zeros((cfg.K, N + 24), dtype=torch.float16, device="cuda")   # strided source
+    wide[:, :N] = W
+    ws = torch.empty((N * cfg.K,), dtype=torch.float16, device="cuda")
+    Qw = torch.empty((N, cfg.K // 2), dtype=torch.uint8, device="cuda")
+    sw = torch.empty((N,), dtype=torch.float32, device="cuda")
+    R1, R2 = torch.from_numpy(L.R1).cuda(), torch.from_numpy(L.R2).cuda()
+    sq.sq_prepare_weights(wide[:, :N], L.giv_i, L.giv_j, L.giv_theta, R1, R2, ws, Qw, sw)
+    torch.cuda.synchronize()
+    assert np.array_equal(ws.cpu().numpy().reshape(N, cfg.K), Wt)        # the transpose is exact
+    Qo, so = oracle.prepare_weights(Wt, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)
+    check_codes(Qw.cpu().numpy(), sw.cpu().numpy(), Qo, so)
+    # same bytes as the row kernel applied to W^T directly
+    Q2 = torch.empty_like(Qw)
+    s2 = torch.empty_like(sw)
+    sq.sq_rotate_quantize(torch.from_numpy(Wt).cuda(), L.giv_i, L.giv_j, L.giv_theta, R1, R2, Q2, s2)
+    torch.cuda.synchronize()
+    assert torch.equal(Q2, Qw) and torch.equal(s2, sw)
+    # the prepared weights drive the GEMM
+    Qx, sx, _ = run_rotate_quantize(L, want_xrot=False)
+    Yg, accg = run_gemm(Qx, sx, Qw.cpu().numpy(), sw.cpu().numpy())
+    _, acco = oracle.gemm(Qx, sx, Qw.cpu().numpy(), sw.cpu().numpy())
+    assert np.array_equal(accg, acco)
