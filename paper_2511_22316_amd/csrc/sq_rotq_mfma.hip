@@ -179,6 +179,37 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
     // rows 8(e/4) + 4g + e%4).  That is the row order stage B wants.  Stage A wants rows 8g + e
     // per step, which is the same order with bits 2 and 3 of the row swapped, so the lanes of
     // operand A fetch their rows in that swapped order.
+    // declared here, filled in once the plan entries have arrived
+    int my_level = -1, gs_tile[2] = {-1, -1}, gs_lo[2] = {0, 0};
+
+    // lead wave: Givens list on the tile in ring slot `slot`, side tile `lo_sel`
+    auto givens = [&](int slot, int lo_sel) {
+        if (plan.n_slots == 0) return;
+        char *xt = lds + S::OFF_X + (tok_slot * NSX + slot) * S::TILE_BYTES;
+        char *lo_t = lds + S::OFF_LO + (tok_slot * 2 + lo_sel) * lo_bytes;
+        float *gv = reinterpret_cast<float *>(lds + off_gv) + tok_slot * kRotqMaxSlots;
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+            if (gs_tile[u] >= 0) gv[lane + 64 * u] = __half2float(*reinterpret_cast<const __half *>(xt + gs_tile[u]));
+        for (int lv = 0; lv < plan.n_levels; ++lv) {
+            __builtin_amdgcn_wave_barrier();     // LDS traffic of one wave stays in program order
+            if (my_level == lv) {                // lane l owns pair l of the level-sorted list
+                const float a = gv[my_si], b = gv[my_sj];
+                gv[my_si] = a * my_c + b * my_s;
+                gv[my_sj] = b * my_c - a * my_s;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+            if (gs_tile[u] >= 0) {
+                const float v = gv[lane + 64 * u];
+                const __half hi = __float2half_rn(v);
+                *reinterpret_cast<__half *>(xt + gs_tile[u]) = hi;
+                *reinterpret_cast<__half *>(lo_t + gs_lo[u]) = __float2half_rn(v - __half2float(hi));
+            }
+    };
+
     v8h r2f[KSA], r2x[QS_MAX], r1f[MB][KSB];
     {
         v8h sel[2];                       // identity slices: B[k][n] = (16kk + k == n), k = 8g + e
@@ -269,6 +300,30 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
             rawx[xb][1] = chunk(r2col + qrow[xb] * N2, C16{}, CN2{});
         }
         __builtin_amdgcn_sched_barrier(0);              // every request is out before the first use
+        // While those requests are in flight: zeros where nothing is ever loaded, then the lead wave
+        // rotates the first row.  Row one was requested before the plan entries and loads complete in
+        // order, so it has landed once the entries are here.  The barrier is the bare instruction:
+        // the fence of __syncthreads would wait for every load above.  (Zeros: padding rows p >= N1
+        // of every ring tile, and the side tiles.)
+        if (N1P > N1) {
+            constexpr int PAD_CHUNKS = (N1P - N1) * CPRX;
+            for (int c = tid; c < TPP * NSX * PAD_CHUNKS; c += 256) {
+                const int tile = c / PAD_CHUNKS, r = c % PAD_CHUNKS;
+                *reinterpret_cast<uint4 *>(lds + S::OFF_X + tile * S::TILE_BYTES + (N1 * CPRX + r) * 16) = uint4{0, 0, 0, 0};
+            }
+        }
+        for (int c = tid; c < TPP * 2 * lo_bytes / 16; c += 256)
+            *reinterpret_cast<uint4 *>(lds + S::OFF_LO + c * 16) = uint4{0, 0, 0, 0};
+
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        my_level = (my_level_raw == 0xFF) ? -1 : my_level_raw;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int p = my_chan[u] / N2, q = my_chan[u] % N2, qs = my_qslot[u];
+            gs_tile[u] = (lane + 64 * u < plan.n_slots) ? (p * CPRX + ((q >> 3) ^ swz<CPRX>(p))) * 16 + (q & 7) * 2 : -1;
+            gs_lo[u] = (qs >> 4) * S::LO_STEP_BYTES + p * 32 + (qs & 15) * 2;
+        }
+        if (lead) givens(0, 0);
 #pragma unroll
         for (int blk = 0; blk < N2 / 32; ++blk) {
             const v16f c = block_t(raw2[blk][0], raw2[blk][1]);
@@ -297,52 +352,6 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
         issue_row(g0 + stride, 1);
         issue_row(g0 + 2 * stride, 2);
     }
-    const int my_level = (my_level_raw == 0xFF) ? -1 : my_level_raw;
-    int gs_tile[2], gs_lo[2];
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-        const int p = my_chan[u] / N2, q = my_chan[u] % N2, qs = my_qslot[u];
-        gs_tile[u] = (lane + 64 * u < plan.n_slots) ? (p * CPRX + ((q >> 3) ^ swz<CPRX>(p))) * 16 + (q & 7) * 2 : -1;
-        gs_lo[u] = (qs >> 4) * S::LO_STEP_BYTES + p * 32 + (qs & 15) * 2;
-    }
-    // zeros where nothing is ever loaded: padding rows p >= N1 of every ring tile, and the side tiles
-    if (N1P > N1) {
-        constexpr int PAD_CHUNKS = (N1P - N1) * CPRX;
-        for (int c = tid; c < TPP * NSX * PAD_CHUNKS; c += 256) {
-            const int tile = c / PAD_CHUNKS, r = c % PAD_CHUNKS;
-            *reinterpret_cast<uint4 *>(lds + S::OFF_X + tile * S::TILE_BYTES + (N1 * CPRX + r) * 16) = uint4{0, 0, 0, 0};
-        }
-    }
-    for (int c = tid; c < TPP * 2 * lo_bytes / 16; c += 256)
-        *reinterpret_cast<uint4 *>(lds + S::OFF_LO + c * 16) = uint4{0, 0, 0, 0};
-
-    // lead wave: Givens list on the tile in ring slot `slot`, side tile `lo_sel`
-    auto givens = [&](int slot, int lo_sel) {
-        if (plan.n_slots == 0) return;
-        char *xt = lds + S::OFF_X + (tok_slot * NSX + slot) * S::TILE_BYTES;
-        char *lo_t = lds + S::OFF_LO + (tok_slot * 2 + lo_sel) * lo_bytes;
-        float *gv = reinterpret_cast<float *>(lds + off_gv) + tok_slot * kRotqMaxSlots;
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-            if (gs_tile[u] >= 0) gv[lane + 64 * u] = __half2float(*reinterpret_cast<const __half *>(xt + gs_tile[u]));
-        for (int lv = 0; lv < plan.n_levels; ++lv) {
-            __builtin_amdgcn_wave_barrier();     // LDS traffic of one wave stays in program order
-            if (my_level == lv) {                // lane l owns pair l of the level-sorted list
-                const float a = gv[my_si], b = gv[my_sj];
-                gv[my_si] = a * my_c + b * my_s;
-                gv[my_sj] = b * my_c - a * my_s;
-            }
-        }
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-            if (gs_tile[u] >= 0) {
-                const float v = gv[lane + 64 * u];
-                const __half hi = __float2half_rn(v);
-                *reinterpret_cast<__half *>(xt + gs_tile[u]) = hi;
-                *reinterpret_cast<__half *>(lo_t + gs_lo[u]) = __float2half_rn(v - __half2float(hi));
-            }
-    };
 
     // LDS byte offsets of this lane's operand chunks inside a tile (row block 0): the swizzle
     // only touches the low bits of the chunk index, so four offsets cover every step
@@ -390,14 +399,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
     };
 
     // ---- pipeline prologue: first row rotated, its stage A done -------------------------------
-    __syncthreads();                       // zeros are in place before the first side-tile writes
-    if (lead) {
-        if (has_row(g0 + 2 * stride)) wait_loads_le<2 * LPT>();
-        else if (has_row(g0 + stride)) wait_loads_le<LPT>();
-        else wait_loads_le<0>();
-        givens(0, 0);
-    }
-    __syncthreads();
+    __syncthreads();                       // first row rotated
     stage_a(0, 0, [](int) {});
 
     int slot = 0, it = 0;
