@@ -269,10 +269,10 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
         using C16 = std::integral_constant<int, 16>;
         using CN2 = std::integral_constant<int, N2>;
         using CN1 = std::integral_constant<int, N1>;
-        v8h raw2[N2 / 32][2], rawx[QS_MAX / 2][2], raw1[MB][MB][2];
-        int qrow[QS_MAX / 2];
+        v8h raw2[N2 / 32][2], raw1[MB][MB][2];
+        int qrow[QS_MAX / 2];             // row of R2 that q-slot 32xb + lsw repairs, -1 behind the end
 #pragma unroll
-        for (int xb = 0; xb < QS_MAX / 2; ++xb) qrow[xb] = plan.qlist[32 * xb + lsw];   // 0 behind the end
+        for (int xb = 0; xb < QS_MAX / 2; ++xb) qrow[xb] = plan.qlist[32 * xb + lsw];
 #pragma unroll
         for (int blk = 0; blk < N2 / 32; ++blk) {
             raw2[blk][0] = chunk(r2col + (32 * blk + lsw) * N2, C0{}, CN2{});
@@ -294,11 +294,6 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
                     raw1[nb][blk][1] = chunk(row, std::integral_constant<int, 80>{}, CN1{});
                 }
             }
-#pragma unroll
-        for (int xb = 0; xb < QS_MAX / 2; ++xb) {       // after the others: the row numbers come out of the plan
-            rawx[xb][0] = chunk(r2col + qrow[xb] * N2, C0{}, CN2{});
-            rawx[xb][1] = chunk(r2col + qrow[xb] * N2, C16{}, CN2{});
-        }
         __builtin_amdgcn_sched_barrier(0);              // every request is out before the first use
         // While those requests are in flight: zeros where nothing is ever loaded, then the lead wave
         // rotates the first row.  Row one was requested before the plan entries and loads complete in
@@ -339,12 +334,31 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
                 r1f[nb][2 * blk] = to_frag(c, 0);
                 r1f[nb][2 * blk + 1] = to_frag(c, 1);
             }
+        // The rows of R2 that repair the Givens rounding (one per q-slot) are picked out of the
+        // blocks just built, again on the matrix cores and again exactly: operand A holds a single
+        // 1 per row, at column qlist[slot], and operand B is R2 as stage A uses it.  This saves
+        // a second trip to memory behind the plan entries.
 #pragma unroll
         for (int xb = 0; xb < QS_MAX / 2; ++xb) {
-            const bool keep = 32 * xb + lsw < plan.n_qslots;
-            const v16f c = block_t(zero_unless(keep, rawx[xb][0]), zero_unless(keep, rawx[xb][1]));
-            r2x[2 * xb] = to_frag(c, 0);
-            r2x[2 * xb + 1] = to_frag(c, 1);
+            if (32 * xb < plan.n_qslots) {
+                const int q = (32 * xb + lsw < plan.n_qslots) ? qrow[xb] : -1;
+                v16f c;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) c[e] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < KSA; ++ks) {
+                    const int d = q - 16 * ks - 8 * g;          // element of this lane's eight that is 1
+                    const uint32_t one = ((uint32_t)d < 8u) ? (0x3C00u << (16 * (d & 1))) : 0u;
+                    const v4u a = {(d >> 1) == 0 ? one : 0u, (d >> 1) == 1 ? one : 0u,
+                                   (d >> 1) == 2 ? one : 0u, (d >> 1) == 3 ? one : 0u};
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a), r2f[ks], c, 0, 0, 0);
+                }
+                r2x[2 * xb] = to_frag(c, 0);
+                r2x[2 * xb + 1] = to_frag(c, 1);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) r2x[2 * xb][e] = r2x[2 * xb + 1][e] = (_Float16)0.f;
+            }
         }
     }
 
