@@ -385,58 +385,67 @@ __global__ __launch_bounds__(WM *WN *kWave, OCC) void w4a4_gemm_kernel(
 }
 
 // ------------------------------------------------------------------------------------------
-// Skinny kernel (T <= 32, K % 256 == 0): the decode-shaped product, bound by the one pass over the
-// weights.  A workgroup owns 32*FN output channels; its NW waves split K between them
-// (256-code slices dealt round-robin) and add their partial accumulators through LDS at the end.
-// Operands go straight from global memory to registers: a lane reads 64 contiguous bytes of its
-// row per slice as four 16-byte loads, so each wave-wide group of four loads consumes whole
-// 128-byte lines, and the loads of the next slice are in flight while this one is multiplied.
+// Skinny kernel (T <= 32*FM <= 64, K % 256 == 0): the decode-shaped product, bound by the one
+// pass over the weights.  A workgroup owns 32*FN output channels and all tokens; its NW waves
+// split K between them (256-code slices dealt round-robin) and add their partial accumulators
+// through LDS at the end.  Operands go straight from global memory to registers: a lane reads 64
+// contiguous bytes of its row per slice as four 16-byte loads, so each wave-wide group of four
+// loads consumes whole 128-byte lines, and the loads of the next slice are in flight while this
+// one is multiplied.
 // ------------------------------------------------------------------------------------------
-template <int FN, int NW>
+template <int FM, int FN, int NW>
 __global__ __launch_bounds__(NW *kWave) void w4a4_gemm_skinny_kernel(
     const uint8_t *__restrict__ Qx, const float *__restrict__ sx, int T, int Kb,
     const uint8_t *__restrict__ Qw, const float *__restrict__ sw, int N, __half *__restrict__ Y,
     int64_t ldy, int32_t *__restrict__ acc_dbg)
 {
     constexpr int BN = 32 * FN, SLICE = 128;        // bytes of a row per slice (256 codes)
-    __shared__ int red[NW][FN][16][kWave];
+    static_assert(NW * FM * FN * 16 * kWave * 4 <= 64 * 1024, "partial sums must fit in static LDS");
+    __shared__ int red[NW][FM][FN][16][kWave];
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int l32 = lane & 31, g = lane >> 5;
     const int col0 = blockIdx.x * BN;
 
     // rows past the ends are clamped: their products are never stored
-    const uint8_t *a_ptr = Qx + (int64_t)min(l32, T - 1) * Kb + g * 64;
+    const uint8_t *a_ptr[FM];
     const uint8_t *b_ptr[FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i) a_ptr[i] = Qx + (int64_t)min(32 * i + l32, T - 1) * Kb + g * 64;
 #pragma unroll
     for (int j = 0; j < FN; ++j) b_ptr[j] = Qw + (int64_t)min(col0 + 32 * j + l32, N - 1) * Kb + g * 64;
 
-    v16i acc[FN];
+    v16i acc[FM][FN];
 #pragma unroll
-    for (int j = 0; j < FN; ++j)
+    for (int i = 0; i < FM; ++i)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[j][e] = 0;
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
 
-    uint4 ra[2][4], rb[2][FN][4];
+    uint4 ra[2][FM][4], rb[2][FN][4];
     const int slices = Kb / SLICE;
 #define SQ_SKINNY_FETCH(BUF, S)                                                                      \
     do {                                                                                             \
         const int off_ = (S) * SLICE;                                                                \
-        _Pragma("unroll") for (int c = 0; c < 4; ++c)                                                \
-            ra[BUF][c] = *reinterpret_cast<const uint4 *>(a_ptr + off_ + 16 * c);                    \
         _Pragma("unroll") for (int j = 0; j < FN; ++j)                                               \
             _Pragma("unroll") for (int c = 0; c < 4; ++c)                                            \
                 rb[BUF][j][c] = *reinterpret_cast<const uint4 *>(b_ptr[j] + off_ + 16 * c);          \
+        _Pragma("unroll") for (int i = 0; i < FM; ++i)                                               \
+            _Pragma("unroll") for (int c = 0; c < 4; ++c)                                            \
+                ra[BUF][i][c] = *reinterpret_cast<const uint4 *>(a_ptr[i] + off_ + 16 * c);          \
     } while (0)
 #define SQ_SKINNY_MULTIPLY(BUF)                                                                      \
     do {                                                                                             \
         _Pragma("unroll") for (int c = 0; c < 4; ++c) {                                              \
-            v4i a0, a1;                                                                              \
-            widen_chunk(ra[BUF][c], a0, a1);                                                         \
-            _Pragma("unroll") for (int j = 0; j < FN; ++j) {                                         \
-                v4i b0, b1;                                                                          \
-                widen_chunk(rb[BUF][j][c], b0, b1);                                                  \
-                acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b0, acc[j], 0, 0, 0);             \
-                acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b1, acc[j], 0, 0, 0);             \
+            v4i b0[FN], b1[FN];                                                                      \
+            _Pragma("unroll") for (int j = 0; j < FN; ++j) widen_chunk(rb[BUF][j][c], b0[j], b1[j]); \
+            _Pragma("unroll") for (int i = 0; i < FM; ++i) {                                         \
+                v4i a0, a1;                                                                          \
+                widen_chunk(ra[BUF][i][c], a0, a1);                                                  \
+                _Pragma("unroll") for (int j = 0; j < FN; ++j) {                                     \
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b0[j], acc[i][j], 0, 0, 0); \
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b1[j], acc[i][j], 0, 0, 0); \
+                }                                                                                    \
             }                                                                                        \
         }                                                                                            \
     } while (0)
@@ -457,18 +466,20 @@ __global__ __launch_bounds__(NW *kWave) void w4a4_gemm_skinny_kernel(
 #undef SQ_SKINNY_MULTIPLY
 
 #pragma unroll
-    for (int j = 0; j < FN; ++j)
+    for (int i = 0; i < FM; ++i)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) red[wave][j][e][lane] = acc[j][e];
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) red[wave][i][j][e][lane] = acc[i][j][e];
     __syncthreads();
     // accumulator layout: lane holds channel (lane % 32); register e holds token
     // 8 * (e / 4) + 4 * (lane / 32) + e % 4.  The sums carry the factor 256 of the widening.
-    for (int idx = tid; idx < FN * 16 * kWave; idx += NW * kWave) {
-        const int ln = idx & (kWave - 1), e = (idx >> 6) & 15, j = idx >> 10;
+    for (int idx = tid; idx < FM * FN * 16 * kWave; idx += NW * kWave) {
+        const int ln = idx & (kWave - 1), e = (idx >> 6) & 15, j = (idx >> 10) % FN, i = (idx >> 10) / FN;
         int sum = 0;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) sum += red[w][j][e][ln];
-        const int t = 8 * (e / 4) + 4 * (ln >> 5) + (e % 4), n = col0 + 32 * j + (ln & 31);
+        for (int w = 0; w < NW; ++w) sum += red[w][i][j][e][ln];
+        const int t = 32 * i + 8 * (e / 4) + 4 * (ln >> 5) + (e % 4), n = col0 + 32 * j + (ln & 31);
         if (t < T && n < N) {
             Y[(int64_t)t * ldy + n] = __float2half_rn((float)sum * (sx[t] * 0.00390625f) * sw[n]);
             if (acc_dbg != nullptr) acc_dbg[(int64_t)t * N + n] = sum >> 8;
@@ -593,12 +604,12 @@ static sq_status launch_main(const uint8_t *Qx, const float *sx, int T, int K, c
     return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
-template <int FN, int NW>
+template <int FM, int FN, int NW>
 static sq_status launch_skinny(const uint8_t *Qx, const float *sx, int T, int K, const uint8_t *Qw,
                                const float *sw, int N, __half *Y, int64_t ldy, int32_t *acc_dbg,
                                hipStream_t st)
 {
-    hipLaunchKernelGGL((w4a4_gemm_skinny_kernel<FN, NW>), dim3((unsigned)((N + 32 * FN - 1) / (32 * FN))),
+    hipLaunchKernelGGL((w4a4_gemm_skinny_kernel<FM, FN, NW>), dim3((unsigned)((N + 32 * FN - 1) / (32 * FN))),
                        dim3(NW * kWave), 0, st, Qx, sx, T, K / 2, Qw, sw, N, Y, ldy, acc_dbg);
     return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
@@ -630,16 +641,22 @@ extern "C" sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T,
     hipStream_t st = static_cast<hipStream_t>(stream);
     __half *Yh = static_cast<__half *>(Y);
     if ((K % 256) != 0) return sq::launch_generic(Qx, sx, (int)T, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
-    // Tile choice.  Both variants run eight waves per CU (two per SIMD): the VALU work of widening
-    // nibbles issues nearly twice as fast from two waves as from one.  Large problems take 256x256
-    // tiles (64x128 per wave: fewer VALU ops per MFMA); smaller ones take 128x256 tiles so that
-    // every CU gets work.  SQ_GEMM_TILE=0..11 overrides the choice (tuning aid).
+    // Kernel choice, from few tokens to many.  The two large tile shapes run eight waves per CU
+    // (two per SIMD): the VALU work of widening nibbles issues nearly twice as fast from two waves
+    // as from one.  Large problems take 256x256 tiles (64x128 per wave: fewer VALU ops per MFMA);
+    // smaller ones take 128x256 tiles so that every CU gets work.  SQ_GEMM_TILE=0..13 overrides the choice (tuning aid).
     static const int forced = [] { const char *e = getenv("SQ_GEMM_TILE"); return e ? atoi(e) : -1; }();
     const int Ti = (int)T;
     int choice = forced;
-    // at most 32 tokens: one pass over the weights.  64 channels per workgroup and K split four
-    // ways if that already puts about eight waves on every CU, else 32 channels and a wider split.
+    // At most 64 tokens: one pass over the weights by the decode-shaped kernel; its launch shape
+    // (token blocks, channels per workgroup, K split) keeps about eight waves on every CU.
     if (choice < 0 && Ti <= 32) choice = (N >= 64 * 384) ? 8 : (N >= 32 * 256 ? 9 : 7);
+    if (choice < 0 && Ti <= 64) choice = (N >= 32 * 256) ? 12 : 13;
+    // Up to a few hundred tokens 128x256 tiles would leave CUs idle: 128x128 tiles (four waves).
+    if (choice < 0) {
+        const int64_t wide = (int64_t)((Ti + 127) / 128) * ((N + 255) / 256);
+        if (wide <= 128) choice = (2 * wide <= 256) ? 5 : 2;
+    }
     if (choice < 0) choice = ((int64_t)((Ti + 255) / 256) * ((N + 255) / 256) >= 512) ? 4 : 1;
     switch (choice) {
         case 0: return sq::launch_main<2, 2, 2, 4, 128, 1>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
@@ -648,11 +665,11 @@ extern "C" sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T,
         case 4: return sq::launch_main<4, 2, 2, 4, 64, 1>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
         case 5: return sq::launch_main<2, 2, 2, 2, 128, 1>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
         case 6: return sq::launch_main<2, 4, 2, 2, 64, 1>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
-        case 7: if (Ti <= 32) return sq::launch_skinny<1, 16>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
-        case 8: if (Ti <= 32) return sq::launch_skinny<2, 4>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
-        case 9: if (Ti <= 32) return sq::launch_skinny<1, 8>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
-        case 10: if (Ti <= 32) return sq::launch_skinny<1, 4>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
-        case 11: if (Ti <= 32) return sq::launch_skinny<2, 8>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
+        case 7: if (Ti <= 32) return sq::launch_skinny<1, 1, 16>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
+        case 8: if (Ti <= 32) return sq::launch_skinny<1, 2, 4>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
+        case 9: if (Ti <= 32) return sq::launch_skinny<1, 1, 8>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
+        case 12: if (Ti <= 64) return sq::launch_skinny<2, 2, 4>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
+        case 13: if (Ti <= 64) return sq::launch_skinny<2, 1, 8>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
         default: break;
     }
     return sq::launch_main<2, 4, 2, 2, 128, 1>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);

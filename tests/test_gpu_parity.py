@@ -179,7 +179,11 @@ def test_rotate_quantize_identity_rotation_is_exact(oracle):
                                    (8, 1024, 520), (300, 2048, 130),
                                    # at most 32 tokens: the decode-shaped kernel in its three launch
                                    # shapes, one K slice only / ragged channel tails / T = 32
-                                   (1, 256, 33), (32, 768, 8200), (31, 512, 24600), (33, 512, 300)])
+                                   (1, 256, 33), (32, 768, 8200), (31, 512, 24600), (33, 512, 300),
+                                   # 33..128 tokens: the same kernel with two and four token blocks
+                                   (64, 768, 16500), (48, 512, 300), (100, 512, 260), (128, 256, 64),
+                                   # a few hundred tokens: 128x128 tiles
+                                   (129, 512, 520), (400, 768, 1000)])
 def test_gemm_random_codes_bit_exact(oracle, T, K, N):
     print(f"case gemm random codes T={T} K={K} N={N}", flush=True)
     g = np.random.default_rng(T * 7 + K + N)
