@@ -5,6 +5,10 @@
 #include <hip/hip_fp16.h>
 #include <stdint.h>
 
+#include <mutex>
+#include <utility>
+#include <vector>
+
 #include "singlequant.h"
 
 namespace sq {
@@ -59,11 +63,21 @@ __device__ __forceinline__ float wave_max(float v)
 // gfx950 has 160 KiB of LDS per workgroup; HIP needs an opt-in above 64 KiB of dynamic LDS.
 constexpr int kMaxDynamicLds = 160 * 1024 - 1024;
 
-// Opt a kernel in to large dynamic LDS, once per (kernel, device).  Host side.
+// Opt a kernel in to large dynamic LDS, once per (kernel, device); later calls only look the pair
+// up.  Host side, thread-safe.
 inline bool allow_large_lds(const void *kernel)
 {
-    return hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynamicLds) ==
-           hipSuccess;
+    static std::mutex guard;
+    static std::vector<std::pair<const void *, int>> done;
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess) return false;
+    std::lock_guard<std::mutex> lock(guard);
+    for (const auto &d : done)
+        if (d.first == kernel && d.second == device) return true;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDynamicLds) != hipSuccess)
+        return false;
+    done.emplace_back(kernel, device);
+    return true;
 }
 
 }  // namespace sq

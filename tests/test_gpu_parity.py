@@ -347,3 +347,42 @@ def test_prepare_weights_matches_oracle(oracle, name, N):
     Yg, accg = run_gemm(Qx, sx, Qw.cpu().numpy(), sw.cpu().numpy())
     _, acco = oracle.gemm(Qx, sx, Qw.cpu().numpy(), sw.cpu().numpy())
     assert np.array_equal(accg, acco)
+
+
+# ------------------------------------------------------------------ streams -----
+
+def test_layer_on_a_side_stream_matches_default_stream(oracle):
+    """Both calls enqueue on the stream they are given and nowhere else: a layer run on a side
+    stream, behind a long fill of its inputs on that stream, equals the run on the default one."""
+    print("case side stream", flush=True)
+    import torch
+    import paper_2511_22316_amd as sq
+    cfg = synth.CONFIGS["attn_proj"]
+    L = synth.layer(cfg, 300)
+    N = 384
+    Wt = synth.weights_t(cfg, N)
+    Qw_h, sw_h = oracle.prepare_weights(Wt, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)
+    dev = "cuda"
+    R1, R2 = torch.from_numpy(L.R1).to(dev), torch.from_numpy(L.R2).to(dev)
+    Qw, sw = torch.from_numpy(Qw_h).to(dev), torch.from_numpy(sw_h).to(dev)
+    Xh = torch.from_numpy(L.X).pin_memory()
+
+    def run(stream):
+        X = torch.empty((300, cfg.K), dtype=torch.float16, device=dev)
+        Q = torch.empty((300, cfg.K // 2), dtype=torch.uint8, device=dev)
+        s = torch.empty((300,), dtype=torch.float32, device=dev)
+        Y = torch.empty((300, N), dtype=torch.float16, device=dev)
+        with torch.cuda.stream(stream):
+            X.copy_(Xh, non_blocking=True)          # the kernels must wait for this copy: same stream
+            sq.sq_rotate_quantize(X, L.giv_i, L.giv_j, L.giv_theta, R1, R2, Q, s, stream=stream)
+            sq.sq_w4a4_gemm(Q, s, Qw, sw, Y, stream=stream)
+        stream.synchronize()
+        return Q.cpu().numpy(), s.cpu().numpy(), Y.cpu().numpy()
+
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    Q1, s1, Y1 = run(side)
+    Q0, s0, Y0 = run(torch.cuda.current_stream())
+    assert np.array_equal(Q0, Q1) and np.array_equal(s0, s1) and np.array_equal(Y0, Y1)
+    xo, Qo, so = _oracle_rq(oracle, L)
+    check_codes(Q1, s1, Qo, so)
