@@ -181,19 +181,6 @@ __global__ __launch_bounds__(WM *WN *kWave, OCC) void w4a4_gemm_kernel(
     for (int g = 0; g < B_LOADS; ++g)
         b_src[g] = Qw + (int64_t)min(col0 + RPL * (wave + NW * g) + lrow, N - 1) * Kb + lchunk * 16;
 
-    // The block's dequantization steps are parked in LDS behind the ring and the staged output
-    // tile, so that the epilogue does not wait on global memory: sx * 2^-8 for the BM tokens (the
-    // accumulators carry a factor 256), then sw for the BN output channels; 0 past the edges.
-    constexpr int SCALE_BYTE = (3 * STAGE_SLOTS * 16 > BM * (BN * 2 + 16)) ? 3 * STAGE_SLOTS * 16
-                                                                           : BM * (BN * 2 + 16);
-    float *scale_lds = reinterpret_cast<float *>(reinterpret_cast<char *>(smem) + SCALE_BYTE);
-    for (int r = tid; r < BM + BN; r += NT) {
-        float v;
-        if (r < BM) v = (row0 + r < T) ? sx[row0 + r] * 0.00390625f : 0.f;
-        else v = (col0 + r - BM < N) ? sw[col0 + r - BM] : 0.f;
-        scale_lds[r] = v;
-    }
-
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)smem;
     const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
     // loads of tile kt into ring stage `stage`, issued only if kt < limit
@@ -284,6 +271,20 @@ __global__ __launch_bounds__(WM *WN *kWave, OCC) void w4a4_gemm_kernel(
     // prologue: tiles 0 and 1 in flight, wait for tile 0, start tile 2, first fragments ready
     issue_tile(0, 0, ktiles);
     issue_tile(1, 1, ktiles);
+    // While the first tiles are on their way, the block's dequantization steps are parked in LDS
+    // behind the ring and the staged output tile, so that the epilogue does not wait on global
+    // memory: sx * 2^-8 for the BM tokens (the accumulators carry a factor 256), then sw for the
+    // BN output channels; 0 past the edges.
+    constexpr int SCALE_BYTE = (3 * STAGE_SLOTS * 16 > BM * (BN * 2 + 16)) ? 3 * STAGE_SLOTS * 16
+                                                                           : BM * (BN * 2 + 16);
+    float *scale_lds = reinterpret_cast<float *>(reinterpret_cast<char *>(smem) + SCALE_BYTE);
+    for (int r = tid; r < BM + BN; r += NT) {
+        float v;
+        if (r < BM) v = (row0 + r < T) ? sx[row0 + r] * 0.00390625f : 0.f;
+        else v = (col0 + r - BM < N) ? sw[col0 + r - BM] : 0.f;
+        scale_lds[r] = v;
+    }
+
     wait_loads_and_barrier<LOADS>(1, ktiles);
     issue_tile(2, 2, ktiles);
     read_step(0, 0);
