@@ -167,6 +167,42 @@ static bool build_rotq_plan(const GivensList &giv, int n2, RotqPlan &plan)
 
 }  // namespace sq
 
+// Test hook, not part of the public header: the launch plan the matrix-core kernel would get for a
+// Givens list, flattened into int32 arrays so that host-only tests can check the regrouping.
+// Returns the number of levels, or -1 if the list cannot be planned.  Every out array has room
+// for 2 * SQ_MAX_GIVENS entries.
+extern "C" int32_t sq_internal_rotq_plan(const int32_t *giv_i, const int32_t *giv_j, int32_t P, int32_t n2,
+                                         int32_t *n_slots, int32_t *n_qslots, int32_t *slot_chan,
+                                         int32_t *slot_qslot, int32_t *qslot_q, int32_t *pair_slot_i,
+                                         int32_t *pair_slot_j, int32_t *pair_level)
+{
+    if (P < 0 || P > SQ_MAX_GIVENS || n2 <= 0) return -1;
+    sq::GivensList giv;
+    giv.count = P;
+    for (int p = 0; p < P; ++p) {
+        giv.i[p] = giv_i[p];
+        giv.j[p] = giv_j[p];
+        giv.c[p] = (float)p;              // tags that let the test recover the list position of a sorted pair
+        giv.s[p] = 0.f;
+    }
+    sq::RotqPlan plan;
+    if (!sq::build_rotq_plan(giv, n2, plan)) return -1;
+    *n_slots = plan.n_slots;
+    *n_qslots = plan.n_qslots;
+    for (int s = 0; s < plan.n_slots; ++s) {
+        slot_chan[s] = plan.chan[s];
+        slot_qslot[s] = plan.qslot[s];
+    }
+    for (int q = 0; q < plan.n_qslots; ++q) qslot_q[q] = plan.qlist[q];
+    for (int k = 0; k < P; ++k) {         // sorted position k holds list position (int)c[k]
+        const int p = (int)plan.c[k];
+        pair_slot_i[p] = plan.pair_i[k];
+        pair_slot_j[p] = plan.pair_j[k];
+        pair_level[p] = plan.pair_level[k];
+    }
+    return plan.n_levels;
+}
+
 extern "C" sq_status sq_rotate_quantize(const void *X, int64_t T, int32_t K, int64_t ldx,
                                         const int32_t *giv_i, const int32_t *giv_j,
                                         const float *giv_theta, int32_t P, const void *R1,

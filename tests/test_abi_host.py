@@ -112,3 +112,66 @@ def test_prepare_weights_argument_errors(lib):
     assert _pw(lib, W=FAKE + 1) == 4
     assert _pw(lib, Qw=FAKE + 4) == 4
     assert _pw(lib, N=0) == 0                       # nothing to do, nothing enqueued
+
+
+# ------------------------------------------------------------------ launch plan of the Givens list -----
+
+def _plan(lib, gi, gj, n2):
+    gi, gj = np.asarray(gi, np.int32), np.asarray(gj, np.int32)
+    P = len(gi)
+    ns, nq = C.c_int32(), C.c_int32()
+    arr = lambda: np.full(128, -1, np.int32)
+    chan, qslot, qq, si, sj, lv = arr(), arr(), arr(), arr(), arr(), arr()
+    fn = lib.sq_internal_rotq_plan
+    fn.restype = C.c_int32
+    fn.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p] + [C.c_void_p] * 6
+    levels = fn(gi.ctypes.data, gj.ctypes.data, P, n2, C.addressof(ns), C.addressof(nq), chan.ctypes.data,
+                qslot.ctypes.data, qq.ctypes.data, si.ctypes.data, sj.ctypes.data, lv.ctypes.data)
+    return levels, ns.value, nq.value, chan, qslot, qq, si[:P], sj[:P], lv[:P]
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_givens_plan_keeps_list_order(lib, seed):
+    """The regrouping into levels must be equivalent to the list: slots name the touched channels
+    one to one, pairs of one level share no channel, and a pair sits in a later level than every
+    earlier pair it shares a channel with."""
+    g = np.random.default_rng(seed)
+    n2 = int(g.choice([32, 64, 128]))
+    K = n2 * int(g.choice([16, 64, 86]))
+    P = int(g.integers(1, 65))
+    pool = g.choice(K, size=int(g.integers(2, 2 * P + 1)), replace=False)     # small pools force reuse
+    gi = g.choice(pool, size=P)
+    gj = np.array([g.choice(pool[pool != a]) for a in gi])
+    levels, n_slots, n_qslots, chan, qslot, qq, si, sj, lv = _plan(lib, gi, gj, n2)
+    touched = sorted(set(gi.tolist()) | set(gj.tolist()))
+    assert levels >= 1 and n_slots == len(touched)
+    assert sorted(chan[:n_slots].tolist()) == touched
+    assert n_qslots == len({c % n2 for c in touched})
+    assert all(qq[qslot[s]] == chan[s] % n2 for s in range(n_slots))
+    assert all(chan[si[p]] == gi[p] and chan[sj[p]] == gj[p] for p in range(P))
+    assert lv.min() == 0 and lv.max() == levels - 1
+    for l in range(levels):
+        used = [c for p in range(P) if lv[p] == l for c in (gi[p], gj[p])]
+        assert len(used) == len(set(used)), "pairs of one level share a channel"
+    last = {}
+    for p in range(P):                                  # dependencies point to earlier levels
+        for c in (gi[p], gj[p]):
+            if c in last:
+                assert lv[p] > last[c]
+        last[gi[p]] = last[gj[p]] = lv[p]
+    # and no pair is pushed later than its dependencies force it to be
+    last = {}
+    for p in range(P):
+        need = 1 + max(last.get(gi[p], -1), last.get(gj[p], -1))
+        assert lv[p] == need
+        last[gi[p]] = last[gj[p]] = lv[p]
+
+
+def test_givens_plan_limits(lib):
+    levels, n_slots, n_qslots, *_ = _plan(lib, [], [], 64)
+    assert (levels, n_slots, n_qslots) == (0, 0, 0)
+    gi = np.arange(64) * 128                     # 128 channels in 128 different columns of an n2 = 128 view
+    gj = np.arange(64) * 128 + 64 + np.arange(64)
+    gi = gi + np.arange(64)
+    levels, n_slots, n_qslots, *_ = _plan(lib, gi, gj, 128)
+    assert levels == 1 and n_slots == 128 and n_qslots == 128
