@@ -2,7 +2,11 @@
 seeded inputs.  Element by element at sizes the oracle finishes in seconds; sampled rows,
 sampled elements and exact checksums at the full benchmark sizes."""
 import numpy as np
+import os
+
 import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 from paper_2511_22316_amd import synth
 from parity_util import (Y_ROW_TOL, check_codes, check_rotation, codes_of, half_ulp_distance,
@@ -158,6 +162,48 @@ def test_rotate_quantize_givens_list_touching_every_column(oracle, name):
     xo, Qo, so = _oracle_rq(oracle, L2)
     check_rotation(xg, xo)
     check_codes(Qg, sg, Qo, so)
+
+
+@pytest.mark.parametrize("n1,n2,P", [(32, 32, 8), (32, 64, 16), (80, 64, 24),      # matrix-core kernel
+                                     (24, 40, 6), (12, 8, 3), (128, 16, 10)])       # generic kernel
+def test_rotate_quantize_other_factor_shapes(oracle, n1, n2, P):
+    """Factor pairs beyond the five benchmark layers: the remaining instantiations of the
+    matrix-core kernel and shapes only the generic kernel takes."""
+    print(f"case rotate_quantize shape {n1}x{n2}", flush=True)
+    cfg = synth.LayerConfig(f"shape_{n1}x{n2}", 37, n1, n2, 64, P, "normal", 3, 300.0, 0.01, 20.0, 0.02, 4242 + n1 * n2)
+    L = synth.layer(cfg)
+    Qg, sg, xg = run_rotate_quantize(L)
+    xo, Qo, so = _oracle_rq(oracle, L)
+    check_rotation(xg, xo)
+    check_codes(Qg, sg, Qo, so)
+
+
+def test_rotate_quantize_generic_kernel_on_benchmark_shape(oracle):
+    """The generic kernel, forced on a shape the matrix-core kernel normally takes, must agree with
+    the oracle as well (it is the fallback for every shape without an instantiation)."""
+    print("case rotate_quantize generic kernel forced", flush=True)
+    import subprocess
+    import sys
+    import textwrap
+    # the switch is read once per process, so the forced run needs a process of its own
+    code = textwrap.dedent("""
+        import sys, numpy as np
+        sys.path[:0] = [%r, %r]
+        import oracle
+        from paper_2511_22316_amd import synth
+        from parity_util import run_rotate_quantize, check_rotation, check_codes
+        oracle.build()
+        L = synth.layer(synth.CONFIGS["attn_proj"], 20)
+        Qg, sg, xg = run_rotate_quantize(L)
+        xr = oracle.rotate(L.X, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)
+        Qo, so = oracle.quantize_rows(xr)
+        check_rotation(xg, xr)
+        check_codes(Qg, sg, Qo, so)
+        print("generic ok")
+    """) % (ROOT, os.path.join(ROOT, "tests"))
+    env = dict(os.environ, SQ_ROTQ_GENERIC="1")
+    r = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=110, cwd=ROOT)
+    assert r.returncode == 0 and "generic ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
 
 
 def test_rotate_quantize_identity_rotation_is_exact(oracle):
