@@ -432,3 +432,52 @@ def test_layer_on_a_side_stream_matches_default_stream(oracle):
     assert np.array_equal(Q0, Q1) and np.array_equal(s0, s1) and np.array_equal(Y0, Y1)
     xo, Qo, so = _oracle_rq(oracle, L)
     check_codes(Q1, s1, Qo, so)
+
+
+def test_layer_captured_in_a_graph_replays_correctly(oracle):
+    """Both calls can be recorded into a HIP graph (they allocate nothing and only launch
+    kernels): three replays, each on fresh contents of the static input buffer and with eager
+    work and a synchronization in between, equal the eager results bit for bit."""
+    print("case graph capture", flush=True)
+    import torch
+    import paper_2511_22316_amd as sq
+    cfg = synth.CONFIGS["attn_proj"]
+    T, N = 260, 512
+    L = synth.layer(cfg, T)
+    Wt = synth.weights_t(cfg, N)
+    dev = "cuda"
+    R1, R2 = torch.from_numpy(L.R1).to(dev), torch.from_numpy(L.R2).to(dev)
+    Qw = torch.empty((N, cfg.K // 2), dtype=torch.uint8, device=dev)
+    sw = torch.empty((N,), dtype=torch.float32, device=dev)
+    sq.sq_rotate_quantize(torch.from_numpy(Wt).to(dev), L.giv_i, L.giv_j, L.giv_theta, R1, R2, Qw, sw)
+    X = torch.from_numpy(L.X).to(dev)
+    Xin = torch.empty_like(X)                       # static buffers of the graph
+    Q = torch.empty((T, cfg.K // 2), dtype=torch.uint8, device=dev)
+    s = torch.empty((T,), dtype=torch.float32, device=dev)
+    Y = torch.empty((T, N), dtype=torch.float16, device=dev)
+
+    def layer(stream):
+        sq.sq_rotate_quantize(Xin, L.giv_i, L.giv_j, L.giv_theta, R1, R2, Q, s, stream=stream)
+        sq.sq_w4a4_gemm(Q, s, Qw, sw, Y, stream=stream)
+
+    side = torch.cuda.Stream()
+    Xin.copy_(X)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):                   # warm-up outside capture (one-time kernel attributes)
+        layer(side)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        layer(side)
+    for shift in (0, 7, 101):
+        Xs = torch.roll(X, shift, 0).contiguous()
+        Xin.copy_(Xs)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (Q.clone(), s.clone(), Y.clone())
+        Qe, se, Ye = torch.empty_like(Q), torch.empty_like(s), torch.empty_like(Y)   # eager, other buffers
+        sq.sq_rotate_quantize(Xs, L.giv_i, L.giv_j, L.giv_theta, R1, R2, Qe, se)
+        sq.sq_w4a4_gemm(Qe, se, Qw, sw, Ye)
+        torch.cuda.synchronize()
+        assert torch.equal(got[0], Qe) and torch.equal(got[1], se) and torch.equal(got[2], Ye), f"replay with shift {shift}"
