@@ -161,11 +161,18 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
     // This lane's plan entries are requested now and used after the rotation blocks are built.
     // Lane l owns pair l of the level-sorted Givens list (its slots, angle and level) and two of
     // the touched channels (slots l and l + 64) for the gather / scatter around the list.
-    const int my_level_raw = plan.pair_level[lane];
-    const int my_si = plan.pair_i[lane], my_sj = plan.pair_j[lane];
-    const float my_c = plan.c[lane], my_s = plan.s[lane];
-    const int my_chan[2] = {plan.chan[lane], plan.chan[lane + 64]};
-    const int my_qslot[2] = {plan.qslot[lane], plan.qslot[lane + 64]};
+    // The first Givens pass below relies on these loads being issued after the row request above
+    // (loads complete in order, so the row has landed once they have).  Their index therefore
+    // carries a zero that exists only after that request: volatile statements keep their order,
+    // and the loads cannot move ahead of a value they depend on.
+    int after_row_request;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(after_row_request));
+    const int pl = lane + after_row_request;
+    const int my_level_raw = plan.pair_level[pl];
+    const int my_si = plan.pair_i[pl], my_sj = plan.pair_j[pl];
+    const float my_c = plan.c[pl], my_s = plan.s[pl];
+    const int my_chan[2] = {plan.chan[pl], plan.chan[pl + 64]};
+    const int my_qslot[2] = {plan.qslot[pl], plan.qslot[pl + 64]};
 
     // R2 (stage A, operand B): lane holds column q' = 32cb + l32, step ks, element e <-> row
     // q = 16ks + 8g + e.  R1 (stage B, operand B): lane holds column p' = 32nb + l32; step ks,
