@@ -232,7 +232,7 @@ extern "C" sq_status sq_rotate_quantize(const void *X, int64_t T, int32_t K, int
     if (T == 0) return SQ_OK;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
-    // matrix-core kernel for the shapes it covers (n2 in {32, 64, 128}, n1 <= 96); the plain-FMA
+    // matrix-core kernel for the shapes it covers (n2 in {32, 64, 128}, n1 <= 128); the plain-FMA
     // kernel takes every other shape.  SQ_ROTQ_GENERIC=1 forces the latter (tuning aid).
     static const bool force_generic = [] { const char *e = getenv("SQ_ROTQ_GENERIC"); return e && e[0] == '1'; }();
     sq::RotqPlan plan;

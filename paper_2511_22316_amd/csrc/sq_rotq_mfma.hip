@@ -94,13 +94,15 @@ struct RotqShape {
     static constexpr int OUT_UNITS = N2 / 4;      // 2-byte units (4 codes) per output row p'
     static constexpr int OUT_BYTES = OUT_UNITS * N1P * 2;             // staged as [unit][p']
     static constexpr int OFF_X = 0;                                   // [TPP][NSX][TILE]
-    static constexpr int OFF_LO = TPP * NSX * TILE_BYTES;             // [TPP][2][qsteps][LO_STEP]
+    static constexpr int OFF_LO = TPP * NSX * TILE_BYTES;             // [TPP][qsteps][LO_STEP]
     // after the side tiles (runtime size): [TPP][128] float, [TPP][4] float, [TPP][OUT]
     static constexpr int TAIL_BYTES = TPP * (kRotqMaxSlots * 4 + 16 + OUT_BYTES);
-    static constexpr int lds_bytes(int qsteps) { return OFF_LO + TPP * 2 * qsteps * LO_STEP_BYTES + TAIL_BYTES; }
+    static constexpr int lds_bytes(int qsteps) { return OFF_LO + TPP * qsteps * LO_STEP_BYTES + TAIL_BYTES; }
     static_assert(N2 == 32 || N2 == 64 || N2 == 128, "one to four waves per token");
-    static_assert(N1P <= 96, "at most three row blocks");
-    static_assert(2 * LPT < 64, "outstanding loads must fit the vmcnt counter");
+    static_assert(N1P <= 128, "at most four row blocks");
+    // two rows are in flight at most; at 64 outstanding loads the counter is full and the issue
+    // of the last one simply waits
+    static_assert(2 * LPT <= 64, "outstanding loads must fit the vmcnt counter");
 };
 
 // QS_MAX: repair steps of 16 q-slots each the kernel holds rotation rows for (4 or 8).
@@ -125,7 +127,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
 
     const int qsteps = (plan.n_qslots + 15) / 16;            // extra MFMA steps that repair the Givens rounding
     const int lo_bytes = qsteps * S::LO_STEP_BYTES;          // one side tile
-    const int off_gv = S::OFF_LO + TPP * 2 * lo_bytes;
+    const int off_gv = S::OFF_LO + TPP * lo_bytes;
     const int off_red = off_gv + TPP * kRotqMaxSlots * 4;
     const int off_out = off_red + TPP * 16;
 
@@ -189,11 +191,11 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
     // declared here, filled in once the plan entries have arrived
     int my_level = -1, gs_tile[2] = {-1, -1}, gs_lo[2] = {0, 0};
 
-    // lead wave: Givens list on the tile in ring slot `slot`, side tile `lo_sel`
-    auto givens = [&](int slot, int lo_sel) {
+    // lead wave: Givens list on the tile in ring slot `slot`; fills the token's side tile
+    auto givens = [&](int slot) {
         if (plan.n_slots == 0) return;
         char *xt = lds + S::OFF_X + (tok_slot * NSX + slot) * S::TILE_BYTES;
-        char *lo_t = lds + S::OFF_LO + (tok_slot * 2 + lo_sel) * lo_bytes;
+        char *lo_t = lds + S::OFF_LO + tok_slot * lo_bytes;
         float *gv = reinterpret_cast<float *>(lds + off_gv) + tok_slot * kRotqMaxSlots;
 #pragma unroll
         for (int u = 0; u < 2; ++u)
@@ -276,7 +278,30 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
         using C16 = std::integral_constant<int, 16>;
         using CN2 = std::integral_constant<int, N2>;
         using CN1 = std::integral_constant<int, N1>;
-        v8h raw2[N2 / 32][2], raw1[MB][MB][2];
+        // Up to three row blocks, all of R1 is requested at once.  With four, that would not fit
+        // the registers: the blocks of column block nb + 1 are requested while those of nb are
+        // transposed, in two alternating sets.
+        constexpr int RAW1_SETS = MB <= 3 ? MB : 2;
+        v8h raw2[N2 / 32][2], raw1[RAW1_SETS][MB][2];
+        auto load_raw1 = [&](int nb, v8h (&dst)[MB][2]) {
+#pragma unroll
+            for (int blk = 0; blk < MB; ++blk) {
+                const __half *row = R1 + min(32 * blk + l32, N1 - 1) * N1;
+                if (nb == 0) {
+                    dst[blk][0] = chunk(row, std::integral_constant<int, 0>{}, CN1{});
+                    dst[blk][1] = chunk(row, std::integral_constant<int, 16>{}, CN1{});
+                } else if (nb == 1) {
+                    dst[blk][0] = chunk(row, std::integral_constant<int, 32>{}, CN1{});
+                    dst[blk][1] = chunk(row, std::integral_constant<int, 48>{}, CN1{});
+                } else if (nb == 2) {
+                    dst[blk][0] = chunk(row, std::integral_constant<int, 64>{}, CN1{});
+                    dst[blk][1] = chunk(row, std::integral_constant<int, 80>{}, CN1{});
+                } else {
+                    dst[blk][0] = chunk(row, std::integral_constant<int, 96>{}, CN1{});
+                    dst[blk][1] = chunk(row, std::integral_constant<int, 112>{}, CN1{});
+                }
+            }
+        };
         int qrow[QS_MAX / 2];             // row of R2 that q-slot 32xb + lsw repairs, -1 behind the end
 #pragma unroll
         for (int xb = 0; xb < QS_MAX / 2; ++xb) qrow[xb] = plan.qlist[32 * xb + lsw];
@@ -286,21 +311,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
             raw2[blk][1] = chunk(r2col + (32 * blk + lsw) * N2, C16{}, CN2{});
         }
 #pragma unroll
-        for (int nb = 0; nb < MB; ++nb)
-#pragma unroll
-            for (int blk = 0; blk < MB; ++blk) {
-                const __half *row = R1 + min(32 * blk + l32, N1 - 1) * N1;
-                if (nb == 0) {
-                    raw1[0][blk][0] = chunk(row, std::integral_constant<int, 0>{}, CN1{});
-                    raw1[0][blk][1] = chunk(row, std::integral_constant<int, 16>{}, CN1{});
-                } else if (nb == 1) {
-                    raw1[nb][blk][0] = chunk(row, std::integral_constant<int, 32>{}, CN1{});
-                    raw1[nb][blk][1] = chunk(row, std::integral_constant<int, 48>{}, CN1{});
-                } else {
-                    raw1[nb][blk][0] = chunk(row, std::integral_constant<int, 64>{}, CN1{});
-                    raw1[nb][blk][1] = chunk(row, std::integral_constant<int, 80>{}, CN1{});
-                }
-            }
+        for (int nb = 0; nb < (MB <= 3 ? MB : 1); ++nb) load_raw1(nb, raw1[nb]);
         __builtin_amdgcn_sched_barrier(0);              // every request is out before the first use
         // While those requests are in flight: zeros where nothing is ever loaded, then the lead wave
         // rotates the first row.  Row one was requested before the plan entries and loads complete in
@@ -314,7 +325,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
                 *reinterpret_cast<uint4 *>(lds + S::OFF_X + tile * S::TILE_BYTES + (N1 * CPRX + r) * 16) = uint4{0, 0, 0, 0};
             }
         }
-        for (int c = tid; c < TPP * 2 * lo_bytes / 16; c += 256)
+        for (int c = tid; c < TPP * lo_bytes / 16; c += 256)
             *reinterpret_cast<uint4 *>(lds + S::OFF_LO + c * 16) = uint4{0, 0, 0, 0};
 
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -325,7 +336,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
             gs_tile[u] = (lane + 64 * u < plan.n_slots) ? (p * CPRX + ((q >> 3) ^ swz<CPRX>(p))) * 16 + (q & 7) * 2 : -1;
             gs_lo[u] = (qs >> 4) * S::LO_STEP_BYTES + p * 32 + (qs & 15) * 2;
         }
-        if (lead) givens(0, 0);
+        if (lead) givens(0);
 #pragma unroll
         for (int blk = 0; blk < N2 / 32; ++blk) {
             const v16f c = block_t(raw2[blk][0], raw2[blk][1]);
@@ -333,14 +344,18 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
             r2f[2 * blk + 1] = to_frag(c, 1);
         }
 #pragma unroll
-        for (int nb = 0; nb < MB; ++nb)
+        for (int nb = 0; nb < MB; ++nb) {
+            constexpr bool ALTERNATE = MB > 3;
+            const int set = ALTERNATE ? (nb & 1) : nb;
+            if (ALTERNATE && nb + 1 < MB) load_raw1(nb + 1, raw1[(nb + 1) & 1]);
 #pragma unroll
             for (int blk = 0; blk < MB; ++blk) {
                 const bool keep = 32 * blk + l32 < N1;
-                const v16f c = block_t(zero_unless(keep, raw1[nb][blk][0]), zero_unless(keep, raw1[nb][blk][1]));
+                const v16f c = block_t(zero_unless(keep, raw1[set][blk][0]), zero_unless(keep, raw1[set][blk][1]));
                 r1f[nb][2 * blk] = to_frag(c, 0);
                 r1f[nb][2 * blk + 1] = to_frag(c, 1);
             }
+        }
         // The rows of R2 that repair the Givens rounding (one per q-slot) are picked out of the
         // blocks just built, again on the matrix cores and again exactly: operand A holds a single
         // 1 per row, at column qlist[slot], and operand B is R2 as stage A uses it.  This saves
@@ -382,11 +397,11 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
     for (int j = 0; j < NJ; ++j) a_off[j] = (l32 * CPRX + ((2 * j + g) ^ swz<CPRX>(l32))) * 16;
     const int lo_off = (l32 * 2 + g) * 16;
 
-    // stage A of the token in ring slot `slot` / side tile `lo_sel`; after every UNIT_EVERY MFMAs
-    // one unit of `between(u)` is issued (the quantization of the previous token, or nothing)
+    // stage A of the token in ring slot `slot` (and its side tile); after MFMA m, `between(m)` is
+    // issued (quantization units of the previous token, or nothing)
     v16f accz[MB], accy[MB];
     constexpr int NMA = MB * KSA;
-    auto stage_a = [&](int slot, int lo_sel, auto between) {
+    auto stage_a = [&](int slot, auto between) {
         const char *xt = lds + S::OFF_X + (tok_slot * NSX + slot) * S::TILE_BYTES;
         auto a_at = [&](int m) {
             const int mb = m / KSA, ks = m % KSA;
@@ -406,7 +421,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
             a0 = a1;
             a1 = a2;
         }
-        const char *lo_t = lds + S::OFF_LO + (tok_slot * 2 + lo_sel) * lo_bytes;
+        const char *lo_t = lds + S::OFF_LO + tok_slot * lo_bytes;
 #pragma unroll
         for (int x = 0; x < QS_MAX; ++x) {
             if (x < qsteps) {
@@ -421,10 +436,14 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
 
     // ---- pipeline prologue: first row rotated, its stage A done -------------------------------
     __syncthreads();                       // first row rotated
-    stage_a(0, 0, [](int) {});
+    stage_a(0, [](int) {});
+    // One side tile per token serves every row: stage A of a row has read it before the barrier
+    // that ends an iteration, and the list of the next row writes it after that barrier.  Here,
+    // ahead of the first iteration, the same order needs a barrier of its own.
+    __syncthreads();
 
-    int slot = 0, it = 0;
-    for (int grp = g0; grp < groups; grp += stride, ++it) {
+    int slot = 0;
+    for (int grp = g0; grp < groups; grp += stride) {
         const int t = grp * TPP + tok_slot;
         const bool live = t < T;
         const int slot1 = (slot + 1 == NSX) ? 0 : slot + 1;
@@ -502,7 +521,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
         if (lead) {
             if (has_row(grp + 2 * stride)) wait_loads_le<LPT>();
             else wait_loads_le<0>();
-            if (has_row(grp + stride)) givens(slot1, (it + 1) & 1);
+            if (has_row(grp + stride)) givens(slot1);
         }
         __syncthreads();     // B2: maxima visible; next tile rotated; copy-out of the last token done
         // stage A of this token ran an iteration ago, so its ring slot is free for the row after next
@@ -544,7 +563,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
             }
             outq[(8 * cb + 2 * rg + g) * N1P + 32 * nb + l32] = (uint16_t)(w ^ 0x8888u);
         };
-        stage_a(slot1, (it + 1) & 1, [&](int m) {
+        stage_a(slot1, [&](int m) {
             // NU units spread over the NMA MFMAs
 #pragma unroll
             for (int u = 0; u < NU; ++u)
@@ -621,7 +640,11 @@ bool rotq_mfma_dispatch(const __half *X, int64_t ldx, int T, int n1, int n2, con
     SQ_ROTQ_CASE(64, 64)     // 4096
     SQ_ROTQ_CASE(80, 64)     // 5120
     SQ_ROTQ_CASE(64, 128)    // 8192
+    SQ_ROTQ_CASE(128, 64)    // 8192, the split Alg. 1 picks
     SQ_ROTQ_CASE(86, 128)    // 11008
+    SQ_ROTQ_CASE(108, 128)   // 13824
+    SQ_ROTQ_CASE(112, 128)   // 14336
+    SQ_ROTQ_CASE(128, 128)   // 16384
 #undef SQ_ROTQ_CASE
     return false;
 }

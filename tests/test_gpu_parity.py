@@ -165,6 +165,7 @@ def test_rotate_quantize_givens_list_touching_every_column(oracle, name):
 
 
 @pytest.mark.parametrize("n1,n2,P", [(32, 32, 8), (32, 64, 16), (80, 64, 24),      # matrix-core kernel
+                                     (128, 64, 32), (108, 128, 24), (112, 128, 64), (128, 128, 48),
                                      (24, 40, 6), (12, 8, 3), (128, 16, 10)])       # generic kernel
 def test_rotate_quantize_other_factor_shapes(oracle, n1, n2, P):
     """Factor pairs beyond the five benchmark layers: the remaining instantiations of the
@@ -176,6 +177,28 @@ def test_rotate_quantize_other_factor_shapes(oracle, n1, n2, P):
     xo, Qo, so = _oracle_rq(oracle, L)
     check_rotation(xg, xo)
     check_codes(Qg, sg, Qo, so)
+
+
+@pytest.mark.parametrize("n1,n2,wide_list", [(128, 64, False), (112, 128, True)])
+def test_rotate_quantize_four_row_blocks_many_tokens(oracle, n1, n2, wide_list):
+    """Shapes with four 32-row blocks (8192 = 128 x 64 is the split Alg. 1 picks; 14336 = 112 x 128)
+    with enough tokens that every workgroup walks its ring several times; sampled rows against
+    the oracle.  The second case carries a list whose channels fall on 128 different columns."""
+    print(f"case rotate_quantize shape {n1}x{n2} many tokens", flush=True)
+    T = 1700 if n2 == 64 else 900
+    cfg = synth.LayerConfig(f"shape_{n1}x{n2}_long", T, n1, n2, 64, 32, "normal", 3, 300.0, 0.01, 20.0, 0.02, 99 + n1)
+    L = synth.layer(cfg)
+    if wide_list:
+        g = np.random.default_rng(5 + n1)
+        chans = np.array([g.integers(0, n1) * n2 + q for q in g.permutation(n2)])
+        L = synth.Layer(cfg, L.X, chans[:64].astype(np.int32), chans[64:].astype(np.int32),
+                        g.uniform(-3.1, 3.1, 64).astype(np.float32), L.R1, L.R2, L.R1_f64, L.R2_f64)
+    Qg, sg, xg = run_rotate_quantize(L)
+    rows = np.unique(np.concatenate([[0, 1, T - 2, T - 1], np.random.default_rng(2).integers(0, T, 60)]))
+    xo, Qo, so = _oracle_rq(oracle, L, L.X[rows])
+    check_rotation(xg[rows], xo)
+    check_codes(Qg[rows], sg[rows], Qo, so)
+    assert np.all(np.max(np.abs(codes_of(Qg)), axis=1) == 7)
 
 
 def test_rotate_quantize_generic_kernel_on_benchmark_shape(oracle):
