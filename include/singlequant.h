@@ -130,6 +130,64 @@ sq_status sq_prepare_weights(const void *W, int32_t K, int32_t N, int64_t ldw,
                              void *workspace, uint8_t *Qw, float *sw,
                              void *stream);
 
+/*
+ * sq_kron_factor -- Kronecker dimension factorization (Alg. 1): n2 is the power
+ * of two dividing n that lies closest to sqrt(n) (of two equally close ones the
+ * smaller), n1 = n / n2.  Host only; n >= 1.
+ */
+sq_status sq_kron_factor(int32_t n, int32_t *n1, int32_t *n2);
+
+/*
+ * sq_build_rotation -- the closed-form construction of the rotation from one
+ * batch of calibration activations (Sec. 4.2; no gradients, no iterations).
+ * What is computed, in this order (the points the paper leaves open are marked
+ * "reading"):
+ *   1. Calibration vector c: the row of X with the largest |entry|, the lowest
+ *      such row among equals (reading).
+ *   2. ART, P steps ("Alignment Rotation Transformation"; several steps as in
+ *      the paper's study of the number of ART steps): i = channel of largest
+ *      |c|, j = channel of smallest |c| other than i (lowest channel among
+ *      equals), theta = atan2(c_j, c_i) - pi/4 (Lemma 1), after which c_i and
+ *      c_j both hold sqrt(c_i^2 + c_j^2) / sqrt(2).  The pairs index the
+ *      K-channel space and are returned as the Givens list sq_rotate_quantize
+ *      takes; they are not folded into a Kronecker factor (reading).
+ *   3. URT ("Uniformity Rotation Transformation") for each side, from a vector
+ *      V: uniform target U = template q_k = (2k - n - 1)/n handed out by the
+ *      rank order of V (ascending, lower index first among equals) and scaled
+ *      to ||V||; R_map, R'_map = n - 1 plane rotations each that take V and U
+ *      to ||V|| e_1, entry k being zeroed in the plane (k-1, k), k = n-1 .. 1
+ *      (reading: the paper leaves the chain open); R^U = R_map R'_map^T, so
+ *      that V R^U = U.  Side vectors (reading): with C the n1 x n2 view of c
+ *      after step 2, V1 = row means of C, V2 = column means of C.
+ *   4. Composition ("The Overall SingleQuant Method"): R1 = R^U(V1),
+ *      R2 = H R^U(V2 H), H the normalised Sylvester Hadamard matrix.  Reading:
+ *      the paper prints the left factor transposed, for matrices acting on
+ *      column vectors; with rows acted on as in Eq. 18 (R1 enters as R1^T) the
+ *      factor that sends the columns of C to their uniform target is R^U
+ *      itself.
+ * Index decisions (steps 1, 2 and the rank order of step 3) are taken on fp32
+ * values rounded once per operation in index order; matrices are fp32, rounded
+ * to fp16 at the end.
+ *
+ *   X          device, fp16 [T, ldx], T >= 1; rows 16-byte aligned (ldx % 8 == 0)
+ *   n1, n2     2 <= n1 <= 128; n2 a power of two, 8 <= n2 <= 256; K = n1*n2 <= 16384
+ *   P          0 .. 64 ART steps
+ *   giv_i/j    device out, int32 [P]; giv_theta device out, float [P].  Copy them
+ *              to the host (after the stream has passed this call) to hand them
+ *              to sq_rotate_quantize / sq_prepare_weights.  May be NULL if P == 0.
+ *   R1, R2     device out, fp16 [n1,n1] and [n2,n2], row-major
+ *   workspace  device, sq_build_rotation_workspace_bytes(T, n1, n2) bytes, 16-byte
+ *              aligned, caller-owned; free to reuse once the stream has passed
+ *              the call
+ */
+sq_status sq_build_rotation(const void *X, int64_t T, int32_t K, int64_t ldx,
+                            int32_t n1, int32_t n2, int32_t P,
+                            int32_t *giv_i, int32_t *giv_j, float *giv_theta,
+                            void *R1, void *R2, void *workspace, void *stream);
+
+/* Bytes of workspace sq_build_rotation needs; 0 if a size is out of range. */
+int64_t sq_build_rotation_workspace_bytes(int64_t T, int32_t n1, int32_t n2);
+
 /* Static, human-readable name of a status code. */
 const char *sq_status_string(sq_status status);
 

@@ -1,5 +1,6 @@
 """MI355X-native W4A4 hot path of SingleQuant (arxiv 2511.22316): the online Givens + Kronecker
-rotation fused with per-token int4 quantization, and the int4 x int4 GEMM with dequant epilogue.
+rotation fused with per-token int4 quantization, the int4 x int4 GEMM with dequant epilogue, the
+offline weight path and the closed-form construction of the rotation.
 
 ``binding`` is the thin ctypes layer over the C-ABI library built from ``csrc/``;
 ``synth`` draws the seeded synthetic layers used by tests and the benchmark.
@@ -8,6 +9,9 @@ from . import synth  # noqa: F401
 from .binding import (  # noqa: F401
     SQError,
     library_path,
+    sq_build_rotation,
+    sq_build_rotation_workspace_bytes,
+    sq_kron_factor,
     sq_prepare_weights,
     sq_rotate_quantize,
     sq_w4a4_gemm,

@@ -54,6 +54,14 @@ def _load():
             C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
             C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.sq_kron_factor.restype = C.c_int
+        lib.sq_kron_factor.argtypes = [C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+        lib.sq_build_rotation.restype = C.c_int
+        lib.sq_build_rotation.argtypes = [
+            C.c_void_p, C.c_int64, C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.sq_build_rotation_workspace_bytes.restype = C.c_int64
+        lib.sq_build_rotation_workspace_bytes.argtypes = [C.c_int64, C.c_int32, C.c_int32]
         lib.sq_status_string.restype = C.c_char_p
         lib.sq_status_string.argtypes = [C.c_int]
         _lib = lib
@@ -127,4 +135,31 @@ def sq_prepare_weights(W, giv_i, giv_j, giv_theta, R1, R2, workspace, Qw, sw, st
         None if gt is None else gt.ctypes.data, P,
         _dev_ptr(R1), int(R1.shape[0]), _dev_ptr(R2), int(R2.shape[0]),
         _dev_ptr(workspace), _dev_ptr(Qw), _dev_ptr(sw), _stream_handle(stream))
+    _check(code)
+
+
+def sq_kron_factor(n: int):
+    """Alg. 1: (n1, n2) with n = n1 * n2 and n2 the power of two closest to sqrt(n).  Host only."""
+    a, b = C.c_int32(0), C.c_int32(0)
+    _check(_load().sq_kron_factor(int(n), C.byref(a), C.byref(b)))
+    return a.value, b.value
+
+
+def sq_build_rotation_workspace_bytes(T: int, n1: int, n2: int) -> int:
+    return int(_load().sq_build_rotation_workspace_bytes(int(T), int(n1), int(n2)))
+
+
+def sq_build_rotation(X, n1, n2, giv_i, giv_j, giv_theta, R1, R2, workspace, stream=None) -> None:
+    """X fp16 [T, K] calibration activations; outputs (all device tensors): giv_i, giv_j int32 [P],
+    giv_theta fp32 [P] (P = their length; None for P = 0), R1 fp16 [n1, n1], R2 fp16 [n2, n2];
+    workspace: any device tensor of at least sq_build_rotation_workspace_bytes(T, n1, n2) bytes."""
+    T, K = int(X.shape[0]), int(X.shape[1])
+    ldx = int(X.stride(0)) if T > 1 else K
+    P = 0 if giv_i is None else int(giv_i.numel())
+    need = sq_build_rotation_workspace_bytes(T, n1, n2)
+    if workspace is not None and workspace.numel() * workspace.element_size() < need:
+        raise ValueError("workspace is smaller than sq_build_rotation_workspace_bytes")
+    code = _load().sq_build_rotation(
+        _dev_ptr(X), T, K, ldx, int(n1), int(n2), P, _dev_ptr(giv_i), _dev_ptr(giv_j), _dev_ptr(giv_theta),
+        _dev_ptr(R1), _dev_ptr(R2), _dev_ptr(workspace), _stream_handle(stream))
     _check(code)

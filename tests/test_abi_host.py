@@ -175,3 +175,51 @@ def test_givens_plan_limits(lib):
     gi = gi + np.arange(64)
     levels, n_slots, n_qslots, *_ = _plan(lib, gi, gj, 128)
     assert levels == 1 and n_slots == 128 and n_qslots == 128
+
+
+# ------------------------------------------------------------------ rotation constructor ---
+
+def _br(lib, T=4, K=128, ldx=128, n1=8, n2=16, P=2, X=FAKE, gi=FAKE, gj=FAKE, gt=FAKE, R1=FAKE, R2=FAKE,
+        ws=FAKE):
+    return lib.sq_build_rotation(X, T, K, ldx, n1, n2, P, gi, gj, gt, R1, R2, ws, None)
+
+
+def test_build_rotation_argument_errors(lib):
+    assert _br(lib, X=None) == 1
+    assert _br(lib, R2=None) == 1
+    assert _br(lib, ws=None) == 1
+    assert _br(lib, gi=None) == 1                   # P > 0 needs the three output lists
+    assert _br(lib, T=0) == 2                       # a calibration batch cannot be empty
+    assert _br(lib, K=120) == 2                     # K != n1*n2
+    assert _br(lib, n1=16, n2=8, K=128, P=65) == 2
+    assert _br(lib, n1=1, n2=128) == 2              # a URT needs at least two entries
+    assert _br(lib, n1=4, n2=24, K=96, ldx=96) == 2  # n2 must be a power of two (Hadamard factor)
+    assert _br(lib, n1=32, n2=4) == 2
+    assert _br(lib, ldx=64) == 2
+    assert _br(lib, n1=128, n2=256, K=32768, ldx=32768) == 2
+    assert _br(lib, X=FAKE + 4) == 4
+    assert _br(lib, ldx=132) == 4
+    assert _br(lib, ws=FAKE + 8) == 4
+
+
+def test_build_rotation_workspace_size(lib):
+    f = sq.sq_build_rotation_workspace_bytes
+    assert f(0, 8, 8) == 0 and f(4, 0, 8) == 0 and f(4, 129, 8) == 0 and f(4, 8, 257) == 0
+    small, big = f(1, 64, 64), f(100000, 64, 64)
+    assert small % 4 == 0 and small >= 4 * (1 + 2 * 64 * 64 + 3 * 64 * 64)
+    assert big - small >= 4 * 99999 - 256           # one float per calibration row
+
+
+def test_kron_factor_follows_alg1(lib, oracle):
+    """Against the oracle's own routine and a brute force over every divisor that is a power of two."""
+    for n in list(range(1, 300)) + [512, 4096, 5120, 8192, 11008, 13824, 14336, 16384, 28672, 2 ** 20 + 2 ** 10]:
+        n1, n2 = sq.sq_kron_factor(n)
+        assert n1 * n2 == n and (n2 & (n2 - 1)) == 0
+        cands = [2 ** k for k in range(0, 31) if 2 ** k <= n and n % 2 ** k == 0]
+        best = min(cands, key=lambda a: (abs(a - np.sqrt(n)), a))
+        assert n2 == best
+        assert (n1, n2) == tuple(oracle.kron_factor(n))
+    assert sq.sq_kron_factor(4096) == (64, 64) and sq.sq_kron_factor(11008) == (86, 128)
+    a = C.c_int32(0)
+    assert lib.sq_kron_factor(0, C.byref(a), C.byref(a)) == 2
+    assert lib.sq_kron_factor(8, None, C.byref(a)) == 1
