@@ -129,6 +129,26 @@ def measure_layer(cfg, torch, sq, synth, steps, warmup):
     return out
 
 
+def measure_build_rotation(cfg, torch, sq, synth, steps, warmup):
+    """The offline constructor (sq_build_rotation) on the workload's activations as calibration
+    batch.  Not part of the layer time.  Its one large kernel reads X once (2*T*K bytes); the rest
+    is a few small launches, so the whole-call rate is a lower bound on that kernel's."""
+    dev = torch.device("cuda:0")
+    X0 = torch.from_numpy(synth.activations(cfg)).to(dev)
+    sets = max(2, min(16, -(-RING_BYTES // (2 * cfg.T * cfg.K))))
+    Xs = [X0 if i == 0 else torch.roll(X0, shifts=7 * i, dims=0).contiguous() for i in range(sets)]
+    gi = torch.empty((cfg.P,), dtype=torch.int32, device=dev)
+    gj = torch.empty((cfg.P,), dtype=torch.int32, device=dev)
+    gt = torch.empty((cfg.P,), dtype=torch.float32, device=dev)
+    R1 = torch.empty((cfg.n1, cfg.n1), dtype=torch.float16, device=dev)
+    R2 = torch.empty((cfg.n2, cfg.n2), dtype=torch.float16, device=dev)
+    ws = torch.empty((sq.sq_build_rotation_workspace_bytes(cfg.T, cfg.n1, cfg.n2),), dtype=torch.uint8, device=dev)
+    _, ms = timed(torch, lambda i: sq.sq_build_rotation(Xs[i], cfg.n1, cfg.n2, gi, gj, gt, R1, R2, ws), sets, steps, warmup)
+    return {"workload": cfg.name, "T": cfg.T, "n1": cfg.n1, "n2": cfg.n2, "art_steps": cfg.P, "us": ms * 1e3,
+            "calibration_bytes": 2.0 * cfg.T * cfg.K, "whole_call_GBps": 2.0 * cfg.T * cfg.K / (ms * 1e-3) / 1e9,
+            "ring_sets": sets}
+
+
 def cpu_baseline(cfg, synth):
     """The CPU oracle, as it stands, on this machine's host cores: rotate+quantize of every token and
     the integer GEMM on the first 512 tokens (scaled linearly in T)."""
@@ -161,6 +181,8 @@ def main() -> int:
     ap.add_argument("--workload", default="attn_proj", help="layer shape for the headline number")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the other layer shapes")
+    ap.add_argument("--only-build-rotation", action="store_true",
+                    help="time only the offline constructor on --workload and print its numbers")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run three plain 256 MiB device copies (known traffic: the scale for "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -189,6 +211,9 @@ def main() -> int:
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    if args.only_build_rotation:
+        print(json.dumps({"build_rotation": measure_build_rotation(cfg, torch, sq, synth, args.steps, args.warmup)}))
+        return 0
     head = measure_layer(cfg, torch, sq, synth, args.steps, args.warmup)
     extra = {}
     if not args.no_extra:
@@ -222,6 +247,9 @@ def main() -> int:
                                   "traffic_detail": prof.get("rotate_quantize")},
         "other_workloads": extra,
     }
+    if not args.no_extra and cfg.n2 & (cfg.n2 - 1) == 0:
+        result["build_rotation"] = measure_build_rotation(cfg, torch, sq, synth, max(10, args.steps // 4),
+                                                          max(2, args.warmup // 4))
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, synth)
     print(json.dumps(result))

@@ -8,7 +8,7 @@
 //   row_absmax_kernel     max |x| of every token row
 //   art_urt_kernel        one workgroup: calibration row, P ART steps, the vectors of the two URTs,
 //                         their uniform targets, and the four chains of plane rotations
-//   rmap_kernel           the four maps to e_1 as dense matrices, row by row in closed form
+//   rmap_kernel           the four maps to e_1 as dense matrices, entry by entry in closed form
 //   urt_product_kernel    R^U = R_map R'_map^T for both sides (side 1 is R1)
 //   hadamard_left_kernel  R2 = H R^U_2
 //
@@ -28,7 +28,9 @@ namespace {
 constexpr int kBuildThreads = 1024;
 constexpr int kBuildWaves = kBuildThreads / kWave;
 constexpr int kMaxSide = 256;                 // n1 <= 128, n2 <= 256
-constexpr int kBuildSmallBytes = 2 * kBuildWaves * 8 + 5 * kMaxSide * 4;
+static_assert(kBuildThreads == 4 * kMaxSide, "one thread per step of each of the four chains");
+static_assert(SQ_MAX_N1 <= kMaxSide && SQ_MAX_N2 <= kMaxSide && SQ_MAX_GIVENS <= kBuildThreads, "limits");
+constexpr int kBuildSmallBytes = 4 * kBuildWaves * 4 + 5 * kMaxSide * 4 + 2 * SQ_MAX_GIVENS * 4;
 
 // workspace, in floats
 struct BuildWorkspace {
@@ -80,8 +82,6 @@ __device__ __forceinline__ float rn_add(float a, float b)
     asm volatile("" : "+v"(r));
     return r;
 }
-__device__ __forceinline__ uint64_t larger(uint64_t a, uint64_t b) { return a > b ? a : b; }
-__device__ __forceinline__ uint64_t smaller(uint64_t a, uint64_t b) { return a < b ? a : b; }
 
 // max |x| per token row.  One wave per row; a lane reads 16 bytes at a time, four loads in
 // flight.  |fp16| bit patterns order like unsigned integers, so the maximum is taken on the
@@ -115,46 +115,64 @@ __global__ __launch_bounds__(256) void row_absmax_kernel(const __half *__restric
     }
 }
 
-__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int mask)
-{
-    const uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)v, mask, kWave);
-    const uint32_t hi = (uint32_t)__shfl_xor((int)(uint32_t)(v >> 32), mask, kWave);
-    return ((uint64_t)hi << 32) | lo;
-}
-
-// largest (or smallest) key of the workgroup, returned in every thread; `slots` holds one key
-// per wave and must not be rewritten before every thread has passed a later barrier
+// Largest (or smallest) 32-bit unsigned value of the wave, in every lane.  DPP steps as in
+// wave_max; lanes a step does not write keep the identity of the operation.
 template <bool LARGEST>
-__device__ __forceinline__ uint64_t block_select(uint64_t key, uint64_t *slots)
+__device__ __forceinline__ uint32_t wave_extreme(uint32_t v)
 {
-#pragma unroll
-    for (int off = kWave / 2; off >= 1; off >>= 1) {
-        const uint64_t o = shfl_xor_u64(key, off);
-        key = LARGEST ? (o > key ? o : key) : (o < key ? o : key);
-    }
-    if ((threadIdx.x & (kWave - 1)) == 0) slots[threadIdx.x / kWave] = key;
-    __syncthreads();
-    uint64_t best = slots[0];
-#pragma unroll
-    for (int w = 1; w < kBuildWaves; ++w) {
-        const uint64_t o = slots[w];
-        best = LARGEST ? (o > best ? o : best) : (o < best ? o : best);
-    }
-    return best;
+    constexpr int kIdentity = LARGEST ? 0 : -1;
+#define SQ_DPP_STEP(ctrl, row_mask)                                                                  \
+    do {                                                                                             \
+        const uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp(kIdentity, (int)v, ctrl, row_mask, 0xF, false); \
+        v = LARGEST ? (o > v ? o : v) : (o < v ? o : v);                                             \
+    } while (0)
+    SQ_DPP_STEP(0xB1, 0xF);     // quad_perm [1,0,3,2]
+    SQ_DPP_STEP(0x4E, 0xF);     // quad_perm [2,3,0,1]
+    SQ_DPP_STEP(0x141, 0xF);    // row_half_mirror
+    SQ_DPP_STEP(0x140, 0xF);    // row_mirror: every lane holds the result of its row of 16
+    SQ_DPP_STEP(0x142, 0xA);    // row_bcast:15 into rows 1 and 3
+    SQ_DPP_STEP(0x143, 0xC);    // row_bcast:31 into rows 2 and 3: lane 63 holds the wave's result
+#undef SQ_DPP_STEP
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
-// Givens chain that takes `vec` (n entries) to ||vec|| e_1: entry k is zeroed by a rotation in the
-// plane (k - 1, k), k = n - 1 down to 1; (cos, sin) of step k go to cs[k] and cs[kMaxSide + k].
-__device__ void chain_to_e1(const float *vec, int n, float *cs)
+// Channel of the largest (or smallest) magnitude in the workgroup, the lowest channel among equal
+// magnitudes; every thread passes the best (magnitude bits, channel) of its own elements and gets
+// the result.  `slots` ([2][kBuildWaves] words) must not be rewritten before every thread has
+// passed a later barrier.
+template <bool LARGEST>
+__device__ __forceinline__ uint32_t block_arg(uint32_t mag, uint32_t idx, uint32_t *slots)
 {
-    double carry = vec[n - 1];
-    for (int k = n - 1; k >= 1; --k) {
-        const double x = vec[k - 1], h = sqrt(x * x + carry * carry);
-        const double co = (h == 0.0) ? 1.0 : x / h, si = (h == 0.0) ? 0.0 : carry / h;
-        cs[k] = (float)co;
-        cs[kMaxSide + k] = (float)si;
-        carry = h;
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    constexpr uint32_t kNone = LARGEST ? 0u : 0xFFFFFFFFu;
+    uint32_t best = wave_extreme<LARGEST>(mag);
+    uint32_t who = wave_extreme<false>(mag == best ? idx : 0xFFFFFFFFu);
+    if (lane == 0) {
+        slots[wave] = best;
+        slots[kBuildWaves + wave] = who;
     }
+    __syncthreads();
+    // every wave combines the per-wave results on its own
+    const uint32_t m2 = lane < kBuildWaves ? slots[lane] : kNone;
+    const uint32_t i2 = lane < kBuildWaves ? slots[kBuildWaves + lane] : 0xFFFFFFFFu;
+    best = wave_extreme<LARGEST>(m2);
+    return wave_extreme<false>(m2 == best ? i2 : 0xFFFFFFFFu);
+}
+
+// Step k of the Givens chain that takes `vec` (n entries) to ||vec|| e_1: entry k is zeroed by a
+// rotation in the plane (k - 1, k), k = n - 1 down to 1.  When step k acts, entry k holds the norm
+// of the original entries k .. n-1, so with S_k the sum of their squares
+//   cos_k = v_{k-1} / sqrt(S_{k-1}),   sin_k = sqrt(S_k / S_{k-1})     (cos = 1, sin = 0 if S_{k-1} = 0;
+//   sin_{n-1} = v_{n-1} / sqrt(S_{n-2}), because the last entry enters with its sign)
+// and the steps can be computed independently of one another.  Stored at cs[k], cs[kMaxSide + k].
+__device__ __forceinline__ void chain_step(const float *vec, int n, int k, float *cs)
+{
+    double tail = 0.0;
+    for (int m = n - 1; m >= k; --m) tail += (double)vec[m] * (double)vec[m];
+    const double x = vec[k - 1], all = tail + x * x;
+    cs[k] = (all == 0.0) ? 1.f : (float)(x / sqrt(all));
+    // the first step (k = n-1) meets the last entry itself, sign included; later ones meet a norm
+    cs[kMaxSide + k] = (all == 0.0) ? 0.f : (float)(k == n - 1 ? (double)vec[k] / sqrt(all) : sqrt(tail / all));
 }
 
 // One workgroup.  All of its LDS is dynamic (kBuildSmallBytes + 4K bytes): the reduction slots,
@@ -164,40 +182,49 @@ __global__ __launch_bounds__(kBuildThreads) void art_urt_kernel(
     const float *__restrict__ rowmax, int32_t *__restrict__ giv_i, int32_t *__restrict__ giv_j,
     float *__restrict__ giv_theta, float *__restrict__ chain)
 {
-    extern __shared__ uint64_t build_lds[];
-    uint64_t *slot_a = build_lds, *slot_b = build_lds + kBuildWaves;
-    float(*vec)[kMaxSide] = reinterpret_cast<float(*)[kMaxSide]>(build_lds + 2 * kBuildWaves);   // V1 | V2 H
+    extern __shared__ uint32_t build_lds[];
+    uint32_t *slots_a = build_lds, *slots_b = build_lds + 2 * kBuildWaves;
+    float(*vec)[kMaxSide] = reinterpret_cast<float(*)[kMaxSide]>(build_lds + 4 * kBuildWaves);   // V1 | V2 H
     float *v2 = vec[2];
     float(*target)[kMaxSide] = reinterpret_cast<float(*)[kMaxSide]>(vec[3]);                     // U1 | U2
-    float *cvec = vec[5];
+    float *pair_a = vec[5], *pair_b = pair_a + SQ_MAX_GIVENS;      // (c_i, c_j) each ART angle is made for
+    float *cvec = pair_b + SQ_MAX_GIVENS;
     const int tid = threadIdx.x;
 
     // calibration row: the largest row maximum, lowest row among equals
-    uint64_t key = 0;
-    for (int t = tid; t < T; t += kBuildThreads)
-        key = larger(key, ((uint64_t)__float_as_uint(rowmax[t]) << 32) | (0xFFFFFFFFu - (uint32_t)t));
-    const int t_star = (int)(0xFFFFFFFFu - (uint32_t)block_select<true>(key, slot_a));
+    uint32_t top = 0, top_at = 0xFFFFFFFFu;
+    for (int t = tid; t < T; t += kBuildThreads) {
+        const uint32_t m = __float_as_uint(rowmax[t]);
+        if (m > top || top_at == 0xFFFFFFFFu) top = m, top_at = (uint32_t)t;      // t ascends: ties keep the lower row
+    }
+    const int t_star = (int)block_arg<true>(top, top_at, slots_a);
     for (int k = tid; k < K; k += kBuildThreads) cvec[k] = __half2float(X[(int64_t)t_star * ldx + k]);
     __syncthreads();
 
     // ART (Sec. 4.2; several steps as in the "ART steps" study): largest against smallest
     // magnitude, angle of Lemma 1, after which both channels hold r / sqrt(2)
     for (int p = 0; p < P; ++p) {
-        uint64_t hi = 0;
-        for (int k = tid; k < K; k += kBuildThreads)
-            hi = larger(hi, ((uint64_t)__float_as_uint(fabsf(cvec[k])) << 32) | (0xFFFFFFFFu - (uint32_t)k));
-        const int i = (int)(0xFFFFFFFFu - (uint32_t)block_select<true>(hi, slot_a));
-        uint64_t lo = ~0ull;
-        for (int k = tid; k < K; k += kBuildThreads)
-            if (k != i) lo = smaller(lo, ((uint64_t)__float_as_uint(fabsf(cvec[k])) << 32) | (uint32_t)k);
-        const int j = (int)(uint32_t)block_select<false>(lo, slot_b);
+        // k ascends within a thread, so strict comparisons keep the lower channel among equals
+        uint32_t hi = 0, hi_at = 0xFFFFFFFFu;
+        for (int k = tid; k < K; k += kBuildThreads) {
+            const uint32_t m = __float_as_uint(fabsf(cvec[k]));
+            if (m > hi || hi_at == 0xFFFFFFFFu) hi = m, hi_at = (uint32_t)k;
+        }
+        const int i = (int)block_arg<true>(hi, hi_at, slots_a);
+        uint32_t lo = 0xFFFFFFFFu, lo_at = 0xFFFFFFFFu;
+        for (int k = tid; k < K; k += kBuildThreads) {
+            const uint32_t m = __float_as_uint(fabsf(cvec[k]));
+            if (k != i && (m < lo || lo_at == 0xFFFFFFFFu)) lo = m, lo_at = (uint32_t)k;
+        }
+        const int j = (int)block_arg<false>(lo, lo_at, slots_b);
         if (tid == 0) {
             const float a = cvec[i], b = cvec[j];
             const float r = sqrtf(rn_add(rn_mul(a, a), rn_mul(b, b)));
             const float e = rn_mul(r, 0.70710678118654752440f);
             giv_i[p] = i;
             giv_j[p] = j;
-            giv_theta[p] = (float)(atan2((double)b, (double)a) - 0.78539816339744830962);
+            pair_a[p] = a;
+            pair_b[p] = b;
             cvec[i] = e;
             cvec[j] = e;
         }
@@ -245,67 +272,87 @@ __global__ __launch_bounds__(kBuildThreads) void art_urt_kernel(
     }
     __syncthreads();
 
-    // the four chains, one thread each, in four different waves
-    if ((tid & (kWave - 1)) == 0 && tid < 4 * kWave) {
-        const int which = tid / kWave, side = which >> 1, is_target = which & 1;
-        chain_to_e1(is_target ? target[side] : vec[side], side ? n2 : n1, chain + which * 2 * kMaxSide);
+    // the four chains: thread (which, k) computes step k of chain `which`
+    {
+        const int which = tid / kMaxSide, k = tid % kMaxSide, side = which >> 1, is_target = which & 1;
+        const int n = side ? n2 : n1;
+        if (k >= 1 && k < n) chain_step(is_target ? target[side] : vec[side], n, k, chain + which * 2 * kMaxSide);
     }
+
+    // the angles of Lemma 1, one thread per ART step
+    if (tid < P) giv_theta[tid] = (float)(atan2((double)pair_b[tid], (double)pair_a[tid]) - 0.78539816339744830962);
 }
 
-// Row r of the product of the chain (step n-1 first): nothing right of column r + 1; the entry
-// that starts as 1 in column r is carried leftwards, multiplied by sin at every step.
-__global__ __launch_bounds__(kMaxSide) void rmap_kernel(const float *__restrict__ chain, int n1, int n2,
-                                                       float *m0, float *m1, float *m2, float *m3)
+// Entry (r, k) of the product of a chain (step n-1 first).  Row r starts as e_r; step r+1 leaves
+// (cos, -sin) in columns r and r+1, and every later step k <= r multiplies what is carried in
+// column k by sin_k on its way to column k-1 and leaves carry * cos_k behind.  Nothing ever
+// reaches a column right of r+1.  blockIdx.y = which of the four matrices.
+__global__ __launch_bounds__(256) void rmap_kernel(const float *__restrict__ chain, int n1, int n2,
+                                                   float *m0, float *m1, float *m2, float *m3)
 {
-    const int which = blockIdx.x, n = (which >> 1) ? n2 : n1, r = threadIdx.x;
+    const int which = blockIdx.y, n = (which >> 1) ? n2 : n1;
     float *M = which == 0 ? m0 : which == 1 ? m1 : which == 2 ? m2 : m3;
     const float *co = chain + which * 2 * kMaxSide, *si = co + kMaxSide;
-    if (r >= n) return;
-    float *row = M + (int64_t)r * n;
-    for (int k = r + 2; k < n; ++k) row[k] = 0.f;
-    float carry = 1.f;
-    if (r + 1 < n) {
-        row[r + 1] = -si[r + 1];
-        carry = co[r + 1];
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= n * n) return;
+    const int r = idx / n, k = idx % n;
+    float v = 0.f;
+    if (k == r + 1) {
+        v = -si[k];
+    } else if (k <= r) {
+        v = (r + 1 < n) ? co[r + 1] : 1.f;
+        for (int m = r; m > k; --m) v *= si[m];
+        if (k >= 1) v *= co[k];
     }
-    for (int k = r; k >= 1; --k) {
-        row[k] = carry * co[k];
-        carry *= si[k];
-    }
-    row[0] = carry;
+    M[idx] = v;
 }
 
-// R^U = R_map R'_map^T (Sec. 4.2 URT).  blockIdx.y = side; side 1 leaves as fp16 R1, side 2 stays
-// fp32 for the Hadamard factor.
+// R^U = R_map R'_map^T (Sec. 4.2 URT), 16 x 16 output tile per workgroup, operands staged through
+// LDS.  blockIdx.z = side; side 1 leaves as fp16 R1, side 2 stays fp32 for the Hadamard factor.
 __global__ __launch_bounds__(256) void urt_product_kernel(const float *__restrict__ a1, const float *__restrict__ b1,
                                                           const float *__restrict__ a2, const float *__restrict__ b2,
                                                           int n1, int n2, __half *__restrict__ R1,
                                                           float *__restrict__ ru2)
 {
-    const int side = blockIdx.y, n = side ? n2 : n1;
+    __shared__ float ta[16][17], tb[16][17];
+    const int side = blockIdx.z, n = side ? n2 : n1;
     const float *A = side ? a2 : a1, *B = side ? b2 : b1;
-    const int idx = blockIdx.x * 256 + threadIdx.x;
-    if (idx >= n * n) return;
-    const int r = idx / n, b = idx % n;
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int r0 = blockIdx.y * 16, c0 = blockIdx.x * 16;
+    if (r0 >= n || c0 >= n) return;                      // whole workgroup: the grid is sized for the larger side
     float s = 0.f;
-    for (int k = 0; k < n; ++k) s += A[r * n + k] * B[b * n + k];
-    if (side) ru2[idx] = s;
-    else R1[idx] = __float2half_rn(s);
+    for (int k0 = 0; k0 < n; k0 += 16) {
+        ta[ty][tx] = (r0 + ty < n && k0 + tx < n) ? A[(r0 + ty) * n + k0 + tx] : 0.f;
+        tb[ty][tx] = (c0 + ty < n && k0 + tx < n) ? B[(c0 + ty) * n + k0 + tx] : 0.f;
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 16; ++k) s += ta[ty][k] * tb[tx][k];
+        __syncthreads();
+    }
+    const int r = r0 + ty, c = c0 + tx;
+    if (r < n && c < n) {
+        if (side) ru2[r * n + c] = s;
+        else R1[r * n + c] = __float2half_rn(s);
+    }
 }
 
-// R2 = H R^U_2 with the normalised Sylvester Hadamard matrix, H[a][m] = (-1)^popcount(a & m) / sqrt n
+// R2 = H R^U_2 with the normalised Sylvester Hadamard matrix, H[a][m] = (-1)^popcount(a & m) / sqrt n;
+// same tiling (n2 is a power of two >= 8; partial tiles are masked)
 __global__ __launch_bounds__(256) void hadamard_left_kernel(const float *__restrict__ ru2, int n2, float inv_sqrt_n2,
                                                             __half *__restrict__ R2)
 {
-    const int idx = blockIdx.x * 256 + threadIdx.x;
-    if (idx >= n2 * n2) return;
-    const int a = idx / n2, b = idx % n2;
+    __shared__ float tm[16][17];
+    const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+    const int a = blockIdx.y * 16 + ty, b0 = blockIdx.x * 16;
     float s = 0.f;
-    for (int m = 0; m < n2; ++m) {
-        const float x = ru2[m * n2 + b];
-        s += (__popc(a & m) & 1) ? -x : x;
+    for (int m0 = 0; m0 < n2; m0 += 16) {
+        tm[ty][tx] = (m0 + ty < n2 && b0 + tx < n2) ? ru2[(m0 + ty) * n2 + b0 + tx] : 0.f;
+        __syncthreads();
+#pragma unroll
+        for (int m = 0; m < 16; ++m) s += (__popc(a & (m0 + m)) & 1) ? -tm[m][tx] : tm[m][tx];
+        __syncthreads();
     }
-    R2[idx] = __float2half_rn(s * inv_sqrt_n2);
+    if (a < n2 && b0 + tx < n2) R2[a * n2 + b0 + tx] = __float2half_rn(s * inv_sqrt_n2);
 }
 
 bool build_shape_ok(int64_t T, int32_t K, int32_t n1, int32_t n2, int32_t P)
@@ -366,12 +413,13 @@ extern "C" sq_status sq_build_rotation(const void *X, int64_t T, int32_t K, int6
     if (!sq::allow_large_lds(reinterpret_cast<const void *>(art))) return SQ_ERR_LAUNCH;
     hipLaunchKernelGGL(art, dim3(1), dim3(sq::kBuildThreads), lds, st, Xh, ldx, (int)T, K, n1, n2, P, inv_sqrt_n2,
                        w.rowmax, giv_i, giv_j, giv_theta, w.chain);
-    hipLaunchKernelGGL(sq::rmap_kernel, dim3(4), dim3(sq::kMaxSide), 0, st, w.chain, n1, n2, w.rmap[0], w.rmap[1],
-                       w.rmap[2], w.rmap[3]);
     const int big = n1 > n2 ? n1 : n2;
-    hipLaunchKernelGGL(sq::urt_product_kernel, dim3((unsigned)((big * big + 255) / 256), 2), dim3(256), 0, st,
-                       w.rmap[0], w.rmap[1], w.rmap[2], w.rmap[3], n1, n2, static_cast<__half *>(R1), w.ru2);
-    hipLaunchKernelGGL(sq::hadamard_left_kernel, dim3((unsigned)((n2 * n2 + 255) / 256)), dim3(256), 0, st, w.ru2,
-                       n2, inv_sqrt_n2, static_cast<__half *>(R2));
+    hipLaunchKernelGGL(sq::rmap_kernel, dim3((unsigned)((big * big + 255) / 256), 4), dim3(256), 0, st, w.chain, n1,
+                       n2, w.rmap[0], w.rmap[1], w.rmap[2], w.rmap[3]);
+    const unsigned tiles = (unsigned)((big + 15) / 16), tiles2 = (unsigned)((n2 + 15) / 16);
+    hipLaunchKernelGGL(sq::urt_product_kernel, dim3(tiles, tiles, 2), dim3(256), 0, st, w.rmap[0], w.rmap[1],
+                       w.rmap[2], w.rmap[3], n1, n2, static_cast<__half *>(R1), w.ru2);
+    hipLaunchKernelGGL(sq::hadamard_left_kernel, dim3(tiles2, tiles2), dim3(256), 0, st, w.ru2, n2, inv_sqrt_n2,
+                       static_cast<__half *>(R2));
     return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
