@@ -26,6 +26,8 @@
 #include "sq_common.h"
 #include "sq_rotq_plan.h"
 
+#include <stdlib.h>
+
 #include <type_traits>
 
 namespace sq {
@@ -77,7 +79,9 @@ __device__ __forceinline__ float max_abs16(const v16f &a, float m)
 
 }  // namespace
 
-template <int N1, int N2>
+// NSX_: token tiles per ring (3: two rows ahead of the one being multiplied; 2: one row ahead,
+// with less LDS so that a third workgroup fits a CU)
+template <int N1, int N2, int NSX_>
 struct RotqShape {
     static constexpr int N1P = (N1 + 31) / 32 * 32;   // rows padded to the MFMA block
     static constexpr int MB = N1P / 32;           // 32-row blocks of X_mat / Z (rows p)
@@ -88,7 +92,7 @@ struct RotqShape {
     static constexpr int CPRX = N2 / 8;           // 16-byte chunks per tile row
     static constexpr int ROW_CHUNKS = N1 * CPRX;  // 16-byte chunks of one token row
     static constexpr int LPT = (ROW_CHUNKS + 63) / 64;    // wave-wide loads per token row
-    static constexpr int NSX = 3;                 // ring of token tiles
+    static constexpr int NSX = NSX_;              // ring of token tiles
     static constexpr int TILE_BYTES = N1P * N2 * 2;
     static constexpr int LO_STEP_BYTES = N1P * 32;        // side tile: [step][row p][16 fp16]
     static constexpr int OUT_UNITS = N2 / 4;      // 2-byte units (4 codes) per output row p'
@@ -99,6 +103,7 @@ struct RotqShape {
     static constexpr int TAIL_BYTES = TPP * (kRotqMaxSlots * 4 + 16 + OUT_BYTES);
     static constexpr int lds_bytes(int qsteps) { return OFF_LO + TPP * qsteps * LO_STEP_BYTES + TAIL_BYTES; }
     static_assert(N2 == 32 || N2 == 64 || N2 == 128, "one to four waves per token");
+    static_assert(NSX == 2 || NSX == 3, "ring of two or three tiles");
     static_assert(N1P <= 128, "at most four row blocks");
     // two rows are in flight at most; at 64 outstanding loads the counter is full and the issue
     // of the last one simply waits
@@ -106,13 +111,13 @@ struct RotqShape {
 };
 
 // QS_MAX: repair steps of 16 q-slots each the kernel holds rotation rows for (4 or 8).
-template <int N1, int N2, int OCC, int QS_MAX>
+template <int N1, int N2, int OCC, int QS_MAX, int NSX_>
 __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
     const __half *__restrict__ X, int64_t ldx, int T, RotqPlan plan,
     const __half *__restrict__ R1, const __half *__restrict__ R2, uint8_t *__restrict__ Q,
     float *__restrict__ scales, float *__restrict__ xrot)
 {
-    using S = RotqShape<N1, N2>;
+    using S = RotqShape<N1, N2, NSX_>;
     constexpr int N1P = S::N1P, MB = S::MB, NCB = S::NCB, TPP = S::TPP, KSA = S::KSA, KSB = S::KSB;
     constexpr int CPRX = S::CPRX, LPT = S::LPT, NSX = S::NSX, K = N1 * N2;
     static_assert(QS_MAX == 4 || QS_MAX == 8, "64 or 128 q-slots");
@@ -386,7 +391,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
 
     if (lead) {
         issue_row(g0 + stride, 1);
-        issue_row(g0 + 2 * stride, 2);
+        if (NSX == 3) issue_row(g0 + 2 * stride, 2);
     }
 
     // LDS byte offsets of this lane's operand chunks inside a tile (row block 0): the swizzle
@@ -447,6 +452,9 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
         const int t = grp * TPP + tok_slot;
         const bool live = t < T;
         const int slot1 = (slot + 1 == NSX) ? 0 : slot + 1;
+        // ring of two: the tile of this token went through stage A an iteration ago (every wave
+        // has passed the barrier that ended it), so the row after next can start now
+        if (NSX == 2 && lead) issue_row(grp + 2 * stride, slot);
 
         // ---- power-of-two prescale of this wave's columns so that hi/lo fit fp16 -------------
         // Stage B contracts over rows p within a column, so a per-wave factor commutes with it.
@@ -525,7 +533,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
         }
         __syncthreads();     // B2: maxima visible; next tile rotated; copy-out of the last token done
         // stage A of this token ran an iteration ago, so its ring slot is free for the row after next
-        if (lead) issue_row(grp + 3 * stride, slot);
+        if (NSX == 3 && lead) issue_row(grp + 3 * stride, slot);
 
         amax = red[0];
 #pragma unroll
@@ -591,24 +599,43 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
     wait_loads_le<0>();
 }
 
+// OCC: workgroups per CU the registers allow (512 per lane and SIMD, one wave of each workgroup
+// per SIMD); the LDS the list needs may allow fewer.
+template <int N1, int N2, int QS_MAX, int NSX, int OCC>
+static sq_status launch_rotq_mfma_ring(const __half *X, int64_t ldx, int T, const RotqPlan &plan,
+                                       const __half *R1, const __half *R2, uint8_t *Q, float *scales,
+                                       float *xrot, hipStream_t st)
+{
+    using S = RotqShape<N1, N2, NSX>;
+    const int qsteps = (plan.n_qslots + 15) / 16;
+    const int lds = S::lds_bytes(qsteps);
+    if (lds > kMaxDynamicLds) return SQ_ERR_SHAPE;
+    auto kernel = rotate_quantize_mfma_kernel<N1, N2, OCC, QS_MAX, NSX>;
+    if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return SQ_ERR_LAUNCH;
+    const int groups = (T + S::TPP - 1) / S::TPP;
+    const int by_lds = (160 * 1024) / lds;
+    const int per_cu = by_lds < OCC ? by_lds : OCC;                       // workgroups a CU holds
+    const int resident = 256 * per_cu;
+    const int grid = groups < resident ? groups : resident;
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), lds, st, X, ldx, T, plan, R1, R2, Q, scales, xrot);
+    return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
 template <int N1, int N2, int QS_MAX>
 static sq_status launch_rotq_mfma_qs(const __half *X, int64_t ldx, int T, const RotqPlan &plan,
                                      const __half *R1, const __half *R2, uint8_t *Q, float *scales,
                                      float *xrot, hipStream_t st)
 {
-    using S = RotqShape<N1, N2>;
-    constexpr int OCC = (S::MB <= 2) ? 2 : 1;               // register budget: 256 per wave at two per SIMD
-    const int qsteps = (plan.n_qslots + 15) / 16;
-    const int lds = S::lds_bytes(qsteps);
-    if (lds > kMaxDynamicLds) return SQ_ERR_SHAPE;
-    auto kernel = rotate_quantize_mfma_kernel<N1, N2, OCC, QS_MAX>;
-    if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return SQ_ERR_LAUNCH;
-    const int groups = (T + S::TPP - 1) / S::TPP;
-    const int per_cu = (OCC == 2 && 2 * lds <= 158 * 1024) ? 2 : 1;      // workgroups a CU holds
-    const int resident = 256 * per_cu;
-    const int grid = groups < resident ? groups : resident;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), lds, st, X, ldx, T, plan, R1, R2, Q, scales, xrot);
-    return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+    constexpr int MB = (N1 + 31) / 32;
+    if constexpr (N1 == 64 && N2 == 64) {
+        // 168 registers: three workgroups fit a CU if the ring has two tiles.  Measured faster than
+        // the ring of three at two workgroups per CU from 4096 tokens on (4 % there, 12 % at 32768),
+        // 3 % slower below.  SQ_ROTQ_RING=2 or 3 forces one of them (tuning aid).
+        static const int forced = [] { const char *e = getenv("SQ_ROTQ_RING"); return e ? atoi(e) : 0; }();
+        const bool ring2 = forced == 2 || (forced != 3 && T >= 4096);
+        if (ring2) return launch_rotq_mfma_ring<N1, N2, QS_MAX, 2, 3>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st);
+    }
+    return launch_rotq_mfma_ring<N1, N2, QS_MAX, 3, (MB <= 2) ? 2 : 1>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st);
 }
 
 // A list touches at most min(2P, n2) distinct columns q: more than 64 only if n2 is 128.

@@ -201,6 +201,29 @@ def test_rotate_quantize_four_row_blocks_many_tokens(oracle, n1, n2, wide_list):
     assert np.all(np.max(np.abs(codes_of(Qg)), axis=1) == 7)
 
 
+@pytest.mark.parametrize("with_list", [True, False])
+def test_rotate_quantize_64x64_many_tokens(oracle, with_list):
+    """From 4096 tokens on, the 64 x 64 shape runs with a ring of two tiles and three workgroups per
+    CU: 5000 tokens (every workgroup walks its ring several times, the last pass is ragged),
+    sampled rows against the oracle, with the layer's Givens list and without one."""
+    print(f"case rotate_quantize attn_proj T=5000 list={with_list}", flush=True)
+    cfg = synth.CONFIGS["attn_proj"]
+    T = 5000
+    L = synth.layer(cfg, T)
+    if not with_list:
+        e = np.zeros(0, np.int32)
+        L = synth.Layer(cfg, L.X, e, e, np.zeros(0, np.float32), L.R1, L.R2, L.R1_f64, L.R2_f64)
+    Qg, sg, xg = run_rotate_quantize(L)
+    rows = np.unique(np.concatenate([[0, 1, 767, 768, 1535, 1536, T - 2, T - 1],
+                                     np.random.default_rng(8).integers(0, T, 80)]))
+    xo, Qo, so = _oracle_rq(oracle, L, L.X[rows])
+    check_rotation(xg[rows], xo)
+    check_codes(Qg[rows], sg[rows], Qo, so)
+    assert np.all(np.max(np.abs(codes_of(Qg)), axis=1) == 7)
+    Qg2, sg2, _ = run_rotate_quantize(L, want_xrot=False)
+    assert np.array_equal(Qg, Qg2) and np.array_equal(sg, sg2)
+
+
 def test_rotate_quantize_generic_kernel_on_benchmark_shape(oracle):
     """The generic kernel, forced on a shape the matrix-core kernel normally takes, must agree with
     the oracle as well (it is the fallback for every shape without an instantiation)."""
