@@ -81,7 +81,9 @@ __device__ __forceinline__ float max_abs16(const v16f &a, float m)
 
 // NSX_: token tiles per ring (3: two rows ahead of the one being multiplied; 2: one row ahead,
 // with less LDS so that a third workgroup fits a CU)
-template <int N1, int N2, int NSX_>
+// R1LDS_: the stage-B operand fragments of R1 live in LDS, one copy shared by the four waves,
+// instead of in every wave's registers (frees 8 MB^2 registers per lane)
+template <int N1, int N2, int NSX_, bool R1LDS_ = false>
 struct RotqShape {
     static constexpr int N1P = (N1 + 31) / 32 * 32;   // rows padded to the MFMA block
     static constexpr int MB = N1P / 32;           // 32-row blocks of X_mat / Z (rows p)
@@ -98,7 +100,9 @@ struct RotqShape {
     static constexpr int OUT_UNITS = N2 / 4;      // 2-byte units (4 codes) per output row p'
     static constexpr int OUT_BYTES = OUT_UNITS * N1P * 2;             // staged as [unit][p']
     static constexpr int OFF_X = 0;                                   // [TPP][NSX][TILE]
-    static constexpr int OFF_LO = TPP * NSX * TILE_BYTES;             // [TPP][qsteps][LO_STEP]
+    static constexpr int OFF_R1F = TPP * NSX * TILE_BYTES;            // [MB][KSB][64 lanes][16 bytes]
+    static constexpr int R1F_BYTES = R1LDS_ ? MB * KSB * 1024 : 0;
+    static constexpr int OFF_LO = OFF_R1F + R1F_BYTES;                // [TPP][qsteps][LO_STEP]
     // after the side tiles (runtime size): [TPP][128] float, [TPP][4] float, [TPP][OUT]
     static constexpr int TAIL_BYTES = TPP * (kRotqMaxSlots * 4 + 16 + OUT_BYTES);
     static constexpr int lds_bytes(int qsteps) { return OFF_LO + TPP * qsteps * LO_STEP_BYTES + TAIL_BYTES; }
@@ -111,13 +115,13 @@ struct RotqShape {
 };
 
 // QS_MAX: repair steps of 16 q-slots each the kernel holds rotation rows for (4 or 8).
-template <int N1, int N2, int OCC, int QS_MAX, int NSX_>
+template <int N1, int N2, int OCC, int QS_MAX, int NSX_, bool R1LDS>
 __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
     const __half *__restrict__ X, int64_t ldx, int T, RotqPlan plan,
     const __half *__restrict__ R1, const __half *__restrict__ R2, uint8_t *__restrict__ Q,
     float *__restrict__ scales, float *__restrict__ xrot)
 {
-    using S = RotqShape<N1, N2, NSX_>;
+    using S = RotqShape<N1, N2, NSX_, R1LDS>;
     constexpr int N1P = S::N1P, MB = S::MB, NCB = S::NCB, TPP = S::TPP, KSA = S::KSA, KSB = S::KSB;
     constexpr int CPRX = S::CPRX, LPT = S::LPT, NSX = S::NSX, K = N1 * N2;
     static_assert(QS_MAX == 4 || QS_MAX == 8, "64 or 128 q-slots");
@@ -224,7 +228,8 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
             }
     };
 
-    v8h r2f[KSA], r2x[QS_MAX], r1f[MB][KSB];
+    v8h r2f[KSA], r2x[QS_MAX], r1f[R1LDS ? 1 : MB][R1LDS ? 1 : KSB];
+    static_assert(!R1LDS || MB <= 4, "one wave per column block of R1 builds the shared fragments");
     {
         v8h sel[2];                       // identity slices: B[k][n] = (16kk + k == n), k = 8g + e
 #pragma unroll
@@ -286,7 +291,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
         // Up to three row blocks, all of R1 is requested at once.  With four, that would not fit
         // the registers: the blocks of column block nb + 1 are requested while those of nb are
         // transposed, in two alternating sets.
-        constexpr int RAW1_SETS = MB <= 3 ? MB : 2;
+        constexpr int RAW1_SETS = R1LDS ? 1 : (MB <= 3 ? MB : 2);
         v8h raw2[N2 / 32][2], raw1[RAW1_SETS][MB][2];
         auto load_raw1 = [&](int nb, v8h (&dst)[MB][2]) {
 #pragma unroll
@@ -315,8 +320,14 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
             raw2[blk][0] = chunk(r2col + (32 * blk + lsw) * N2, C0{}, CN2{});
             raw2[blk][1] = chunk(r2col + (32 * blk + lsw) * N2, C16{}, CN2{});
         }
+        // shared fragments: wave nb fetches (and later transposes) column block nb of R1
+        const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+        if constexpr (R1LDS) {
+            if (wave_s < MB) load_raw1(wave_s, raw1[0]);
+        } else {
 #pragma unroll
-        for (int nb = 0; nb < (MB <= 3 ? MB : 1); ++nb) load_raw1(nb, raw1[nb]);
+            for (int nb = 0; nb < (MB <= 3 ? MB : 1); ++nb) load_raw1(nb, raw1[nb]);
+        }
         __builtin_amdgcn_sched_barrier(0);              // every request is out before the first use
         // While those requests are in flight: zeros where nothing is ever loaded, then the lead wave
         // rotates the first row.  Row one was requested before the plan entries and loads complete in
@@ -348,17 +359,31 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
             r2f[2 * blk] = to_frag(c, 0);
             r2f[2 * blk + 1] = to_frag(c, 1);
         }
+        if constexpr (R1LDS) {
+            // visible to the other waves after the barrier that precedes the first stage A
+            if (wave_s < MB) {
+                v8h *dst = reinterpret_cast<v8h *>(lds + S::OFF_R1F) + (wave_s * KSB) * kWave + lane;
 #pragma unroll
-        for (int nb = 0; nb < MB; ++nb) {
-            constexpr bool ALTERNATE = MB > 3;
-            const int set = ALTERNATE ? (nb & 1) : nb;
-            if (ALTERNATE && nb + 1 < MB) load_raw1(nb + 1, raw1[(nb + 1) & 1]);
+                for (int blk = 0; blk < MB; ++blk) {
+                    const bool keep = 32 * blk + l32 < N1;
+                    const v16f c = block_t(zero_unless(keep, raw1[0][blk][0]), zero_unless(keep, raw1[0][blk][1]));
+                    dst[(2 * blk) * kWave] = to_frag(c, 0);
+                    dst[(2 * blk + 1) * kWave] = to_frag(c, 1);
+                }
+            }
+        } else {
 #pragma unroll
-            for (int blk = 0; blk < MB; ++blk) {
-                const bool keep = 32 * blk + l32 < N1;
-                const v16f c = block_t(zero_unless(keep, raw1[set][blk][0]), zero_unless(keep, raw1[set][blk][1]));
-                r1f[nb][2 * blk] = to_frag(c, 0);
-                r1f[nb][2 * blk + 1] = to_frag(c, 1);
+            for (int nb = 0; nb < MB; ++nb) {
+                constexpr bool ALTERNATE = MB > 3;
+                const int set = ALTERNATE ? (nb & 1) : nb;
+                if (ALTERNATE && nb + 1 < MB) load_raw1(nb + 1, raw1[(nb + 1) & 1]);
+#pragma unroll
+                for (int blk = 0; blk < MB; ++blk) {
+                    const bool keep = 32 * blk + l32 < N1;
+                    const v16f c = block_t(zero_unless(keep, raw1[set][blk][0]), zero_unless(keep, raw1[set][blk][1]));
+                    r1f[nb][2 * blk] = to_frag(c, 0);
+                    r1f[nb][2 * blk + 1] = to_frag(c, 1);
+                }
             }
         }
         // The rows of R2 that repair the Givens rounding (one per q-slot) are picked out of the
@@ -488,14 +513,27 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
             zh[e] = hi;
             zl[e] = lo;
         }
+        // shared fragments of R1: those of step ks + 1 are read while step ks is multiplied
+        const v8h *r1s = reinterpret_cast<const v8h *>(lds + S::OFF_R1F) + lane;
+        v8h rb[R1LDS ? MB : 1], rb_n[R1LDS ? MB : 1];
+        if constexpr (R1LDS) {
+#pragma unroll
+            for (int nb = 0; nb < MB; ++nb) rb[nb] = r1s[(nb * KSB) * kWave];
+        }
 #pragma unroll
         for (int ks = 0; ks < KSB; ++ks) {
             const v8h zhv = __builtin_bit_cast(v8h, zh), zlv = __builtin_bit_cast(v8h, zl);
             constexpr int NMB = 2 * MB;          // MFMAs of this step
 #pragma unroll
             for (int j = 0; j < (NMB > 4 ? NMB : 4); ++j) {
-                if (j < NMB)
-                    accy[j / 2] = __builtin_amdgcn_mfma_f32_32x32x16_f16((j & 1) ? zlv : zhv, r1f[j / 2][ks], accy[j / 2], 0, 0, 0);
+                if constexpr (R1LDS) {
+                    if (j < NMB && (j & 1) == 0 && ks + 1 < KSB) rb_n[j / 2] = r1s[((j / 2) * KSB + ks + 1) * kWave];
+                    if (j < NMB)
+                        accy[j / 2] = __builtin_amdgcn_mfma_f32_32x32x16_f16((j & 1) ? zlv : zhv, rb[j / 2], accy[j / 2], 0, 0, 0);
+                } else {
+                    if (j < NMB)
+                        accy[j / 2] = __builtin_amdgcn_mfma_f32_32x32x16_f16((j & 1) ? zlv : zhv, r1f[j / 2][ks], accy[j / 2], 0, 0, 0);
+                }
                 if (ks + 1 < KSB) {
                     // pairs of the next step: 4 pairs spread over the MFMAs (all after the last if fewer)
                     const int per = (4 + NMB - 1) / NMB;
@@ -514,6 +552,10 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
             }
             zh = zh_n;
             zl = zl_n;
+            if constexpr (R1LDS) {
+#pragma unroll
+                for (int nb = 0; nb < MB; ++nb) rb[nb] = rb_n[nb];
+            }
         }
 
         // ---- per-token step: wave maximum now, token maximum after the barrier --------------
@@ -601,16 +643,16 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
 
 // OCC: workgroups per CU the registers allow (512 per lane and SIMD, one wave of each workgroup
 // per SIMD); the LDS the list needs may allow fewer.
-template <int N1, int N2, int QS_MAX, int NSX, int OCC>
+template <int N1, int N2, int QS_MAX, int NSX, int OCC, bool R1LDS = false>
 static sq_status launch_rotq_mfma_ring(const __half *X, int64_t ldx, int T, const RotqPlan &plan,
                                        const __half *R1, const __half *R2, uint8_t *Q, float *scales,
                                        float *xrot, hipStream_t st)
 {
-    using S = RotqShape<N1, N2, NSX>;
+    using S = RotqShape<N1, N2, NSX, R1LDS>;
     const int qsteps = (plan.n_qslots + 15) / 16;
     const int lds = S::lds_bytes(qsteps);
     if (lds > kMaxDynamicLds) return SQ_ERR_SHAPE;
-    auto kernel = rotate_quantize_mfma_kernel<N1, N2, OCC, QS_MAX, NSX>;
+    auto kernel = rotate_quantize_mfma_kernel<N1, N2, OCC, QS_MAX, NSX, R1LDS>;
     if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return SQ_ERR_LAUNCH;
     const int groups = (T + S::TPP - 1) / S::TPP;
     const int by_lds = (160 * 1024) / lds;
@@ -634,6 +676,15 @@ static sq_status launch_rotq_mfma_qs(const __half *X, int64_t ldx, int T, const 
         static const int forced = [] { const char *e = getenv("SQ_ROTQ_RING"); return e ? atoi(e) : 0; }();
         const bool ring2 = forced == 2 || (forced != 3 && T >= 4096);
         if (ring2) return launch_rotq_mfma_ring<N1, N2, QS_MAX, 2, 3>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st);
+    }
+    if constexpr (MB == 3 && QS_MAX == 4) {       // more than 64 q-slots never leave room for two workgroups
+        // With R1 in registers three row blocks need more than 256 of them: one workgroup per CU.
+        // With the shared copy in LDS and a ring of two tiles, two fit if the list's side tiles are
+        // small enough.  SQ_ROTQ_R1=reg forces the register variant (tuning aid).
+        using S2 = RotqShape<N1, N2, 2, true>;
+        static const bool force_reg = [] { const char *e = getenv("SQ_ROTQ_R1"); return e && e[0] == 'r'; }();
+        if (!force_reg && 2 * S2::lds_bytes((plan.n_qslots + 15) / 16) <= 160 * 1024)
+            return launch_rotq_mfma_ring<N1, N2, QS_MAX, 2, 2, true>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st);
     }
     return launch_rotq_mfma_ring<N1, N2, QS_MAX, 3, (MB <= 2) ? 2 : 1>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st);
 }
