@@ -33,8 +33,8 @@ RING_BYTES = 640 << 20          # > 2x the 256 MB Infinity Cache
 # profiles/w4a4_gemm_attn_proj.md and profiles/rotate_quantize_attn_proj.md (FETCH_SIZE and
 # WRITE_SIZE, each scaled by what the counter reads for a plain 256 MiB copy: x2.000 and x1.000).
 PROFILED_TRAFFIC = {
-    "attn_proj": {"gemm": {"fetch": 33792685, "write": 16777216},
-                  "rotate_quantize": {"fetch": 17089859, "write": 4227072}},
+    "attn_proj": {"gemm": {"fetch": 33792691, "write": 16777216},
+                  "rotate_quantize": {"fetch": 17090886, "write": 4227072}},
 }
 
 
