@@ -44,11 +44,13 @@ typedef enum {
 } sq_status;
 
 /* Limits (SQ_ERR_SHAPE beyond them): n1 <= 128, n2 <= 256 and n2 a multiple
- * of 8, K = n1*n2 <= 16384, P <= 64, K a multiple of 32 for the GEMM. */
+ * of 8, K = n1*n2 <= 16384, P <= 64, at most 2^30 rows per call of the row
+ * kernels (2^24 tokens for the GEMM), K a multiple of 32 for the GEMM. */
 #define SQ_MAX_N1 128
 #define SQ_MAX_N2 256
 #define SQ_MAX_K 16384
 #define SQ_MAX_GIVENS 64
+#define SQ_MAX_ROWS (1 << 30)
 
 /*
  * sq_rotate_quantize -- online rotation fused with per-token 4-bit quantization.

@@ -357,7 +357,7 @@ __global__ __launch_bounds__(256) void hadamard_left_kernel(const float *__restr
 
 bool build_shape_ok(int64_t T, int32_t K, int32_t n1, int32_t n2, int32_t P)
 {
-    if (T < 1 || T > 0x7FFFFFFF || K <= 0 || P < 0 || P > SQ_MAX_GIVENS) return false;
+    if (T < 1 || T > SQ_MAX_ROWS || K <= 0 || P < 0 || P > SQ_MAX_GIVENS) return false;
     if (n1 < 2 || n1 > SQ_MAX_N1 || n2 < 8 || n2 > SQ_MAX_N2 || (n2 & (n2 - 1)) != 0) return false;
     return (int64_t)n1 * n2 == K && K <= SQ_MAX_K;
 }

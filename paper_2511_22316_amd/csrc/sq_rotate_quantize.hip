@@ -212,7 +212,7 @@ extern "C" sq_status sq_rotate_quantize(const void *X, int64_t T, int32_t K, int
     if (T < 0 || K <= 0 || n1 <= 0 || n2 <= 0 || P < 0) return SQ_ERR_SHAPE;
     if (n1 > SQ_MAX_N1 || n2 > SQ_MAX_N2 || P > SQ_MAX_GIVENS) return SQ_ERR_SHAPE;
     if ((int64_t)n1 * n2 != K || (n2 % 8) != 0 || K > SQ_MAX_K || ldx < K) return SQ_ERR_SHAPE;
-    if (T > 0x7fffffff) return SQ_ERR_SHAPE;
+    if (T > SQ_MAX_ROWS) return SQ_ERR_SHAPE;
     if (P > 0 && (!giv_i || !giv_j || !giv_theta)) return SQ_ERR_NULL;
     if (!R1 || !R2) return SQ_ERR_NULL;
     if (T > 0 && (!X || !Q || !scales)) return SQ_ERR_NULL;
