@@ -9,10 +9,13 @@
 // One wave owns 32 columns q' of one token through both stages: the 32x32 accumulator layout of
 // stage A (lane = column, registers = rows p) is, register for register, the operand layout stage
 // B needs for its contraction over p, so Z never leaves the registers.  R2 and R1 are held in
-// registers as MFMA operands for the life of the workgroup, which walks over many tokens.
+// registers as MFMA operands for the life of the workgroup, which walks over many tokens (for
+// three 32-row blocks the fragments of R1, which every wave needs alike, are kept once in LDS
+// instead, so that the registers allow a second workgroup on the CU).
 //
-// Token rows stream from HBM straight into a ring of three LDS tiles (global_load_lds), two rows
-// ahead of the one being multiplied; two workgroups share a CU, so four rows per CU are in flight.
+// Token rows stream from HBM straight into a ring of LDS tiles (global_load_lds): three tiles, two
+// rows ahead of the one being multiplied, with two workgroups per CU; or two tiles where that
+// makes room for one more workgroup per CU.
 // The loop is rotated so that the MFMAs of stage A of the NEXT token are issued between the VALU
 // instructions that quantize the current one, and the hi/lo split of the next stage-B step
 // between the MFMAs of the current step.
