@@ -165,6 +165,7 @@ def test_rotate_quantize_givens_list_touching_every_column(oracle, name):
 
 
 @pytest.mark.parametrize("n1,n2,P", [(32, 32, 8), (32, 64, 16), (80, 64, 24),      # matrix-core kernel
+                                     (80, 64, 6), (80, 64, 0), (86, 128, 0),        # ... with R1 shared in LDS
                                      (128, 64, 32), (108, 128, 24), (112, 128, 64), (128, 128, 48),
                                      (24, 40, 6), (12, 8, 3), (128, 16, 10)])       # generic kernel
 def test_rotate_quantize_other_factor_shapes(oracle, n1, n2, P):
@@ -201,14 +202,14 @@ def test_rotate_quantize_four_row_blocks_many_tokens(oracle, n1, n2, wide_list):
     assert np.all(np.max(np.abs(codes_of(Qg)), axis=1) == 7)
 
 
-@pytest.mark.parametrize("with_list", [True, False])
-def test_rotate_quantize_64x64_many_tokens(oracle, with_list):
+@pytest.mark.parametrize("T,with_list", [(5000, True), (5000, False), (4097, True)])
+def test_rotate_quantize_64x64_many_tokens(oracle, T, with_list):
     """From 4096 tokens on, the 64 x 64 shape runs with a ring of two tiles and three workgroups per
-    CU: 5000 tokens (every workgroup walks its ring several times, the last pass is ragged),
-    sampled rows against the oracle, with the layer's Givens list and without one."""
-    print(f"case rotate_quantize attn_proj T=5000 list={with_list}", flush=True)
+    CU: 5000 tokens (every workgroup walks its ring several times, the last pass is ragged) and
+    4097 (the last pair of token slots is half empty), sampled rows against the oracle, with the
+    layer's Givens list and without one."""
+    print(f"case rotate_quantize attn_proj T={T} list={with_list}", flush=True)
     cfg = synth.CONFIGS["attn_proj"]
-    T = 5000
     L = synth.layer(cfg, T)
     if not with_list:
         e = np.zeros(0, np.int32)
