@@ -142,6 +142,9 @@ def measure_layer(cfg, torch, sq, synth, steps, warmup):
         "gemm_weight_stream_GBps": (N * K / 2) / (gm_ms * 1e-3) / 1e9,
         "ring_sets": B.sets, "settle_steps": settled,
     }
+    out["rotate_quant_frac_of_hbm_peak"] = out["rotate_quant_GBps"] / HBM_PEAK_GBPS
+    out["gemm_frac_of_int8_peak"] = out["gemm_int_TOPS"] / INT8_MFMA_PEAK_TOPS
+    out["gemm_weight_stream_frac_of_hbm_peak"] = out["gemm_weight_stream_GBps"] / HBM_PEAK_GBPS
     del B
     torch.cuda.empty_cache()
     return out
