@@ -29,12 +29,18 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 INT8_MFMA_PEAK_TOPS = 5000.0    # MI355X dense int8 matrix peak
 RING_BYTES = 640 << 20          # > 2x the 256 MB Infinity Cache
 
-# HBM-side bytes per launch on the headline workload, from the rocprofv3 --pmc runs summarised in
-# profiles/w4a4_gemm_attn_proj.md and profiles/rotate_quantize_attn_proj.md (FETCH_SIZE and
+# HBM-side bytes per launch, from the rocprofv3 --pmc runs summarised in
+# profiles/w4a4_gemm_<workload>.md and profiles/rotate_quantize_<workload>.md (FETCH_SIZE and
 # WRITE_SIZE, each scaled by what the counter reads for a plain 256 MiB copy: x2.000 and x1.000).
 PROFILED_TRAFFIC = {
-    "attn_proj": {"gemm": {"fetch": 33792691, "write": 16777216},
-                  "rotate_quantize": {"fetch": 17090886, "write": 4227072}},
+    "attn_proj": {"gemm": {"fetch": 33792664, "write": 16777216},
+                  "rotate_quantize": {"fetch": 17090872, "write": 4227072}},
+    "mlp_down": {"gemm": {"fetch": 90409989, "write": 16777216},
+                 "rotate_quantize": {"fetch": 45737420, "write": 11337728}},
+    "decode": {"gemm": {"fetch": 117976463, "write": 468032},
+               "rotate_quantize": {"fetch": 677820, "write": 33024}},
+    "large_prefill": {"gemm": {"fetch": 1411945426, "write": 469762048},
+                      "rotate_quantize": {"fetch": 134759049, "write": 33816576}},
 }
 
 
@@ -248,8 +254,18 @@ def main() -> int:
     gemm_tops = head["gemm_int_TOPS"]
     prof = PROFILED_TRAFFIC.get(cfg.name, {})
     traffic = lambda k: (prof[k]["fetch"] + prof[k]["write"]) if k in prof else None
+    if cfg.T <= 64:      # decode-shaped GEMM: one pass over the weights, HBM-bound
+        gemm_roofline = {"kernel": "w4a4_gemm_skinny_kernel", "bound": "hbm", "achieved": head["gemm_weight_stream_GBps"],
+                         "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": head["gemm_weight_stream_GBps"] / HBM_PEAK_GBPS,
+                         "bytes_per_launch": cfg.N * cfg.K / 2.0, "traffic": traffic("gemm"),
+                         "traffic_detail": prof.get("gemm")}
+    else:
+        gemm_roofline = {"kernel": "w4a4_gemm_kernel", "bound": "mfma", "achieved": gemm_tops,
+                         "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": gemm_tops / INT8_MFMA_PEAK_TOPS,
+                         "ops_per_launch": gemm_ops(cfg.T, cfg.K, cfg.N), "traffic": traffic("gemm"),
+                         "traffic_detail": prof.get("gemm")}
     result = {
-        "metric": "layer time, rotate+quant then W4A4 GEMM, T=2048 K=N=4096 (also: rotate+quant HBM GB/s, GEMM int TOPS)",
+        "metric": f"layer time, rotate+quant then W4A4 GEMM, T={cfg.T} K={cfg.K} N={cfg.N} (also: rotate+quant HBM GB/s, GEMM int TOPS)",
         "value": head["layer_us"], "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": head["layer_us"] / 1e3, "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "int4 codes on int8 MFMA, int32 accumulate; fp32 rotation",
@@ -258,10 +274,7 @@ def main() -> int:
                    "ring_sets": head["ring_sets"], "settle_steps_before_warmup": head["settle_steps"]},
         "rotate_quant_GBps": head["rotate_quant_GBps"], "gemm_int_TOPS": gemm_tops,
         "rotate_quant_us": head["rotate_quant_us"], "gemm_us": head["gemm_us"],
-        "roofline": {"kernel": "w4a4_gemm_kernel", "bound": "mfma", "achieved": gemm_tops,
-                     "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": gemm_tops / INT8_MFMA_PEAK_TOPS,
-                     "ops_per_launch": gemm_ops(cfg.T, cfg.K, cfg.N), "traffic": traffic("gemm"),
-                     "traffic_detail": prof.get("gemm")},
+        "roofline": gemm_roofline,
         "roofline_rotate_quant": {"kernel": "rotate_quantize", "bound": "hbm", "achieved": head["rotate_quant_GBps"],
                                   "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                                   "frac": head["rotate_quant_GBps"] / HBM_PEAK_GBPS,
