@@ -147,6 +147,7 @@ def measure_layer(cfg, torch, sq, synth, steps, warmup):
         "gemm_int_TOPS": gemm_ops(T, K, N) / (gm_ms * 1e-3) / 1e12,
         "gemm_weight_stream_GBps": (N * K / 2) / (gm_ms * 1e-3) / 1e9,
         "ring_sets": B.sets, "settle_steps": settled,
+        "massive_channels": [int(c) for c in synth.massive_channels(cfg)],
     }
     out["rotate_quant_frac_of_hbm_peak"] = out["rotate_quant_GBps"] / HBM_PEAK_GBPS
     out["gemm_frac_of_int8_peak"] = out["gemm_int_TOPS"] / INT8_MFMA_PEAK_TOPS
@@ -246,7 +247,7 @@ def main() -> int:
     head = measure_layer(cfg, torch, sq, synth, args.steps, args.warmup)
     extra = {}
     if not args.no_extra:
-        for name, st in (("mlp_down", max(10, args.steps // 4)), ("decode", args.steps),
+        for name, st in (("tiny", args.steps), ("mlp_down", max(10, args.steps // 4)), ("decode", args.steps),
                          ("large_prefill", max(5, args.steps // 20))):
             if name != args.workload:
                 extra[name] = measure_layer(synth.CONFIGS[name], torch, sq, synth, st, max(2, args.warmup // 4))
@@ -271,7 +272,8 @@ def main() -> int:
         "vs_baseline": None, "dtype": "int4 codes on int8 MFMA, int32 accumulate; fp32 rotation",
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: T={cfg.T} K={cfg.K} ({cfg.n1}x{cfg.n2}) N={cfg.N}, {cfg.P} Givens pairs",
-                   "ring_sets": head["ring_sets"], "settle_steps_before_warmup": head["settle_steps"]},
+                   "ring_sets": head["ring_sets"], "settle_steps_before_warmup": head["settle_steps"],
+                   "massive_channels": head["massive_channels"]},
         "rotate_quant_GBps": head["rotate_quant_GBps"], "gemm_int_TOPS": gemm_tops,
         "rotate_quant_us": head["rotate_quant_us"], "gemm_us": head["gemm_us"],
         "roofline": gemm_roofline,
