@@ -216,16 +216,45 @@ extern "C" sq_status sq_rotate_quantize(const void *X, int64_t T, int32_t K, int
     if (P > 0 && (!giv_i || !giv_j || !giv_theta)) return SQ_ERR_NULL;
     if (!R1 || !R2) return SQ_ERR_NULL;
     if (T > 0 && (!X || !Q || !scales)) return SQ_ERR_NULL;
-    sq::GivensList giv;
-    giv.count = P;
-    for (int p = 0; p < P; ++p) {
-        if (giv_i[p] < 0 || giv_i[p] >= K || giv_j[p] < 0 || giv_j[p] >= K || giv_i[p] == giv_j[p])
-            return SQ_ERR_INDEX;
-        giv.i[p] = giv_i[p];
-        giv.j[p] = giv_j[p];
-        giv.c[p] = (float)cos((double)giv_theta[p]);
-        giv.s[p] = (float)sin((double)giv_theta[p]);
+    // The list as the kernels take it (cos / sin, and the regrouping into levels) is kept from the
+    // last call of this thread and reused when the same list comes again, which is what a layer
+    // called once per forward pass sends.
+    struct Prepared {
+        int32_t count = -1, channels = 0, cols = 0;
+        int32_t i[SQ_MAX_GIVENS], j[SQ_MAX_GIVENS];
+        float theta[SQ_MAX_GIVENS];
+        sq::GivensList giv;
+        sq::RotqPlan plan;
+        bool plan_ok = false;
+    };
+    static thread_local Prepared prep;
+    const bool same = prep.count == P && prep.channels == K && prep.cols == n2 &&
+                      (P == 0 || (memcmp(prep.i, giv_i, sizeof(int32_t) * P) == 0 &&
+                                  memcmp(prep.j, giv_j, sizeof(int32_t) * P) == 0 &&
+                                  memcmp(prep.theta, giv_theta, sizeof(float) * P) == 0));
+    if (!same) {
+        prep.count = -1;                     // stays invalid if a check below fails
+        sq::GivensList &g = prep.giv;
+        g.count = P;
+        for (int p = 0; p < P; ++p) {
+            if (giv_i[p] < 0 || giv_i[p] >= K || giv_j[p] < 0 || giv_j[p] >= K || giv_i[p] == giv_j[p])
+                return SQ_ERR_INDEX;
+            g.i[p] = giv_i[p];
+            g.j[p] = giv_j[p];
+            g.c[p] = (float)cos((double)giv_theta[p]);
+            g.s[p] = (float)sin((double)giv_theta[p]);
+        }
+        prep.plan_ok = sq::build_rotq_plan(g, n2, prep.plan);
+        if (P > 0) {
+            memcpy(prep.i, giv_i, sizeof(int32_t) * P);
+            memcpy(prep.j, giv_j, sizeof(int32_t) * P);
+            memcpy(prep.theta, giv_theta, sizeof(float) * P);
+        }
+        prep.channels = K;
+        prep.cols = n2;
+        prep.count = P;
     }
+    const sq::GivensList &giv = prep.giv;
     if ((ldx % 8) != 0 || ((uintptr_t)X & 15) || ((uintptr_t)Q & 15) || ((uintptr_t)R1 & 15) ||
         ((uintptr_t)R2 & 15) || ((uintptr_t)scales & 3) || ((uintptr_t)xrot_dbg & 3))
         return SQ_ERR_ALIGN;
@@ -235,10 +264,9 @@ extern "C" sq_status sq_rotate_quantize(const void *X, int64_t T, int32_t K, int
     // matrix-core kernel for the shapes it covers (n2 in {32, 64, 128}, n1 <= 128); the plain-FMA
     // kernel takes every other shape.  SQ_ROTQ_GENERIC=1 forces the latter (tuning aid).
     static const bool force_generic = [] { const char *e = getenv("SQ_ROTQ_GENERIC"); return e && e[0] == '1'; }();
-    sq::RotqPlan plan;
-    if (!force_generic && sq::build_rotq_plan(giv, n2, plan)) {
+    if (!force_generic && prep.plan_ok) {
         sq_status status = SQ_OK;
-        if (sq::rotq_mfma_dispatch(static_cast<const __half *>(X), ldx, (int)T, n1, n2, plan,
+        if (sq::rotq_mfma_dispatch(static_cast<const __half *>(X), ldx, (int)T, n1, n2, prep.plan,
                                    static_cast<const __half *>(R1), static_cast<const __half *>(R2), Q,
                                    scales, xrot_dbg, st, &status))
             return status;
