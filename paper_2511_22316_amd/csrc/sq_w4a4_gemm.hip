@@ -644,8 +644,8 @@ extern "C" sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T,
     if ((K % 256) != 0) return sq::launch_generic(Qx, sx, (int)T, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
     // Kernel choice, from few tokens to many.  The two large tile shapes run eight waves per CU
     // (two per SIMD): the VALU work of widening nibbles issues nearly twice as fast from two waves
-    // as from one.  Large problems take 256x256 tiles (64x128 per wave: fewer VALU ops per MFMA);
-    // smaller ones take 128x256 tiles so that every CU gets work.  SQ_GEMM_TILE=0..13 overrides the choice (tuning aid).
+    // as from one.  256x256 tiles (64x128 per wave: fewer VALU ops per MFMA) or 128x256 tiles,
+    // whichever needs less time for its rounds over the CUs.  SQ_GEMM_TILE=0..13 overrides the choice (tuning aid).
     static const int forced = [] { const char *e = getenv("SQ_GEMM_TILE"); return e ? atoi(e) : -1; }();
     const int Ti = (int)T;
     int choice = forced;
@@ -658,7 +658,16 @@ extern "C" sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T,
         const int64_t wide = (int64_t)((Ti + 127) / 128) * ((N + 255) / 256);
         if (wide <= 128) choice = (2 * wide <= 256) ? 5 : 2;
     }
-    if (choice < 0) choice = ((int64_t)((Ti + 255) / 256) * ((N + 255) / 256) >= 512) ? 4 : 1;
+    // 128x256 or 256x256 tiles: one workgroup per CU either way, so the time goes with the number
+    // of rounds of 256 tiles; a 256x256 tile takes about 1.8 times as long as a 128x256 one (twice
+    // the work at a slightly better rate).  Measured with random codes on shapes from 1024 x 11008
+    // to 8192 x 28672.
+    if (choice < 0) {
+        const int64_t n_small = (int64_t)((Ti + 127) / 128) * ((N + 255) / 256);
+        const int64_t n_large = (int64_t)((Ti + 255) / 256) * ((N + 255) / 256);
+        const int64_t rounds_small = (n_small + 255) / 256, rounds_large = (n_large + 255) / 256;
+        choice = (20 * rounds_small > 37 * rounds_large) ? 4 : 1;
+    }
     switch (choice) {
         case 0: return sq::launch_main<2, 2, 2, 4, 128, 1>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
         case 2: return sq::launch_main<2, 2, 2, 2, 64, 2>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
