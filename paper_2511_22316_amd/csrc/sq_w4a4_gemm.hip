@@ -358,9 +358,9 @@ __global__ __launch_bounds__(WM *WN *kWave, OCC) void w4a4_gemm_kernel(
     }
     __syncthreads();
     constexpr int CPRY = BN / 8;         // 16-byte chunks per output row
-    constexpr int ROUNDS = BM * CPRY / NT, BATCH = 4;
-    static_assert((BM * CPRY) % (NT * BATCH) == 0, "copy-out rounds come in batches of four");
-    for (int r0 = 0; r0 < ROUNDS; r0 += BATCH) {       // four LDS reads in flight, then their stores
+    constexpr int ROUNDS = BM * CPRY / NT, BATCH = (ROUNDS % 4 == 0) ? 4 : (ROUNDS % 2 == 0) ? 2 : 1;
+    static_assert((BM * CPRY) % NT == 0, "every thread copies the same number of chunks");
+    for (int r0 = 0; r0 < ROUNDS; r0 += BATCH) {       // up to four LDS reads in flight, then their stores
         uint4 v[BATCH];
 #pragma unroll
         for (int u = 0; u < BATCH; ++u) {
@@ -653,6 +653,14 @@ extern "C" sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T,
     // (token blocks, channels per workgroup, K split) keeps about eight waves on every CU.
     if (choice < 0 && Ti <= 32) choice = (N >= 64 * 384) ? 8 : (N >= 32 * 256 ? 9 : 7);
     if (choice < 0 && Ti <= 64) choice = (N >= 32 * 256) ? 12 : 13;
+    // Few tokens times few output channels: even 128x128 tiles would be too few for 256 CUs, and the
+    // time is one workgroup's walk over K.  64x64 tiles (four times as many workgroups) up to 64
+    // tiles of 128x128, 64x128 tiles up to 128.  (T = 128, K = N = 4096: 19.9 -> 14.6 us.)
+    if (choice < 0) {
+        const int64_t n128 = (int64_t)((Ti + 127) / 128) * ((N + 127) / 128);
+        if (n128 <= 64) choice = 10;
+        else if (n128 <= 128) choice = 11;
+    }
     // Up to a few hundred tokens 128x256 tiles would leave CUs idle: 128x128 tiles (four waves).
     if (choice < 0) {
         const int64_t wide = (int64_t)((Ti + 127) / 128) * ((N + 255) / 256);
@@ -675,6 +683,8 @@ extern "C" sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T,
         case 4: return sq::launch_main<4, 2, 2, 4, 64, 1>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
         case 5: return sq::launch_main<2, 2, 2, 2, 128, 1>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
         case 6: return sq::launch_main<2, 4, 2, 2, 64, 1>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
+        case 10: return sq::launch_main<2, 2, 1, 1, 128, 2>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
+        case 11: return sq::launch_main<2, 2, 1, 2, 128, 2>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
         case 7: if (Ti <= 32) return sq::launch_skinny<1, 1, 16>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
         case 8: if (Ti <= 32) return sq::launch_skinny<1, 2, 4>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
         case 9: if (Ti <= 32) return sq::launch_skinny<1, 1, 8>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
