@@ -651,8 +651,12 @@ extern "C" sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T,
     int choice = forced;
     // At most 64 tokens: one pass over the weights by the decode-shaped kernel; its launch shape
     // (token blocks, channels per workgroup, K split) keeps about eight waves on every CU.
+    // From 33 tokens on (17 with very many channels) and 10240 channels on, 64x64 / 64x128 tiles of
+    // the tile kernel are faster than its token blocks (T = 64, K = 8192, N = 28672: 48.7 -> 32.2 us).
+    if (choice < 0 && Ti <= 64 && N >= 10240 && (Ti > 32 || (Ti > 16 && N >= 64 * 384)))
+        choice = (N >= 64 * 384 && Ti > 32) ? 11 : 10;
     if (choice < 0 && Ti <= 32) choice = (N >= 64 * 384) ? 8 : (N >= 32 * 256 ? 9 : 7);
-    if (choice < 0 && Ti <= 64) choice = (N >= 32 * 256) ? 12 : 13;
+    if (choice < 0 && Ti <= 64) choice = 13;
     // Few tokens times few output channels: even 128x128 tiles would be too few for 256 CUs, and the
     // time is one workgroup's walk over K.  64x64 tiles (four times as many workgroups) up to 64
     // tiles of 128x128, 64x128 tiles up to 128.  (T = 128, K = N = 4096: 19.9 -> 14.6 us.)
@@ -688,7 +692,6 @@ extern "C" sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T,
         case 7: if (Ti <= 32) return sq::launch_skinny<1, 1, 16>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
         case 8: if (Ti <= 32) return sq::launch_skinny<1, 2, 4>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
         case 9: if (Ti <= 32) return sq::launch_skinny<1, 1, 8>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
-        case 12: if (Ti <= 64) return sq::launch_skinny<2, 2, 4>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
         case 13: if (Ti <= 64) return sq::launch_skinny<2, 1, 8>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
         default: break;
     }

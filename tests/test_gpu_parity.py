@@ -273,8 +273,10 @@ def test_rotate_quantize_identity_rotation_is_exact(oracle):
                                    # at most 32 tokens: the decode-shaped kernel in its three launch
                                    # shapes, one K slice only / ragged channel tails / T = 32
                                    (1, 256, 33), (32, 768, 8200), (31, 512, 24600), (33, 512, 300),
-                                   # 33..128 tokens: the same kernel with two and four token blocks
-                                   (64, 768, 16500), (48, 512, 300), (100, 512, 260), (128, 256, 64),
+                                   # 33..64 tokens: the same kernel with two token blocks (few
+                                   # channels) or 64x64 tiles (many); 65..128 tokens: 64x64 tiles
+                                   (64, 768, 16500), (48, 512, 300), (40, 512, 30000), (20, 256, 25000),
+                                   (100, 512, 260), (128, 256, 64),
                                    # a few hundred tokens: 64x64, 64x128 and 128x128 tiles
                                    (129, 512, 520), (400, 768, 1000), (512, 512, 4096), (300, 512, 8200)])
 def test_gemm_random_codes_bit_exact(oracle, T, K, N):
