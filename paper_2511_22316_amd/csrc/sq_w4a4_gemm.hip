@@ -75,20 +75,34 @@ __device__ __forceinline__ void load_to_lds_16_if(const void *gptr, uint32_t lds
                  : "memory", "m0", "scc");
 }
 
-// Wait until at most N global loads are outstanding if a < b, else until none is; then drain the
-// wave's LDS reads and meet the other waves at the barrier.  Branch inside the assembly as above.
-template <int N>
-__device__ __forceinline__ void wait_loads_and_barrier(int a, int b)
+// Ring of NS stages, L loads per wave and tile, `rem` tiles exist beyond the one that must have
+// landed (rem may be negative).  Loads complete in order, so that tile is in LDS once at most
+// min(rem, NS - 2) * L loads are outstanding: wait for the largest count first and step down only
+// in the last turns.  Then the LDS reads are drained and the waves meet at the barrier.
+template <int L, int NS>
+__device__ __forceinline__ void wait_tile_and_barrier(int rem)
 {
-    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-    asm volatile("s_cmp_lt_i32 %0, %1\n\t"
-                 "s_cbranch_scc1 .Lsq_keep_%=\n\t"
+    constexpr int D = NS - 2;
+    static_assert(D >= 1 && D <= 4 && D * L < 64, "vmcnt is a 6-bit counter; at most four levels");
+    constexpr int d0 = D, d1 = D > 1 ? D - 1 : 0, d2 = D > 2 ? D - 2 : 0, d3 = D > 3 ? D - 3 : 0;
+    asm volatile("s_waitcnt vmcnt(%1)\n\t"
+                 "s_cmp_ge_i32 %0, %2\n\t"
+                 "s_cbranch_scc1 .Lsq_landed_%=\n\t"
+                 "s_waitcnt vmcnt(%3)\n\t"
+                 "s_cmp_ge_i32 %0, %4\n\t"
+                 "s_cbranch_scc1 .Lsq_landed_%=\n\t"
+                 "s_waitcnt vmcnt(%5)\n\t"
+                 "s_cmp_ge_i32 %0, %6\n\t"
+                 "s_cbranch_scc1 .Lsq_landed_%=\n\t"
+                 "s_waitcnt vmcnt(%7)\n\t"
+                 "s_cmp_ge_i32 %0, %8\n\t"
+                 "s_cbranch_scc1 .Lsq_landed_%=\n\t"
                  "s_waitcnt vmcnt(0)\n"
-                 ".Lsq_keep_%=:\n\t"
-                 "s_waitcnt vmcnt(%2) lgkmcnt(0)\n\t"
+                 ".Lsq_landed_%=:\n\t"
+                 "s_waitcnt lgkmcnt(0)\n\t"
                  "s_barrier"
                  :
-                 : "s"(a), "s"(b), "n"(N)
+                 : "s"(rem), "n"(d0 * L), "n"(d0), "n"(d1 * L), "n"(d1), "n"(d2 * L), "n"(d2), "n"(d3 * L), "n"(d3)
                  : "memory", "scc");
 }
 
@@ -138,17 +152,22 @@ __device__ __forceinline__ void store_tile(const v16i (&acc)[FM][FN], int row_ba
 // Main kernel (K % (2*BKB) == 0).  Block tile (WM*FM*32) x (WN*FN*32), WM x WN waves, each FM x FN
 // fragments of 32x32.  K is walked in tiles of 2*BKB codes (BKB bytes per row).  Tiles go from
 // global memory straight into LDS (global_load_lds, 16 bytes per lane, no register staging)
-// through a ring of three stages, two tiles ahead of the one being multiplied.  The epilogue
+// through a ring of NS stages, NS - 1 tiles ahead of the one being multiplied (three stages in
+// every launch shape: deeper rings measured no faster, for large tiles or small).  The epilogue
 // stages the fp16 tile in LDS and writes it out in full 16-byte, row-contiguous stores.
 // ------------------------------------------------------------------------------------------
-template <int WM, int WN, int FM, int FN, int BKB, int OCC>
-__global__ __launch_bounds__(WM *WN *kWave, OCC) void w4a4_gemm_kernel(
+// KG = 2: two groups of WM x WN waves share the block tile and split K in halves (group g walks
+// bytes [g Kb/2, (g+1) Kb/2) of every row); the second group's accumulators are added to the
+// first's through LDS before the epilogue.  For tiles so small that the time is the walk over K.
+template <int WM, int WN, int FM, int FN, int BKB, int OCC, int KG, int NS>
+__global__ __launch_bounds__(KG *WM *WN *kWave, OCC) void w4a4_gemm_kernel(
     const uint8_t *__restrict__ Qx, const float *__restrict__ sx, int T, int Kb,
     const uint8_t *__restrict__ Qw, const float *__restrict__ sw, int N, __half *__restrict__ Y,
     int64_t ldy, int32_t *__restrict__ acc_dbg, int tiles_m, int tiles_n, int vec_store)
 {
-    constexpr int NS = 3;
-    constexpr int NW = WM * WN, NT = NW * kWave;
+    static_assert(NS >= 3 && NS <= 6, "ring of three to six stages");
+    static_assert(KG == 1 || KG == 2, "one or two K groups");
+    constexpr int NW = WM * WN, NT = KG * NW * kWave;          // NW: waves of one K group
     constexpr int CPR = BKB / 16;                 // 16-byte chunks per tile row
     constexpr int STEPS = CPR / 2;                // steps of 64 codes per tile
     constexpr int RPL = kWave / CPR;              // tile rows filled by one wave-wide load
@@ -161,8 +180,15 @@ __global__ __launch_bounds__(WM *WN *kWave, OCC) void w4a4_gemm_kernel(
 
     extern __shared__ uint4 smem[];
 
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int tid = threadIdx.x, lane = tid & (kWave - 1);
+    const int kg = (tid / kWave) / NW, wave = (tid / kWave) % NW;   // K group, wave within it
     const int wm = wave / WN, wn = wave % WN;
+    if constexpr (KG == 2) {                 // this group's half of K
+        Kb /= 2;
+        Qx += kg * Kb;
+        Qw += kg * Kb;
+    }
+    const int row_bytes = KG * Kb;           // distance between rows in memory
     int bm, bn;
     tile_of_workgroup(tiles_m, tiles_n, bm, bn);
     const int row0 = bm * BM, col0 = bn * BN;
@@ -176,16 +202,17 @@ __global__ __launch_bounds__(WM *WN *kWave, OCC) void w4a4_gemm_kernel(
     const uint8_t *b_src[B_LOADS];
 #pragma unroll
     for (int g = 0; g < A_LOADS; ++g)   // rows past the end are clamped: their products are never stored
-        a_src[g] = Qx + (int64_t)min(row0 + RPL * (wave + NW * g) + lrow, T - 1) * Kb + lchunk * 16;
+        a_src[g] = Qx + (int64_t)min(row0 + RPL * (wave + NW * g) + lrow, T - 1) * row_bytes + lchunk * 16;
 #pragma unroll
     for (int g = 0; g < B_LOADS; ++g)
-        b_src[g] = Qw + (int64_t)min(col0 + RPL * (wave + NW * g) + lrow, N - 1) * Kb + lchunk * 16;
+        b_src[g] = Qw + (int64_t)min(col0 + RPL * (wave + NW * g) + lrow, N - 1) * row_bytes + lchunk * 16;
 
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)smem;
     const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const uint32_t group_byte = __builtin_amdgcn_readfirstlane(kg) * (STAGE_SLOTS * 16);   // this group's part of a stage
     // loads of tile kt into ring stage `stage`, issued only if kt < limit
     auto issue_tile = [&](int kt, int stage, int limit) {
-        const uint32_t sa = lds_base + (uint32_t)stage * (STAGE_SLOTS * 16) + wave_u * 1024;
+        const uint32_t sa = lds_base + (uint32_t)stage * (KG * STAGE_SLOTS * 16) + group_byte + wave_u * 1024;
         const uint32_t sb = sa + A_SLOTS * 16;
         const int kb0 = kt * BKB;
 #pragma unroll
@@ -207,12 +234,12 @@ __global__ __launch_bounds__(WM *WN *kWave, OCC) void w4a4_gemm_kernel(
 
     // LDS byte offsets of this lane's fragment chunks inside a stage, per step s (the step picks
     // logical chunk 2s + fhalf; the swizzle depends on row % 8 = frow % 8 for every fragment).
-    constexpr int STAGE_BYTES = STAGE_SLOTS * 16, FRAG_BYTES = 32 * BKB;
+    constexpr int STAGE_BYTES = KG * STAGE_SLOTS * 16, FRAG_BYTES = 32 * BKB;
     int a_off[STEPS], b_off[STEPS];
 #pragma unroll
     for (int s = 0; s < STEPS; ++s) {
-        a_off[s] = lds_chunk_slot<BKB>(wm * FM * 32 + frow, 2 * s + fhalf) * 16;
-        b_off[s] = A_SLOTS * 16 + lds_chunk_slot<BKB>(wn * FN * 32 + frow, 2 * s + fhalf) * 16;
+        a_off[s] = kg * (STAGE_SLOTS * 16) + lds_chunk_slot<BKB>(wm * FM * 32 + frow, 2 * s + fhalf) * 16;
+        b_off[s] = kg * (STAGE_SLOTS * 16) + A_SLOTS * 16 + lds_chunk_slot<BKB>(wn * FN * 32 + frow, 2 * s + fhalf) * 16;
     }
     const char *lds = reinterpret_cast<const char *>(smem);
 
@@ -264,19 +291,18 @@ __global__ __launch_bounds__(WM *WN *kWave, OCC) void w4a4_gemm_kernel(
     // drains them), so its stage can take tile kt+3.
 #define SQ_GEMM_TURN()                                                                               \
     do {                                                                                             \
-        wait_loads_and_barrier<LOADS>(kt + 2, ktiles);                                               \
-        issue_tile(kt + 3, st_cur, ktiles);                                                          \
+        wait_tile_and_barrier<LOADS, NS>(ktiles - kt - 2);                                           \
+        issue_tile(kt + NS, st_cur, ktiles);                                                         \
     } while (0)
 
     // prologue: tiles 0 and 1 in flight, wait for tile 0, start tile 2, first fragments ready
-    issue_tile(0, 0, ktiles);
-    issue_tile(1, 1, ktiles);
+#pragma unroll
+    for (int t = 0; t < NS - 1; ++t) issue_tile(t, t, ktiles);
     // While the first tiles are on their way, the block's dequantization steps are parked in LDS
     // behind the ring and the staged output tile, so that the epilogue does not wait on global
     // memory: sx * 2^-8 for the BM tokens (the accumulators carry a factor 256), then sw for the
     // BN output channels; 0 past the edges.
-    constexpr int SCALE_BYTE = (3 * STAGE_SLOTS * 16 > BM * (BN * 2 + 16)) ? 3 * STAGE_SLOTS * 16
-                                                                           : BM * (BN * 2 + 16);
+    constexpr int SCALE_BYTE = (NS * STAGE_BYTES > BM * (BN * 2 + 16)) ? NS * STAGE_BYTES : BM * (BN * 2 + 16);
     float *scale_lds = reinterpret_cast<float *>(reinterpret_cast<char *>(smem) + SCALE_BYTE);
     for (int r = tid; r < BM + BN; r += NT) {
         float v;
@@ -285,8 +311,8 @@ __global__ __launch_bounds__(WM *WN *kWave, OCC) void w4a4_gemm_kernel(
         scale_lds[r] = v;
     }
 
-    wait_loads_and_barrier<LOADS>(1, ktiles);
-    issue_tile(2, 2, ktiles);
+    wait_tile_and_barrier<LOADS, NS>(ktiles - 1);
+    issue_tile(NS - 1, NS - 1, ktiles);
     read_step(0, 0);
 #pragma unroll
     for (int c = 0; c < FM + FN; ++c) widen_chunk(raw[c], frag[0][c][0], frag[0][c][1]);
@@ -322,6 +348,30 @@ __global__ __launch_bounds__(WM *WN *kWave, OCC) void w4a4_gemm_kernel(
     wait_vmcnt<0>();
     block_barrier();                     // the ring is dead: reuse it for the output tile
     char *ys = reinterpret_cast<char *>(smem);
+    if constexpr (KG == 2) {
+        // partial sums of the second group, parked behind where the output tile will be staged
+        constexpr int PART_BYTE = (BM * YS + 15) / 16 * 16;
+        static_assert(PART_BYTE + NW * FM * FN * 16 * kWave * 4 <= NS * STAGE_BYTES, "partial sums must fit in the dead ring");
+        int *part = reinterpret_cast<int *>(ys + PART_BYTE) + wave * (FM * FN * 16 * kWave) + lane;
+        if (kg == 1) {
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) part[((i * FN + j) * 16 + e) * kWave] = acc[i][j][e];
+        }
+        block_barrier();
+        if (kg == 0) {
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc[i][j][e] += part[((i * FN + j) * 16 + e) * kWave];
+        }
+    }
+    if (kg == 0) {
     float swn[FN];
 #pragma unroll
     for (int j = 0; j < FN; ++j) swn[j] = scale_lds[BM + (wn * FN + j) * 32 + frow];
@@ -356,6 +406,7 @@ __global__ __launch_bounds__(WM *WN *kWave, OCC) void w4a4_gemm_kernel(
                 }
             }
     }
+    }   // kg == 0
     __syncthreads();
     constexpr int CPRY = BN / 8;         // 16-byte chunks per output row
     constexpr int ROUNDS = BM * CPRY / NT, BATCH = (ROUNDS % 4 == 0) ? 4 : (ROUNDS % 2 == 0) ? 2 : 1;
@@ -586,21 +637,22 @@ __global__ __launch_bounds__(256) void w4a4_gemm_generic_kernel(
     store_tile<FM, FN>(acc, row0 + wm * FM * 32, col0 + wn * FN * 32, lane, sx, sw, T, N, Y, ldy, acc_dbg);
 }
 
-template <int WM, int WN, int FM, int FN, int BKB, int OCC>
+template <int WM, int WN, int FM, int FN, int BKB, int OCC, int KG = 1, int NS = 3>
 static sq_status launch_main(const uint8_t *Qx, const float *sx, int T, int K, const uint8_t *Qw,
                              const float *sw, int N, __half *Y, int64_t ldy, int32_t *acc_dbg,
                              hipStream_t st)
 {
     constexpr int BM = WM * FM * 32, BN = WN * FN * 32;
-    constexpr size_t ring = (size_t)3 * (BM + BN) * BKB, out_tile = (size_t)BM * (BN * 2 + 16);
+    constexpr size_t ring = (size_t)NS * KG * (BM + BN) * BKB, out_tile = (size_t)BM * (BN * 2 + 16);
     // the epilogue reuses the ring for the output tile; the scales sit behind both
     constexpr size_t lds = (ring > out_tile ? ring : out_tile) + (size_t)(BM + BN) * 4;
     static_assert(lds <= (size_t)kMaxDynamicLds, "ring does not fit in LDS");
-    auto kernel = w4a4_gemm_kernel<WM, WN, FM, FN, BKB, OCC>;
+    auto kernel = w4a4_gemm_kernel<WM, WN, FM, FN, BKB, OCC, KG, NS>;
+    if ((K / 2) % (KG * BKB) != 0) return SQ_ERR_SHAPE;      // every K group walks whole tiles
     if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return SQ_ERR_LAUNCH;
     const int tiles_m = (T + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int vec_store = (((uintptr_t)Y & 15) == 0 && (ldy % 8) == 0) ? 1 : 0;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3(WM * WN * kWave), lds, st, Qx,
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3(KG * WM * WN * kWave), lds, st, Qx,
                        sx, T, K / 2, Qw, sw, N, Y, ldy, acc_dbg, tiles_m, tiles_n, vec_store);
     return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
@@ -645,7 +697,7 @@ extern "C" sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T,
     // Kernel choice, from few tokens to many.  The two large tile shapes run eight waves per CU
     // (two per SIMD): the VALU work of widening nibbles issues nearly twice as fast from two waves
     // as from one.  256x256 tiles (64x128 per wave: fewer VALU ops per MFMA) or 128x256 tiles,
-    // whichever needs less time for its rounds over the CUs.  SQ_GEMM_TILE=0..13 overrides the choice (tuning aid).
+    // whichever needs less time for its rounds over the CUs.  SQ_GEMM_TILE=0..15 overrides the choice (tuning aid).
     static const int forced = [] { const char *e = getenv("SQ_GEMM_TILE"); return e ? atoi(e) : -1; }();
     const int Ti = (int)T;
     int choice = forced;
@@ -653,8 +705,15 @@ extern "C" sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T,
     // (token blocks, channels per workgroup, K split) keeps about eight waves on every CU.
     // From 33 tokens on (17 with very many channels) and 10240 channels on, 64x64 / 64x128 tiles of
     // the tile kernel are faster than its token blocks (T = 64, K = 8192, N = 28672: 48.7 -> 32.2 us).
-    if (choice < 0 && Ti <= 64 && N >= 10240 && (Ti > 32 || (Ti > 16 && N >= 64 * 384)))
+    // With at most 256 tiles (one per CU) the tile kernel's two-K-group form is faster still: eight
+    // waves per CU, each walking half of K (T = 64, K = N = 8192: 18.3 -> 16.7 us; T = 64, K = 8192,
+    // N = 28672: 31.2 -> 28.9 us).  It needs K % 512 == 0.
+    const bool two_k_groups = (K % 512) == 0;
+    if (choice < 0 && Ti > 32 && Ti <= 64 && N >= 8192 && N <= 64 * 256 && two_k_groups) choice = 14;
+    if (choice < 0 && Ti <= 64 && N >= 10240 && (Ti > 32 || (Ti > 16 && N >= 64 * 384))) {
         choice = (N >= 64 * 384 && Ti > 32) ? 11 : 10;
+        if (choice == 11 && N <= 128 * 256 && two_k_groups) choice = 15;
+    }
     if (choice < 0 && Ti <= 32) choice = (N >= 64 * 384) ? 8 : (N >= 32 * 256 ? 9 : 7);
     if (choice < 0 && Ti <= 64) choice = 13;
     // Few tokens times few output channels: even 128x128 tiles would be too few for 256 CUs, and the
@@ -662,8 +721,8 @@ extern "C" sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T,
     // tiles of 128x128, 64x128 tiles up to 128.  (T = 128, K = N = 4096: 19.9 -> 14.6 us.)
     if (choice < 0) {
         const int64_t n128 = (int64_t)((Ti + 127) / 128) * ((N + 127) / 128);
-        if (n128 <= 64) choice = 10;
-        else if (n128 <= 128) choice = 11;
+        if (n128 <= 64) choice = two_k_groups ? 14 : 10;          // T = 200, K = N = 4096: 13.3 -> 11.6 us
+        else if (n128 <= 128) choice = two_k_groups ? 15 : 11;    // T = 384, K = N = 4096: 16.8 -> 15.5 us
     }
     // Up to a few hundred tokens 128x256 tiles would leave CUs idle: 128x128 tiles (four waves).
     if (choice < 0) {
@@ -689,6 +748,8 @@ extern "C" sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T,
         case 6: return sq::launch_main<2, 4, 2, 2, 64, 1>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
         case 10: return sq::launch_main<2, 2, 1, 1, 128, 2>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
         case 11: return sq::launch_main<2, 2, 1, 2, 128, 2>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
+        case 14: if (K % 512 == 0) return sq::launch_main<2, 2, 1, 1, 128, 1, 2>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
+        case 15: if (K % 512 == 0) return sq::launch_main<2, 2, 1, 2, 128, 1, 2>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
         case 7: if (Ti <= 32) return sq::launch_skinny<1, 1, 16>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
         case 8: if (Ti <= 32) return sq::launch_skinny<1, 2, 4>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
         case 9: if (Ti <= 32) return sq::launch_skinny<1, 1, 8>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;

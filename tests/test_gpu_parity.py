@@ -278,7 +278,10 @@ def test_rotate_quantize_identity_rotation_is_exact(oracle):
                                    (64, 768, 16500), (48, 512, 300), (40, 512, 30000), (20, 256, 25000),
                                    (100, 512, 260), (128, 256, 64),
                                    # a few hundred tokens: 64x64, 64x128 and 128x128 tiles
-                                   (129, 512, 520), (400, 768, 1000), (512, 512, 4096), (300, 512, 8200)])
+                                   (129, 512, 520), (400, 768, 1000), (512, 512, 4096), (300, 512, 8200),
+                                   # K % 512 == 0 and at most 256 small tiles: two K groups per
+                                   # workgroup (64x64 and 64x128 tiles), next to shapes just outside
+                                   (64, 1024, 8200), (200, 1536, 4100), (50, 512, 40000), (64, 512, 16385)])
 def test_gemm_random_codes_bit_exact(oracle, T, K, N):
     print(f"case gemm random codes T={T} K={K} N={N}", flush=True)
     g = np.random.default_rng(T * 7 + K + N)
