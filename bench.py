@@ -1,8 +1,10 @@
 #!/usr/bin/env python3
 """Benchmark of the W4A4 hot path on one MI355X.
 
-A step is one pass of the whole path over one synthetic layer: sq_rotate_quantize on X, then
-sq_w4a4_gemm against weights that were rotated and quantized beforehand (the offline phase).
+A step is one pass of the whole path over one synthetic layer: sq_rotate_quantize_prepared on X,
+then sq_w4a4_gemm; the weights were rotated and quantized beforehand and R1, R2 were put into the
+matrix cores' operand order beforehand (the offline phase; the plain sq_rotate_quantize entry,
+which takes R1 and R2 as they are, is timed beside it as rotate_quant_us_unprepared_entry).
 The headline workload is the attention-projection shape T=2048, K=N=4096.  Inputs are resident in
 HBM before the clock starts, and the step cycles through a ring of buffer sets larger than the
 256 MB last-level cache so that "HBM" numbers are not cache numbers.
@@ -75,6 +77,9 @@ class LayerBuffers:
             hi = min(N, lo + slab)
             Wt = torch.from_numpy(synth.weight_rows_t(cfg, np.arange(lo, hi))).to(dev)
             sq.sq_rotate_quantize(Wt, L.giv_i, L.giv_j, L.giv_theta, self.R1, self.R2, Qw0[lo:hi], sw0[lo:hi])
+        # offline as well: R1, R2 in the operand order of the matrix cores (constants of the layer)
+        self.prepared = torch.empty((sq.sq_prepared_rotation_bytes(cfg.n1, cfg.n2),), dtype=torch.uint8, device=dev)
+        sq.sq_prepare_rotation(self.R1, self.R2, self.prepared)
         torch.cuda.synchronize()
         self.X, self.Qw, self.sw, self.Q, self.s, self.Y = [], [], [], [], [], []
         for i in range(self.sets):
@@ -88,6 +93,12 @@ class LayerBuffers:
         torch.cuda.synchronize()
 
     def rotate_quantize(self, i):
+        L = self.L
+        self.sq.sq_rotate_quantize_prepared(self.X[i], L.giv_i, L.giv_j, L.giv_theta, self.prepared,
+                                            self.cfg.n1, self.cfg.n2, self.Q[i], self.s[i])
+
+    def rotate_quantize_plain(self, i):
+        """The entry point that takes R1 and R2 as they are: same results, slower start."""
         L = self.L
         self.sq.sq_rotate_quantize(self.X[i], L.giv_i, L.giv_j, L.giv_theta, self.R1, self.R2, self.Q[i], self.s[i])
 
@@ -139,10 +150,12 @@ def measure_layer(cfg, torch, sq, synth, steps, warmup):
     wall_ms, ev_ms = timed(torch, B.step, B.sets, steps, warmup)
     _, rq_ms = timed(torch, B.rotate_quantize, B.sets, steps, warmup)
     _, gm_ms = timed(torch, B.gemm, B.sets, steps, warmup)
+    _, rq_plain_ms = timed(torch, B.rotate_quantize_plain, B.sets, steps, warmup)
     out = {
         "workload": cfg.name, "T": T, "K": K, "N": N, "n1": cfg.n1, "n2": cfg.n2, "givens_pairs": cfg.P,
         "layer_us": wall_ms * 1e3, "layer_us_events": ev_ms * 1e3,
         "rotate_quant_us": rq_ms * 1e3, "gemm_us": gm_ms * 1e3,
+        "rotate_quant_us_unprepared_entry": rq_plain_ms * 1e3,
         "rotate_quant_GBps": rq_bytes(T, K) / (rq_ms * 1e-3) / 1e9,
         "gemm_int_TOPS": gemm_ops(T, K, N) / (gm_ms * 1e-3) / 1e12,
         "gemm_weight_stream_GBps": (N * K / 2) / (gm_ms * 1e-3) / 1e9,
@@ -278,6 +291,7 @@ def main() -> int:
                    "massive_channels": head["massive_channels"]},
         "rotate_quant_GBps": head["rotate_quant_GBps"], "gemm_int_TOPS": gemm_tops,
         "rotate_quant_us": head["rotate_quant_us"], "gemm_us": head["gemm_us"],
+        "rotate_quant_us_unprepared_entry": head["rotate_quant_us_unprepared_entry"],
         "roofline": gemm_roofline,
         "roofline_rotate_quant": {"kernel": "rotate_quantize", "bound": "hbm", "achieved": head["rotate_quant_GBps"],
                                   "peak": HBM_PEAK_GBPS, "unit": "GB/s",

@@ -88,6 +88,40 @@ sq_status sq_rotate_quantize(const void *X, int64_t T, int32_t K, int64_t ldx,
                              void *stream);
 
 /*
+ * sq_prepare_rotation / sq_rotate_quantize_prepared -- the same operation as
+ * sq_rotate_quantize (Eq. 18 after the Givens list of Sec. 4.1 / 4.2, then the
+ * quantizer of Sec. 3.2) for a caller that keeps a layer's R1 and R2 for many
+ * calls.  R1 and R2 are constants of the layer (Sec. 4.2 builds them once from
+ * calibration data), so their rearrangement into the order in which the matrix
+ * cores take them as operands is moved out of the online call: with it there,
+ * every wave of every launch gathers the two matrices row by row, about 2.5 us
+ * of a launch that takes 11 us at T = 2048, K = 4096.
+ *
+ * sq_prepared_rotation_bytes   size of the prepared form, a multiple of 256;
+ *              0 if (n1, n2) is not a shape sq_rotate_quantize accepts.
+ * sq_prepare_rotation          writes it (two small kernels on `stream`).
+ *   R1, R2     device, fp16 [n1,n1] and [n2,n2], row-major, 16-byte aligned
+ *   prepared   device out, sq_prepared_rotation_bytes(n1, n2) bytes, 16-byte
+ *              aligned, owned by the caller; opaque (copies of R1 and R2 and,
+ *              for the shapes the matrix-core kernel covers, its operand
+ *              fragments); valid for this library build only
+ * sq_rotate_quantize_prepared  all other arguments, limits, results and error
+ *              codes as sq_rotate_quantize; the results are identical bit for
+ *              bit to those of sq_rotate_quantize with the R1, R2 the prepared
+ *              form was written from.  The Givens list is not part of the
+ *              prepared form and is passed on every call as before.
+ */
+int64_t sq_prepared_rotation_bytes(int32_t n1, int32_t n2);
+sq_status sq_prepare_rotation(const void *R1, int32_t n1, const void *R2, int32_t n2,
+                              void *prepared, void *stream);
+sq_status sq_rotate_quantize_prepared(const void *X, int64_t T, int32_t K, int64_t ldx,
+                                      const int32_t *giv_i, const int32_t *giv_j,
+                                      const float *giv_theta, int32_t P,
+                                      const void *prepared, int32_t n1, int32_t n2,
+                                      uint8_t *Q, float *scales, float *xrot_dbg,
+                                      void *stream);
+
+/*
  * sq_w4a4_gemm -- int4 x int4 GEMM with dequantizing epilogue (Eq. 1 evaluated
  * on the codes; the weight operand is Flat(W~_R) = W^T R of Sec. 4.2, one
  * K-contiguous row per output channel).

@@ -12,8 +12,11 @@ from .binding import (  # noqa: F401
     sq_build_rotation,
     sq_build_rotation_workspace_bytes,
     sq_kron_factor,
+    sq_prepare_rotation,
     sq_prepare_weights,
+    sq_prepared_rotation_bytes,
     sq_rotate_quantize,
+    sq_rotate_quantize_prepared,
     sq_w4a4_gemm,
     sq_status_string,
 )

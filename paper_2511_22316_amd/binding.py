@@ -43,6 +43,16 @@ def _load():
             C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
             C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.sq_prepared_rotation_bytes.restype = C.c_int64
+        lib.sq_prepared_rotation_bytes.argtypes = [C.c_int32, C.c_int32]
+        lib.sq_prepare_rotation.restype = C.c_int
+        lib.sq_prepare_rotation.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+        lib.sq_rotate_quantize_prepared.restype = C.c_int
+        lib.sq_rotate_quantize_prepared.argtypes = [
+            C.c_void_p, C.c_int64, C.c_int32, C.c_int64,
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+            C.c_void_p, C.c_int32, C.c_int32,
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.sq_w4a4_gemm.restype = C.c_int
         lib.sq_w4a4_gemm.argtypes = [
             C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
@@ -104,6 +114,41 @@ def sq_rotate_quantize(X, giv_i, giv_j, giv_theta, R1, R2, Q, scales, xrot_dbg=N
         None if gi is None else gi.ctypes.data, None if gj is None else gj.ctypes.data,
         None if gt is None else gt.ctypes.data, P,
         _dev_ptr(R1), int(R1.shape[0]), _dev_ptr(R2), int(R2.shape[0]),
+        _dev_ptr(Q), _dev_ptr(scales), _dev_ptr(xrot_dbg), _stream_handle(stream))
+    _check(code)
+
+
+def sq_prepared_rotation_bytes(n1: int, n2: int) -> int:
+    return int(_load().sq_prepared_rotation_bytes(int(n1), int(n2)))
+
+
+def sq_prepare_rotation(R1, R2, prepared, stream=None) -> None:
+    """R1 fp16 [n1, n1], R2 fp16 [n2, n2]; prepared: any device tensor of at least
+    sq_prepared_rotation_bytes(n1, n2) bytes, written here and passed to
+    sq_rotate_quantize_prepared together with n1 and n2."""
+    n1, n2 = int(R1.shape[0]), int(R2.shape[0])
+    need = sq_prepared_rotation_bytes(n1, n2)
+    if prepared is not None and need > 0 and prepared.numel() * prepared.element_size() < need:
+        raise ValueError("prepared is smaller than sq_prepared_rotation_bytes")
+    _check(_load().sq_prepare_rotation(_dev_ptr(R1), n1, _dev_ptr(R2), n2, _dev_ptr(prepared),
+                                       _stream_handle(stream)))
+
+
+def sq_rotate_quantize_prepared(X, giv_i, giv_j, giv_theta, prepared, n1, n2, Q, scales, xrot_dbg=None,
+                                stream=None) -> None:
+    """As sq_rotate_quantize, with the output of sq_prepare_rotation in place of R1 and R2."""
+    gi, gj, gt = _host(giv_i, np.int32), _host(giv_j, np.int32), _host(giv_theta, np.float32)
+    P = 0 if gi is None else int(gi.size)
+    T, K = int(X.shape[0]), int(X.shape[1])
+    ldx = int(X.stride(0)) if T > 1 else K
+    need = sq_prepared_rotation_bytes(n1, n2)
+    if prepared is not None and need > 0 and prepared.numel() * prepared.element_size() < need:
+        raise ValueError("prepared is smaller than sq_prepared_rotation_bytes")
+    code = _load().sq_rotate_quantize_prepared(
+        _dev_ptr(X), T, K, ldx,
+        None if gi is None else gi.ctypes.data, None if gj is None else gj.ctypes.data,
+        None if gt is None else gt.ctypes.data, P,
+        _dev_ptr(prepared), int(n1), int(n2),
         _dev_ptr(Q), _dev_ptr(scales), _dev_ptr(xrot_dbg), _stream_handle(stream))
     _check(code)
 

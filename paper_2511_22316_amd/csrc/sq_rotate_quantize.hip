@@ -203,11 +203,77 @@ extern "C" int32_t sq_internal_rotq_plan(const int32_t *giv_i, const int32_t *gi
     return plan.n_levels;
 }
 
-extern "C" sq_status sq_rotate_quantize(const void *X, int64_t T, int32_t K, int64_t ldx,
-                                        const int32_t *giv_i, const int32_t *giv_j,
-                                        const float *giv_theta, int32_t P, const void *R1,
-                                        int32_t n1, const void *R2, int32_t n2, uint8_t *Q,
-                                        float *scales, float *xrot_dbg, void *stream)
+namespace sq {
+
+// Layout of a prepared rotation: copies of R1 and R2 (each padded to 256 bytes), then, for the
+// shapes the matrix-core kernel covers, its operand fragments of R1 and of R2.
+struct PreparedLayout {
+    size_t off_r1, off_r2, off_f1, off_f2, bytes;
+    bool fragments;
+};
+
+static PreparedLayout prepared_layout(int n1, int n2)
+{
+    auto pad = [](size_t b) { return (b + 255) / 256 * 256; };
+    PreparedLayout l;
+    l.off_r1 = 0;
+    l.off_r2 = pad((size_t)n1 * n1 * 2);
+    l.off_f1 = l.off_r2 + pad((size_t)n2 * n2 * 2);
+    l.fragments = rotq_mfma_covers(n1, n2);
+    l.off_f2 = l.off_f1 + (l.fragments ? rotq_fragment_bytes_r1(n1) : 0);
+    l.bytes = l.off_f2 + (l.fragments ? rotq_fragment_bytes_r2(n2) : 0);
+    return l;
+}
+
+__global__ __launch_bounds__(256) void copy_halves_kernel(const __half *__restrict__ a, int na, __half *__restrict__ da,
+                                                         const __half *__restrict__ b, int nb, __half *__restrict__ db)
+{
+    const int first = blockIdx.x * blockDim.x + threadIdx.x, step = gridDim.x * blockDim.x;
+    for (int i = first; i < na; i += step) da[i] = a[i];
+    for (int i = first; i < nb; i += step) db[i] = b[i];
+}
+
+static bool rotation_shape_ok(int64_t K, int32_t n1, int32_t n2)
+{
+    if (K <= 0 || n1 <= 0 || n2 <= 0) return false;
+    if (n1 > SQ_MAX_N1 || n2 > SQ_MAX_N2) return false;
+    return (int64_t)n1 * n2 == K && (n2 % 8) == 0 && K <= SQ_MAX_K;
+}
+
+}  // namespace sq
+
+extern "C" int64_t sq_prepared_rotation_bytes(int32_t n1, int32_t n2)
+{
+    if (!sq::rotation_shape_ok((int64_t)n1 * n2, n1, n2)) return 0;
+    return (int64_t)sq::prepared_layout(n1, n2).bytes;
+}
+
+extern "C" sq_status sq_prepare_rotation(const void *R1, int32_t n1, const void *R2, int32_t n2,
+                                         void *prepared, void *stream)
+{
+    if (!sq::rotation_shape_ok((int64_t)n1 * n2, n1, n2)) return SQ_ERR_SHAPE;
+    if (!R1 || !R2 || !prepared) return SQ_ERR_NULL;
+    if (((uintptr_t)R1 & 15) || ((uintptr_t)R2 & 15) || ((uintptr_t)prepared & 15)) return SQ_ERR_ALIGN;
+    const sq::PreparedLayout l = sq::prepared_layout(n1, n2);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *base = static_cast<char *>(prepared);
+    const __half *r1 = static_cast<const __half *>(R1), *r2 = static_cast<const __half *>(R2);
+    const int most = n1 * n1 > n2 * n2 ? n1 * n1 : n2 * n2;
+    hipLaunchKernelGGL(sq::copy_halves_kernel, dim3((unsigned)((most + 255) / 256)), dim3(256), 0, st, r1, n1 * n1,
+                       reinterpret_cast<__half *>(base + l.off_r1), r2, n2 * n2,
+                       reinterpret_cast<__half *>(base + l.off_r2));
+    if (hipGetLastError() != hipSuccess) return SQ_ERR_LAUNCH;
+    if (!l.fragments) return SQ_OK;
+    return sq::rotq_write_fragments(r1, n1, r2, n2, base + l.off_f1, base + l.off_f2, st);
+}
+
+// fragments: null, or the two fragment blocks of a prepared rotation (then R1 / R2 are its copies)
+static sq_status rotate_quantize_any(const void *X, int64_t T, int32_t K, int64_t ldx,
+                                     const int32_t *giv_i, const int32_t *giv_j,
+                                     const float *giv_theta, int32_t P, const void *R1,
+                                     int32_t n1, const void *R2, int32_t n2, uint8_t *Q,
+                                     float *scales, float *xrot_dbg, void *stream, const void *frag1,
+                                     const void *frag2)
 {
     if (T < 0 || K <= 0 || n1 <= 0 || n2 <= 0 || P < 0) return SQ_ERR_SHAPE;
     if (n1 > SQ_MAX_N1 || n2 > SQ_MAX_N2 || P > SQ_MAX_GIVENS) return SQ_ERR_SHAPE;
@@ -266,9 +332,11 @@ extern "C" sq_status sq_rotate_quantize(const void *X, int64_t T, int32_t K, int
     static const bool force_generic = [] { const char *e = getenv("SQ_ROTQ_GENERIC"); return e && e[0] == '1'; }();
     if (!force_generic && prep.plan_ok) {
         sq_status status = SQ_OK;
+        const bool prepared = frag1 != nullptr;
         if (sq::rotq_mfma_dispatch(static_cast<const __half *>(X), ldx, (int)T, n1, n2, prep.plan,
-                                   static_cast<const __half *>(R1), static_cast<const __half *>(R2), Q,
-                                   scales, xrot_dbg, st, &status))
+                                   static_cast<const __half *>(prepared ? frag1 : R1),
+                                   static_cast<const __half *>(prepared ? frag2 : R2), Q, scales, xrot_dbg, st,
+                                   &status, prepared))
             return status;
     }
     const size_t lds = sizeof(float) * 2 * (size_t)K;
@@ -279,4 +347,30 @@ extern "C" sq_status sq_rotate_quantize(const void *X, int64_t T, int32_t K, int
                        static_cast<const __half *>(R1), static_cast<const __half *>(R2), Q, scales,
                        xrot_dbg);
     return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+extern "C" sq_status sq_rotate_quantize(const void *X, int64_t T, int32_t K, int64_t ldx,
+                                        const int32_t *giv_i, const int32_t *giv_j,
+                                        const float *giv_theta, int32_t P, const void *R1,
+                                        int32_t n1, const void *R2, int32_t n2, uint8_t *Q,
+                                        float *scales, float *xrot_dbg, void *stream)
+{
+    return rotate_quantize_any(X, T, K, ldx, giv_i, giv_j, giv_theta, P, R1, n1, R2, n2, Q, scales, xrot_dbg,
+                               stream, nullptr, nullptr);
+}
+
+extern "C" sq_status sq_rotate_quantize_prepared(const void *X, int64_t T, int32_t K, int64_t ldx,
+                                                 const int32_t *giv_i, const int32_t *giv_j,
+                                                 const float *giv_theta, int32_t P, const void *prepared,
+                                                 int32_t n1, int32_t n2, uint8_t *Q, float *scales,
+                                                 float *xrot_dbg, void *stream)
+{
+    if (!sq::rotation_shape_ok(K, n1, n2)) return SQ_ERR_SHAPE;
+    if (!prepared) return SQ_ERR_NULL;
+    if ((uintptr_t)prepared & 15) return SQ_ERR_ALIGN;
+    const sq::PreparedLayout l = sq::prepared_layout(n1, n2);
+    const char *base = static_cast<const char *>(prepared);
+    return rotate_quantize_any(X, T, K, ldx, giv_i, giv_j, giv_theta, P, base + l.off_r1, n1, base + l.off_r2, n2,
+                               Q, scales, xrot_dbg, stream, l.fragments ? base + l.off_f1 : nullptr,
+                               l.fragments ? base + l.off_f2 : nullptr);
 }

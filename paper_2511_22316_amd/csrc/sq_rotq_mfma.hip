@@ -122,7 +122,7 @@ template <int N1, int N2, int OCC, int QS_MAX, int NSX_, bool R1LDS>
 __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
     const __half *__restrict__ X, int64_t ldx, int T, RotqPlan plan,
     const __half *__restrict__ R1, const __half *__restrict__ R2, uint8_t *__restrict__ Q,
-    float *__restrict__ scales, float *__restrict__ xrot)
+    float *__restrict__ scales, float *__restrict__ xrot, int prepared)
 {
     using S = RotqShape<N1, N2, NSX_, R1LDS>;
     constexpr int N1P = S::N1P, MB = S::MB, NCB = S::NCB, TPP = S::TPP, KSA = S::KSA, KSB = S::KSB;
@@ -137,14 +137,21 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
     const int l32 = lane & 31, g = lane >> 5;
     const bool lead = (cb == 0);                             // this wave loads and Givens-rotates its token
 
-    const int qsteps = (plan.n_qslots + 15) / 16;            // extra MFMA steps that repair the Givens rounding
+    // Every scalar argument the kernel will need is fetched here, in one batch.  Left to the
+    // compiler, each is loaded in front of its first use, and the prologue waits for five scalar
+    // memory round trips one after the other (two of them in front of the first loads of R1 / R2).
+    const int n_slots = plan.n_slots, n_levels = plan.n_levels, n_qslots = plan.n_qslots;
+    const int stride = gridDim.x;
+    asm volatile("" ::"s"(X), "s"(ldx), "s"(T), "s"(n_slots), "s"(n_levels), "s"(n_qslots), "s"(R1), "s"(R2),
+                 "s"(Q), "s"(scales), "s"(xrot), "s"(prepared), "s"(stride));
+
+    const int qsteps = (n_qslots + 15) / 16;                 // extra MFMA steps that repair the Givens rounding
     const int lo_bytes = qsteps * S::LO_STEP_BYTES;          // one side tile
     const int off_gv = S::OFF_LO + TPP * lo_bytes;
     const int off_red = off_gv + TPP * kRotqMaxSlots * 4;
     const int off_out = off_red + TPP * 16;
 
     const int groups = (T + TPP - 1) / TPP;
-    const int stride = gridDim.x;
     const int g0 = blockIdx.x;
     // does this wave's token exist in group grp (the last group may be partial)?
     auto has_row = [&](int grp) { return (int64_t)grp * TPP + tok_slot < T; };
@@ -205,14 +212,14 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
 
     // lead wave: Givens list on the tile in ring slot `slot`; fills the token's side tile
     auto givens = [&](int slot) {
-        if (plan.n_slots == 0) return;
+        if (n_slots == 0) return;
         char *xt = lds + S::OFF_X + (tok_slot * NSX + slot) * S::TILE_BYTES;
         char *lo_t = lds + S::OFF_LO + tok_slot * lo_bytes;
         float *gv = reinterpret_cast<float *>(lds + off_gv) + tok_slot * kRotqMaxSlots;
 #pragma unroll
         for (int u = 0; u < 2; ++u)
             if (gs_tile[u] >= 0) gv[lane + 64 * u] = __half2float(*reinterpret_cast<const __half *>(xt + gs_tile[u]));
-        for (int lv = 0; lv < plan.n_levels; ++lv) {
+        for (int lv = 0; lv < n_levels; ++lv) {
             __builtin_amdgcn_wave_barrier();     // LDS traffic of one wave stays in program order
             if (my_level == lv) {                // lane l owns pair l of the level-sorted list
                 const float a = gv[my_si], b = gv[my_sj];
@@ -318,18 +325,42 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
         int qrow[QS_MAX / 2];             // row of R2 that q-slot 32xb + lsw repairs, -1 behind the end
 #pragma unroll
         for (int xb = 0; xb < QS_MAX / 2; ++xb) qrow[xb] = plan.qlist[32 * xb + lsw];
-#pragma unroll
-        for (int blk = 0; blk < N2 / 32; ++blk) {
-            raw2[blk][0] = chunk(r2col + (32 * blk + lsw) * N2, C0{}, CN2{});
-            raw2[blk][1] = chunk(r2col + (32 * blk + lsw) * N2, C16{}, CN2{});
-        }
         // shared fragments: wave nb fetches (and later transposes) column block nb of R1
         const int wave_s = __builtin_amdgcn_readfirstlane(wave);
-        if constexpr (R1LDS) {
-            if (wave_s < MB) load_raw1(wave_s, raw1[0]);
+        if (prepared) {
+            // R1 and R2 point at the operand fragments themselves, stored lane by lane (see
+            // rotation_fragments_kernel): 16 contiguous bytes per lane, whole lines per wave.  Row
+            // gathers like the ones below cost a wave about 80 ns of issue time each.
+            const v8h *f2 = reinterpret_cast<const v8h *>(R2) + (cb * KSA) * kWave + lane;
+#pragma unroll
+            for (int ks = 0; ks < KSA; ++ks) r2f[ks] = f2[ks * kWave];
+            const v8h *f1 = reinterpret_cast<const v8h *>(R1) + lane;
+            if constexpr (R1LDS) {
+                if (wave_s < MB) {
+#pragma unroll
+                    for (int blk = 0; blk < MB; ++blk) {
+                        raw1[0][blk][0] = f1[(wave_s * KSB + 2 * blk) * kWave];
+                        raw1[0][blk][1] = f1[(wave_s * KSB + 2 * blk + 1) * kWave];
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int nb = 0; nb < MB; ++nb)
+#pragma unroll
+                    for (int ks = 0; ks < KSB; ++ks) r1f[nb][ks] = f1[(nb * KSB + ks) * kWave];
+            }
         } else {
 #pragma unroll
-            for (int nb = 0; nb < (MB <= 3 ? MB : 1); ++nb) load_raw1(nb, raw1[nb]);
+            for (int blk = 0; blk < N2 / 32; ++blk) {
+                raw2[blk][0] = chunk(r2col + (32 * blk + lsw) * N2, C0{}, CN2{});
+                raw2[blk][1] = chunk(r2col + (32 * blk + lsw) * N2, C16{}, CN2{});
+            }
+            if constexpr (R1LDS) {
+                if (wave_s < MB) load_raw1(wave_s, raw1[0]);
+            } else {
+#pragma unroll
+                for (int nb = 0; nb < (MB <= 3 ? MB : 1); ++nb) load_raw1(nb, raw1[nb]);
+            }
         }
         __builtin_amdgcn_sched_barrier(0);              // every request is out before the first use
         // While those requests are in flight: zeros where nothing is ever loaded, then the lead wave
@@ -352,15 +383,17 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const int p = my_chan[u] / N2, q = my_chan[u] % N2, qs = my_qslot[u];
-            gs_tile[u] = (lane + 64 * u < plan.n_slots) ? (p * CPRX + ((q >> 3) ^ swz<CPRX>(p))) * 16 + (q & 7) * 2 : -1;
+            gs_tile[u] = (lane + 64 * u < n_slots) ? (p * CPRX + ((q >> 3) ^ swz<CPRX>(p))) * 16 + (q & 7) * 2 : -1;
             gs_lo[u] = (qs >> 4) * S::LO_STEP_BYTES + p * 32 + (qs & 15) * 2;
         }
         if (lead) givens(0);
+        if (!prepared) {
 #pragma unroll
-        for (int blk = 0; blk < N2 / 32; ++blk) {
-            const v16f c = block_t(raw2[blk][0], raw2[blk][1]);
-            r2f[2 * blk] = to_frag(c, 0);
-            r2f[2 * blk + 1] = to_frag(c, 1);
+            for (int blk = 0; blk < N2 / 32; ++blk) {
+                const v16f c = block_t(raw2[blk][0], raw2[blk][1]);
+                r2f[2 * blk] = to_frag(c, 0);
+                r2f[2 * blk + 1] = to_frag(c, 1);
+            }
         }
         if constexpr (R1LDS) {
             // visible to the other waves after the barrier that precedes the first stage A
@@ -368,13 +401,18 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
                 v8h *dst = reinterpret_cast<v8h *>(lds + S::OFF_R1F) + (wave_s * KSB) * kWave + lane;
 #pragma unroll
                 for (int blk = 0; blk < MB; ++blk) {
-                    const bool keep = 32 * blk + l32 < N1;
-                    const v16f c = block_t(zero_unless(keep, raw1[0][blk][0]), zero_unless(keep, raw1[0][blk][1]));
-                    dst[(2 * blk) * kWave] = to_frag(c, 0);
-                    dst[(2 * blk + 1) * kWave] = to_frag(c, 1);
+                    if (prepared) {
+                        dst[(2 * blk) * kWave] = raw1[0][blk][0];
+                        dst[(2 * blk + 1) * kWave] = raw1[0][blk][1];
+                    } else {
+                        const bool keep = 32 * blk + l32 < N1;
+                        const v16f c = block_t(zero_unless(keep, raw1[0][blk][0]), zero_unless(keep, raw1[0][blk][1]));
+                        dst[(2 * blk) * kWave] = to_frag(c, 0);
+                        dst[(2 * blk + 1) * kWave] = to_frag(c, 1);
+                    }
                 }
             }
-        } else {
+        } else if (!prepared) {
 #pragma unroll
             for (int nb = 0; nb < MB; ++nb) {
                 constexpr bool ALTERNATE = MB > 3;
@@ -395,8 +433,8 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
         // a second trip to memory behind the plan entries.
 #pragma unroll
         for (int xb = 0; xb < QS_MAX / 2; ++xb) {
-            if (32 * xb < plan.n_qslots) {
-                const int q = (32 * xb + lsw < plan.n_qslots) ? qrow[xb] : -1;
+            if (32 * xb < n_qslots) {
+                const int q = (32 * xb + lsw < n_qslots) ? qrow[xb] : -1;
                 v16f c;
 #pragma unroll
                 for (int e = 0; e < 16; ++e) c[e] = 0.f;
@@ -649,7 +687,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
 template <int N1, int N2, int QS_MAX, int NSX, int OCC, bool R1LDS = false>
 static sq_status launch_rotq_mfma_ring(const __half *X, int64_t ldx, int T, const RotqPlan &plan,
                                        const __half *R1, const __half *R2, uint8_t *Q, float *scales,
-                                       float *xrot, hipStream_t st)
+                                       float *xrot, hipStream_t st, int prepared)
 {
     using S = RotqShape<N1, N2, NSX, R1LDS>;
     const int qsteps = (plan.n_qslots + 15) / 16;
@@ -662,14 +700,14 @@ static sq_status launch_rotq_mfma_ring(const __half *X, int64_t ldx, int T, cons
     const int per_cu = by_lds < OCC ? by_lds : OCC;                       // workgroups a CU holds
     const int resident = 256 * per_cu;
     const int grid = groups < resident ? groups : resident;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), lds, st, X, ldx, T, plan, R1, R2, Q, scales, xrot);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), lds, st, X, ldx, T, plan, R1, R2, Q, scales, xrot, prepared);
     return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
 template <int N1, int N2, int QS_MAX>
 static sq_status launch_rotq_mfma_qs(const __half *X, int64_t ldx, int T, const RotqPlan &plan,
                                      const __half *R1, const __half *R2, uint8_t *Q, float *scales,
-                                     float *xrot, hipStream_t st)
+                                     float *xrot, hipStream_t st, int prepared)
 {
     constexpr int MB = (N1 + 31) / 32;
     if constexpr (N1 == 64 && N2 == 64) {
@@ -678,7 +716,7 @@ static sq_status launch_rotq_mfma_qs(const __half *X, int64_t ldx, int T, const 
         // 3 % slower below.  SQ_ROTQ_RING=2 or 3 forces one of them (tuning aid).
         static const int forced = [] { const char *e = getenv("SQ_ROTQ_RING"); return e ? atoi(e) : 0; }();
         const bool ring2 = forced == 2 || (forced != 3 && T >= 4096);
-        if (ring2) return launch_rotq_mfma_ring<N1, N2, QS_MAX, 2, 3>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st);
+        if (ring2) return launch_rotq_mfma_ring<N1, N2, QS_MAX, 2, 3>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st, prepared);
     }
     if constexpr (MB == 3 && QS_MAX == 4) {       // more than 64 q-slots never leave room for two workgroups
         // With R1 in registers three row blocks need more than 256 of them: one workgroup per CU.
@@ -687,32 +725,87 @@ static sq_status launch_rotq_mfma_qs(const __half *X, int64_t ldx, int T, const 
         using S2 = RotqShape<N1, N2, 2, true>;
         static const bool force_reg = [] { const char *e = getenv("SQ_ROTQ_R1"); return e && e[0] == 'r'; }();
         if (!force_reg && 2 * S2::lds_bytes((plan.n_qslots + 15) / 16) <= 160 * 1024)
-            return launch_rotq_mfma_ring<N1, N2, QS_MAX, 2, 2, true>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st);
+            return launch_rotq_mfma_ring<N1, N2, QS_MAX, 2, 2, true>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st, prepared);
     }
-    return launch_rotq_mfma_ring<N1, N2, QS_MAX, 3, (MB <= 2) ? 2 : 1>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st);
+    return launch_rotq_mfma_ring<N1, N2, QS_MAX, 3, (MB <= 2) ? 2 : 1>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st, prepared);
 }
 
 // A list touches at most min(2P, n2) distinct columns q: more than 64 only if n2 is 128.
 template <int N1, int N2>
 static sq_status launch_rotq_mfma(const __half *X, int64_t ldx, int T, const RotqPlan &plan,
                                   const __half *R1, const __half *R2, uint8_t *Q, float *scales,
-                                  float *xrot, hipStream_t st)
+                                  float *xrot, hipStream_t st, int prepared)
 {
     if constexpr (N2 > 64) {
         if (plan.n_qslots > 64)
-            return launch_rotq_mfma_qs<N1, N2, 8>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st);
+            return launch_rotq_mfma_qs<N1, N2, 8>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st, prepared);
     }
-    return launch_rotq_mfma_qs<N1, N2, 4>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st);
+    return launch_rotq_mfma_qs<N1, N2, 4>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st, prepared);
+}
+
+// The operand fragments of R2 (stage A) and R1 (stage B) exactly as the kernel above holds them,
+// written lane by lane so that a wave fetches each with one contiguous 1 KB load:
+//   f2[(cb KSA + ks) 64 + lane][e] = R2[16 ks + 8 g + e][32 cb + l32]
+//   f1[(nb KSB + ks) 64 + lane][e] = R1[16 ks + 8 (e / 4) + 4 g + e % 4][32 nb + l32]   (0 outside R1)
+// with l32 = lane % 32, g = lane / 32, KSA = n2 / 16, KSB = 2 ceil(n1 / 32).
+__global__ __launch_bounds__(256) void rotation_fragments_kernel(const __half *__restrict__ R1, int n1,
+                                                                  const __half *__restrict__ R2, int n2,
+                                                                  v8h *__restrict__ f1, v8h *__restrict__ f2)
+{
+    const int ksa = n2 / 16, ncb = n2 / 32, mb = (n1 + 31) / 32, ksb = 2 * mb;
+    const int first = blockIdx.x * blockDim.x + threadIdx.x, step = gridDim.x * blockDim.x;
+    for (int u = first; u < ncb * ksa * kWave; u += step) {
+        const int lane = u % kWave, ks = (u / kWave) % ksa, cb = u / (kWave * ksa);
+        const int l32 = lane & 31, g = lane >> 5;
+        v8h v;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = (_Float16)__half2float(R2[(16 * ks + 8 * g + e) * n2 + 32 * cb + l32]);
+        f2[u] = v;
+    }
+    for (int u = first; u < mb * ksb * kWave; u += step) {
+        const int lane = u % kWave, ks = (u / kWave) % ksb, nb = u / (kWave * ksb);
+        const int l32 = lane & 31, g = lane >> 5, col = 32 * nb + l32;
+        v8h v;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int row = 16 * ks + 8 * (e / 4) + 4 * g + e % 4;
+            v[e] = (row < n1 && col < n1) ? (_Float16)__half2float(R1[row * n1 + col]) : (_Float16)0.f;
+        }
+        f1[u] = v;
+    }
+}
+
+bool rotq_mfma_covers(int n1, int n2)
+{
+    static const int shapes[][2] = {{16, 32}, {32, 32}, {32, 64}, {64, 64}, {80, 64}, {64, 128},
+                                    {128, 64}, {86, 128}, {108, 128}, {112, 128}, {128, 128}};
+    for (const auto &sh : shapes)
+        if (sh[0] == n1 && sh[1] == n2) return true;
+    return false;
+}
+
+size_t rotq_fragment_bytes_r1(int n1) { const int mb = (n1 + 31) / 32; return (size_t)mb * 2 * mb * kWave * 16; }
+size_t rotq_fragment_bytes_r2(int n2) { return (size_t)(n2 / 32) * (n2 / 16) * kWave * 16; }
+
+sq_status rotq_write_fragments(const __half *R1, int n1, const __half *R2, int n2, void *f1, void *f2,
+                               hipStream_t st)
+{
+    const size_t b1 = rotq_fragment_bytes_r1(n1), b2 = rotq_fragment_bytes_r2(n2);
+    const int units = (int)((b1 > b2 ? b1 : b2) / 16);
+    hipLaunchKernelGGL(rotation_fragments_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, st, R1, n1,
+                       R2, n2, static_cast<v8h *>(f1), static_cast<v8h *>(f2));
+    return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
 // Picks the instantiation for (n1, n2); returns false if this kernel does not cover the shape.
+// prepared: R1 and R2 point at the fragments written by rotq_write_fragments.
 bool rotq_mfma_dispatch(const __half *X, int64_t ldx, int T, int n1, int n2, const RotqPlan &plan,
                         const __half *R1, const __half *R2, uint8_t *Q, float *scales, float *xrot,
-                        hipStream_t st, sq_status *status)
+                        hipStream_t st, sq_status *status, bool prepared)
 {
 #define SQ_ROTQ_CASE(N1, N2)                                                                         \
     if (n1 == N1 && n2 == N2) {                                                                      \
-        *status = launch_rotq_mfma<N1, N2>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st);            \
+        *status = launch_rotq_mfma<N1, N2>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st, prepared);            \
         return true;                                                                                 \
     }
     SQ_ROTQ_CASE(16, 32)     // K = 512

@@ -38,8 +38,18 @@ namespace sq {
 
 // Matrix-core kernel (sq_rotq_mfma.hip).  Returns false if it does not cover (n1, n2); otherwise
 // launches on `st` and stores the launch status.
+// prepared: R1 and R2 point at the operand fragments written by rotq_write_fragments, not at the
+// matrices.
 bool rotq_mfma_dispatch(const __half *X, int64_t ldx, int T, int n1, int n2, const RotqPlan &plan,
                         const __half *R1, const __half *R2, uint8_t *Q, float *scales, float *xrot,
-                        hipStream_t st, sq_status *status);
+                        hipStream_t st, sq_status *status, bool prepared = false);
+
+// Shapes the matrix-core kernel covers, and its operand fragments of R1 / R2 in the order the
+// lanes hold them (sizes in bytes; both multiples of 1024).
+bool rotq_mfma_covers(int n1, int n2);
+size_t rotq_fragment_bytes_r1(int n1);
+size_t rotq_fragment_bytes_r2(int n2);
+sq_status rotq_write_fragments(const __half *R1, int n1, const __half *R2, int n2, void *f1, void *f2,
+                               hipStream_t st);
 
 }  // namespace sq

@@ -50,6 +50,20 @@ def run_rotate_quantize(L, X=None, want_xrot=True):
     xr = torch.empty((T, K), dtype=torch.float32, device="cuda") if want_xrot else None
     sq.sq_rotate_quantize(dX, L.giv_i, L.giv_j, L.giv_theta, dR1, dR2, Q, s, xr)
     torch.cuda.synchronize()
+    # The same call through the prepared form of R1, R2 must give the same bits: every check the
+    # caller makes on the result then holds for both entry points.
+    n1, n2 = L.R1.shape[0], L.R2.shape[0]
+    prepared = torch.full((sq.sq_prepared_rotation_bytes(n1, n2) + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+    sq.sq_prepare_rotation(dR1, dR2, prepared)
+    Qp = torch.full_like(Q, 0x5A)
+    sp = torch.full_like(s, -1.0)
+    xp = torch.full_like(xr, -7.0) if want_xrot else None
+    sq.sq_rotate_quantize_prepared(dX, L.giv_i, L.giv_j, L.giv_theta, prepared, n1, n2, Qp, sp, xp)
+    torch.cuda.synchronize()
+    assert torch.all(prepared[-64:] == 0xA5), "sq_prepare_rotation wrote past its stated size"
+    assert torch.equal(Qp, Q) and torch.equal(sp, s), "prepared rotation: codes or steps differ from the plain call"
+    if want_xrot:
+        assert torch.equal(xp, xr), "prepared rotation: rotated activations differ from the plain call"
     return host(Q), host(s), (host(xr) if want_xrot else None)
 
 

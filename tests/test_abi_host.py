@@ -68,6 +68,42 @@ def test_rotate_quantize_argument_errors(lib):
     assert _rq(lib, gi=many, gj=tuple(i + 1 for i in many), gt=(0.0,) * 65, K=128, n1=8, n2=16, ldx=128) == 2
 
 
+def _rqp(lib, T=4, K=64, ldx=64, gi=(1,), gj=(2,), gt=(0.1,), n1=8, n2=8, X=FAKE, prepared=FAKE, Q=FAKE, s=FAKE):
+    gi_a, gj_a = np.asarray(gi, np.int32), np.asarray(gj, np.int32)
+    gt_a = np.asarray(gt, np.float32)
+    return lib.sq_rotate_quantize_prepared(X, T, K, ldx, gi_a.ctypes.data, gj_a.ctypes.data, gt_a.ctypes.data,
+                                           len(gi_a), prepared, n1, n2, Q, s, None, None)
+
+
+def test_prepared_rotation_argument_errors_and_sizes(lib):
+    """The prepared variant validates like the plain one; nothing is dereferenced or enqueued."""
+    assert _rqp(lib, K=63) == 2
+    assert _rqp(lib, T=-1) == 2
+    assert _rqp(lib, ldx=32) == 2
+    assert _rqp(lib, K=36, n1=9, n2=4, ldx=40) == 2
+    assert _rqp(lib, gi=(64,)) == 3
+    assert _rqp(lib, gi=(5,), gj=(5,)) == 3
+    assert _rqp(lib, prepared=None) == 1
+    assert _rqp(lib, X=None) == 1
+    assert _rqp(lib, prepared=FAKE + 8) == 4
+    assert _rqp(lib, X=FAKE + 2) == 4
+    assert _rqp(lib, T=0) == 0
+    prep = lambda **kw: lib.sq_prepare_rotation(kw.get("R1", FAKE), kw.get("n1", 8), kw.get("R2", FAKE),
+                                                kw.get("n2", 8), kw.get("out", FAKE), None)
+    assert prep(n2=4) == 2 and prep(n1=129) == 2 and prep(n1=0) == 2
+    assert prep(n1=128, n2=256) == 2                # K beyond the limit
+    assert prep(R1=None) == 1 and prep(out=None) == 1
+    assert prep(R2=FAKE + 4) == 4 and prep(out=FAKE + 2) == 4
+    size = lib.sq_prepared_rotation_bytes
+    # copies of R1 and R2 padded to 256 bytes, plus 1 KB per 32-column block and 16-row step of
+    # each factor where the matrix-core kernel covers the shape
+    assert size(8, 8) == 256 + 256
+    assert size(64, 64) == 8192 + 8192 + (2 * 4 + 2 * 4) * 1024
+    assert size(86, 128) == 14848 + 32768 + (3 * 6 + 4 * 8) * 1024
+    assert size(128, 128) == 2 * 32768 + 2 * 4 * 8 * 1024
+    assert size(9, 4) == 0 and size(0, 8) == 0 and size(128, 256) == 0
+
+
 def _gemm(lib, T=4, K=64, N=8, ldy=8, Qx=FAKE, sx=FAKE, Qw=FAKE, sw=FAKE, Y=FAKE):
     return lib.sq_w4a4_gemm(Qx, sx, T, K, Qw, sw, N, Y, ldy, None, None)
 
