@@ -118,13 +118,15 @@ struct RotqShape {
 };
 
 // QS_MAX: repair steps of 16 q-slots each the kernel holds rotation rows for (4 or 8).
-template <int N1, int N2, int OCC, int QS_MAX, int NSX_, bool R1LDS>
+// PREPARED: R1 and R2 point at the operand fragments written by rotation_fragments_kernel.
+template <int N1, int N2, int OCC, int QS_MAX, int NSX_, bool R1LDS, bool PREPARED>
 __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
     const __half *__restrict__ X, int64_t ldx, int T, RotqPlan plan,
     const __half *__restrict__ R1, const __half *__restrict__ R2, uint8_t *__restrict__ Q,
-    float *__restrict__ scales, float *__restrict__ xrot, int prepared)
+    float *__restrict__ scales, float *__restrict__ xrot)
 {
     using S = RotqShape<N1, N2, NSX_, R1LDS>;
+    constexpr bool prepared = PREPARED;
     constexpr int N1P = S::N1P, MB = S::MB, NCB = S::NCB, TPP = S::TPP, KSA = S::KSA, KSB = S::KSB;
     constexpr int CPRX = S::CPRX, LPT = S::LPT, NSX = S::NSX, K = N1 * N2;
     static_assert(QS_MAX == 4 || QS_MAX == 8, "64 or 128 q-slots");
@@ -143,7 +145,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
     const int n_slots = plan.n_slots, n_levels = plan.n_levels, n_qslots = plan.n_qslots;
     const int stride = gridDim.x;
     asm volatile("" ::"s"(X), "s"(ldx), "s"(T), "s"(n_slots), "s"(n_levels), "s"(n_qslots), "s"(R1), "s"(R2),
-                 "s"(Q), "s"(scales), "s"(xrot), "s"(prepared), "s"(stride));
+                 "s"(Q), "s"(scales), "s"(xrot), "s"(stride));
 
     const int qsteps = (n_qslots + 15) / 16;                 // extra MFMA steps that repair the Givens rounding
     const int lo_bytes = qsteps * S::LO_STEP_BYTES;          // one side tile
@@ -327,7 +329,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
         for (int xb = 0; xb < QS_MAX / 2; ++xb) qrow[xb] = plan.qlist[32 * xb + lsw];
         // shared fragments: wave nb fetches (and later transposes) column block nb of R1
         const int wave_s = __builtin_amdgcn_readfirstlane(wave);
-        if (prepared) {
+        if constexpr (prepared) {
             // R1 and R2 point at the operand fragments themselves, stored lane by lane (see
             // rotation_fragments_kernel): 16 contiguous bytes per lane, whole lines per wave.  Row
             // gathers like the ones below cost a wave about 80 ns of issue time each.
@@ -387,7 +389,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
             gs_lo[u] = (qs >> 4) * S::LO_STEP_BYTES + p * 32 + (qs & 15) * 2;
         }
         if (lead) givens(0);
-        if (!prepared) {
+        if constexpr (!prepared) {
 #pragma unroll
             for (int blk = 0; blk < N2 / 32; ++blk) {
                 const v16f c = block_t(raw2[blk][0], raw2[blk][1]);
@@ -401,7 +403,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
                 v8h *dst = reinterpret_cast<v8h *>(lds + S::OFF_R1F) + (wave_s * KSB) * kWave + lane;
 #pragma unroll
                 for (int blk = 0; blk < MB; ++blk) {
-                    if (prepared) {
+                    if constexpr (prepared) {
                         dst[(2 * blk) * kWave] = raw1[0][blk][0];
                         dst[(2 * blk + 1) * kWave] = raw1[0][blk][1];
                     } else {
@@ -412,7 +414,7 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
                     }
                 }
             }
-        } else if (!prepared) {
+        } else if constexpr (!prepared) {
 #pragma unroll
             for (int nb = 0; nb < MB; ++nb) {
                 constexpr bool ALTERNATE = MB > 3;
@@ -693,14 +695,15 @@ static sq_status launch_rotq_mfma_ring(const __half *X, int64_t ldx, int T, cons
     const int qsteps = (plan.n_qslots + 15) / 16;
     const int lds = S::lds_bytes(qsteps);
     if (lds > kMaxDynamicLds) return SQ_ERR_SHAPE;
-    auto kernel = rotate_quantize_mfma_kernel<N1, N2, OCC, QS_MAX, NSX, R1LDS>;
+    auto kernel = prepared ? rotate_quantize_mfma_kernel<N1, N2, OCC, QS_MAX, NSX, R1LDS, true>
+                           : rotate_quantize_mfma_kernel<N1, N2, OCC, QS_MAX, NSX, R1LDS, false>;
     if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return SQ_ERR_LAUNCH;
     const int groups = (T + S::TPP - 1) / S::TPP;
     const int by_lds = (160 * 1024) / lds;
     const int per_cu = by_lds < OCC ? by_lds : OCC;                       // workgroups a CU holds
     const int resident = 256 * per_cu;
     const int grid = groups < resident ? groups : resident;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), lds, st, X, ldx, T, plan, R1, R2, Q, scales, xrot, prepared);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), lds, st, X, ldx, T, plan, R1, R2, Q, scales, xrot);
     return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
