@@ -714,7 +714,7 @@ extern "C" sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T,
         choice = (N >= 64 * 384 && Ti > 32) ? 11 : 10;
         if (choice == 11 && N <= 128 * 256 && two_k_groups) choice = 15;
     }
-    if (choice < 0 && Ti <= 32) choice = (N >= 64 * 384) ? 8 : (N >= 32 * 256 ? 9 : 7);
+    if (choice < 0 && Ti <= 32) choice = (N >= 64 * 384) ? 8 : (N >= 10240 ? 9 : 7);
     if (choice < 0 && Ti <= 64) choice = 13;
     // Few tokens times few output channels: even 128x128 tiles would be too few for 256 CUs, and the
     // time is one workgroup's walk over K.  64x64 tiles (four times as many workgroups) up to 64

@@ -272,7 +272,7 @@ def test_rotate_quantize_identity_rotation_is_exact(oracle):
                                    (8, 1024, 520), (300, 2048, 130),
                                    # at most 32 tokens: the decode-shaped kernel in its three launch
                                    # shapes, one K slice only / ragged channel tails / T = 32
-                                   (1, 256, 33), (32, 768, 8200), (31, 512, 24600), (33, 512, 300),
+                                   (1, 256, 33), (32, 768, 8200), (16, 512, 10300), (31, 512, 24600), (33, 512, 300),
                                    # 33..64 tokens: the same kernel with two token blocks (few
                                    # channels) or 64x64 tiles (many); 65..128 tokens: 64x64 tiles
                                    (64, 768, 16500), (48, 512, 300), (40, 512, 30000), (20, 256, 25000),
