@@ -51,6 +51,7 @@ typedef enum {
 #define SQ_MAX_K 16384
 #define SQ_MAX_GIVENS 64
 #define SQ_MAX_ROWS (1 << 30)
+#define SQ_DECODE_MAX_TOKENS 32
 
 /*
  * sq_rotate_quantize -- online rotation fused with per-token 4-bit quantization.
@@ -139,6 +140,40 @@ sq_status sq_rotate_quantize_prepared(const void *X, int64_t T, int32_t K, int64
 sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T, int32_t K,
                        const uint8_t *Qw, const float *sw, int32_t N,
                        void *Y, int64_t ldy, int32_t *acc_dbg, void *stream);
+
+/*
+ * sq_decode_layer -- sq_rotate_quantize_prepared followed by sq_w4a4_gemm in one
+ * launch, for at most SQ_DECODE_MAX_TOKENS tokens (decoding, Sec. 5.4 "Inference
+ * Efficiency",
+ * where the layer is one pass over the weights and the rotation of a few tokens
+ * is pure latency in front of it).  Same operation, same results bit for bit
+ * as the two calls: the first workgroups rotate and quantize one token group
+ * each into `workspace`, every workgroup then multiplies its block of output
+ * channels once all groups are done.
+ *
+ *   X, T, K, ldx, giv_*, P, prepared, n1, n2   as sq_rotate_quantize_prepared;
+ *              (n1, n2) one of 16x32, 32x32, 32x64, 64x64, 64x128, else
+ *              SQ_ERR_SHAPE (use the two calls)
+ *   Qw, sw, N, Y, ldy                          as sq_w4a4_gemm; K % 256 == 0
+ *   workspace  device, sq_decode_layer_workspace_bytes(T, K) bytes, 256-byte
+ *              aligned, owned by the caller.  Its first 16 bytes are counters:
+ *              they must be zero before the first call (one hipMemsetAsync by
+ *              the caller, once) and every call leaves them zero again, so the
+ *              same workspace serves call after call on one stream without
+ *              further clearing.  Calls that may overlap need a workspace each.
+ *              Bytes 12..15 are an error word: a workgroup that waited about a
+ *              second for the rotated tokens gives up, leaves its outputs
+ *              unwritten and sets the word to 1; it stays 0 otherwise.
+ * Needs at least as many blocks of 32 (N < 16384) or 64 output channels as there
+ * are token groups (N >= 32 T is always enough), else SQ_ERR_SHAPE.
+ */
+int64_t sq_decode_layer_workspace_bytes(int64_t T, int32_t K);
+sq_status sq_decode_layer(const void *X, int64_t T, int32_t K, int64_t ldx,
+                          const int32_t *giv_i, const int32_t *giv_j,
+                          const float *giv_theta, int32_t P,
+                          const void *prepared, int32_t n1, int32_t n2,
+                          const uint8_t *Qw, const float *sw, int32_t N,
+                          void *Y, int64_t ldy, void *workspace, void *stream);
 
 /*
  * sq_prepare_weights -- offline weight path of Sec. 4.2: the rotation that is

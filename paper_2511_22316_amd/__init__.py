@@ -11,6 +11,8 @@ from .binding import (  # noqa: F401
     library_path,
     sq_build_rotation,
     sq_build_rotation_workspace_bytes,
+    sq_decode_layer,
+    sq_decode_layer_workspace_bytes,
     sq_kron_factor,
     sq_prepare_rotation,
     sq_prepare_weights,

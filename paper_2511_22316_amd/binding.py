@@ -53,6 +53,14 @@ def _load():
             C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
             C.c_void_p, C.c_int32, C.c_int32,
             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.sq_decode_layer_workspace_bytes.restype = C.c_int64
+        lib.sq_decode_layer_workspace_bytes.argtypes = [C.c_int64, C.c_int32]
+        lib.sq_decode_layer.restype = C.c_int
+        lib.sq_decode_layer.argtypes = [
+            C.c_void_p, C.c_int64, C.c_int32, C.c_int64,
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+            C.c_void_p, C.c_int32, C.c_int32,
+            C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         lib.sq_w4a4_gemm.restype = C.c_int
         lib.sq_w4a4_gemm.argtypes = [
             C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
@@ -162,6 +170,35 @@ def sq_w4a4_gemm(Qx, sx, Qw, sw, Y, acc_dbg=None, stream=None) -> None:
     code = _load().sq_w4a4_gemm(
         _dev_ptr(Qx), _dev_ptr(sx), T, 2 * Kh, _dev_ptr(Qw), _dev_ptr(sw), N,
         _dev_ptr(Y), ldy, _dev_ptr(acc_dbg), _stream_handle(stream))
+    _check(code)
+
+
+def sq_decode_layer_workspace_bytes(T: int, K: int) -> int:
+    return int(_load().sq_decode_layer_workspace_bytes(int(T), int(K)))
+
+
+def sq_decode_layer(X, giv_i, giv_j, giv_theta, prepared, n1, n2, Qw, sw, Y, workspace, stream=None) -> None:
+    """sq_rotate_quantize_prepared followed by sq_w4a4_gemm in one launch, for at most 32 tokens.
+    workspace: device tensor of at least sq_decode_layer_workspace_bytes(T, K) bytes whose first
+    16 bytes were zero before the first call (every call leaves them zero again)."""
+    gi, gj, gt = _host(giv_i, np.int32), _host(giv_j, np.int32), _host(giv_theta, np.float32)
+    P = 0 if gi is None else int(gi.size)
+    T, K = int(X.shape[0]), int(X.shape[1])
+    N = int(Qw.shape[0])
+    ldx = int(X.stride(0)) if T > 1 else K
+    ldy = int(Y.stride(0)) if T > 1 else max(N, 1)
+    need = sq_decode_layer_workspace_bytes(T, K)
+    if workspace is not None and need > 0 and workspace.numel() * workspace.element_size() < need:
+        raise ValueError("workspace is smaller than sq_decode_layer_workspace_bytes")
+    need_p = sq_prepared_rotation_bytes(n1, n2)
+    if prepared is not None and need_p > 0 and prepared.numel() * prepared.element_size() < need_p:
+        raise ValueError("prepared is smaller than sq_prepared_rotation_bytes")
+    code = _load().sq_decode_layer(
+        _dev_ptr(X), T, K, ldx,
+        None if gi is None else gi.ctypes.data, None if gj is None else gj.ctypes.data,
+        None if gt is None else gt.ctypes.data, P,
+        _dev_ptr(prepared), int(n1), int(n2),
+        _dev_ptr(Qw), _dev_ptr(sw), N, _dev_ptr(Y), ldy, _dev_ptr(workspace), _stream_handle(stream))
     _check(code)
 
 

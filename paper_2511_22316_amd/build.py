@@ -13,7 +13,7 @@ _ROOT = os.path.dirname(_HERE)
 _CSRC = os.path.join(_HERE, "csrc")
 _OUT = os.path.join(_HERE, "libsinglequant.so")
 
-SOURCES = ["sq_rotate_quantize.hip", "sq_rotq_mfma.hip", "sq_w4a4_gemm.hip", "sq_prepare_weights.hip", "sq_build_rotation.hip",
+SOURCES = ["sq_rotate_quantize.hip", "sq_rotq_mfma.hip", "sq_w4a4_gemm.hip", "sq_prepare_weights.hip", "sq_build_rotation.hip", "sq_decode_layer.hip",
            "sq_status.cpp"]
 
 # packed-fp32 VALU forms are switched off for every HIP translation unit of this library

@@ -267,6 +267,56 @@ extern "C" sq_status sq_prepare_rotation(const void *R1, int32_t n1, const void 
     return sq::rotq_write_fragments(r1, n1, r2, n2, base + l.off_f1, base + l.off_f2, st);
 }
 
+namespace sq {
+
+// The list as the kernels take it (cos / sin, and the regrouping into levels) is kept from the
+// last call of this thread and reused when the same list comes again, which is what a layer
+// called once per forward pass sends.  The caller has checked P and the pointers.
+struct ListCache {
+    int32_t count = -1, channels = 0, cols = 0;
+    int32_t i[SQ_MAX_GIVENS], j[SQ_MAX_GIVENS];
+    float theta[SQ_MAX_GIVENS];
+    GivensList giv;
+    RotqPlan plan;
+    bool plan_ok = false;
+};
+
+static sq_status cached_list(const int32_t *giv_i, const int32_t *giv_j, const float *giv_theta, int32_t P,
+                             int32_t K, int32_t n2, const ListCache **out)
+{
+    static thread_local ListCache prep;
+    const bool same = prep.count == P && prep.channels == K && prep.cols == n2 &&
+                      (P == 0 || (memcmp(prep.i, giv_i, sizeof(int32_t) * P) == 0 &&
+                                  memcmp(prep.j, giv_j, sizeof(int32_t) * P) == 0 &&
+                                  memcmp(prep.theta, giv_theta, sizeof(float) * P) == 0));
+    if (!same) {
+        prep.count = -1;                     // stays invalid if a check below fails
+        GivensList &g = prep.giv;
+        g.count = P;
+        for (int p = 0; p < P; ++p) {
+            if (giv_i[p] < 0 || giv_i[p] >= K || giv_j[p] < 0 || giv_j[p] >= K || giv_i[p] == giv_j[p])
+                return SQ_ERR_INDEX;
+            g.i[p] = giv_i[p];
+            g.j[p] = giv_j[p];
+            g.c[p] = (float)cos((double)giv_theta[p]);
+            g.s[p] = (float)sin((double)giv_theta[p]);
+        }
+        prep.plan_ok = build_rotq_plan(g, n2, prep.plan);
+        if (P > 0) {
+            memcpy(prep.i, giv_i, sizeof(int32_t) * P);
+            memcpy(prep.j, giv_j, sizeof(int32_t) * P);
+            memcpy(prep.theta, giv_theta, sizeof(float) * P);
+        }
+        prep.channels = K;
+        prep.cols = n2;
+        prep.count = P;
+    }
+    *out = &prep;
+    return SQ_OK;
+}
+
+}  // namespace sq
+
 // fragments: null, or the two fragment blocks of a prepared rotation (then R1 / R2 are its copies)
 static sq_status rotate_quantize_any(const void *X, int64_t T, int32_t K, int64_t ldx,
                                      const int32_t *giv_i, const int32_t *giv_j,
@@ -282,44 +332,10 @@ static sq_status rotate_quantize_any(const void *X, int64_t T, int32_t K, int64_
     if (P > 0 && (!giv_i || !giv_j || !giv_theta)) return SQ_ERR_NULL;
     if (!R1 || !R2) return SQ_ERR_NULL;
     if (T > 0 && (!X || !Q || !scales)) return SQ_ERR_NULL;
-    // The list as the kernels take it (cos / sin, and the regrouping into levels) is kept from the
-    // last call of this thread and reused when the same list comes again, which is what a layer
-    // called once per forward pass sends.
-    struct Prepared {
-        int32_t count = -1, channels = 0, cols = 0;
-        int32_t i[SQ_MAX_GIVENS], j[SQ_MAX_GIVENS];
-        float theta[SQ_MAX_GIVENS];
-        sq::GivensList giv;
-        sq::RotqPlan plan;
-        bool plan_ok = false;
-    };
-    static thread_local Prepared prep;
-    const bool same = prep.count == P && prep.channels == K && prep.cols == n2 &&
-                      (P == 0 || (memcmp(prep.i, giv_i, sizeof(int32_t) * P) == 0 &&
-                                  memcmp(prep.j, giv_j, sizeof(int32_t) * P) == 0 &&
-                                  memcmp(prep.theta, giv_theta, sizeof(float) * P) == 0));
-    if (!same) {
-        prep.count = -1;                     // stays invalid if a check below fails
-        sq::GivensList &g = prep.giv;
-        g.count = P;
-        for (int p = 0; p < P; ++p) {
-            if (giv_i[p] < 0 || giv_i[p] >= K || giv_j[p] < 0 || giv_j[p] >= K || giv_i[p] == giv_j[p])
-                return SQ_ERR_INDEX;
-            g.i[p] = giv_i[p];
-            g.j[p] = giv_j[p];
-            g.c[p] = (float)cos((double)giv_theta[p]);
-            g.s[p] = (float)sin((double)giv_theta[p]);
-        }
-        prep.plan_ok = sq::build_rotq_plan(g, n2, prep.plan);
-        if (P > 0) {
-            memcpy(prep.i, giv_i, sizeof(int32_t) * P);
-            memcpy(prep.j, giv_j, sizeof(int32_t) * P);
-            memcpy(prep.theta, giv_theta, sizeof(float) * P);
-        }
-        prep.channels = K;
-        prep.cols = n2;
-        prep.count = P;
-    }
+    const sq::ListCache *cache = nullptr;
+    const sq_status list_status = sq::cached_list(giv_i, giv_j, giv_theta, P, K, n2, &cache);
+    if (list_status != SQ_OK) return list_status;
+    const sq::ListCache &prep = *cache;
     const sq::GivensList &giv = prep.giv;
     if ((ldx % 8) != 0 || ((uintptr_t)X & 15) || ((uintptr_t)Q & 15) || ((uintptr_t)R1 & 15) ||
         ((uintptr_t)R2 & 15) || ((uintptr_t)scales & 3) || ((uintptr_t)xrot_dbg & 3))
@@ -373,4 +389,41 @@ extern "C" sq_status sq_rotate_quantize_prepared(const void *X, int64_t T, int32
     return rotate_quantize_any(X, T, K, ldx, giv_i, giv_j, giv_theta, P, base + l.off_r1, n1, base + l.off_r2, n2,
                                Q, scales, xrot_dbg, stream, l.fragments ? base + l.off_f1 : nullptr,
                                l.fragments ? base + l.off_f2 : nullptr);
+}
+
+extern "C" int64_t sq_decode_layer_workspace_bytes(int64_t T, int32_t K)
+{
+    if (T < 0 || T > SQ_DECODE_MAX_TOKENS || K <= 0 || K > SQ_MAX_K || (K % 2) != 0) return 0;
+    return 512 + T * (int64_t)(K / 2);       // counters, steps, codes
+}
+
+extern "C" sq_status sq_decode_layer(const void *X, int64_t T, int32_t K, int64_t ldx,
+                                     const int32_t *giv_i, const int32_t *giv_j, const float *giv_theta,
+                                     int32_t P, const void *prepared, int32_t n1, int32_t n2,
+                                     const uint8_t *Qw, const float *sw, int32_t N, void *Y, int64_t ldy,
+                                     void *workspace, void *stream)
+{
+    if (T < 0 || T > SQ_DECODE_MAX_TOKENS || N < 0 || P < 0 || P > SQ_MAX_GIVENS) return SQ_ERR_SHAPE;
+    if (!sq::rotation_shape_ok(K, n1, n2) || ldx < K || ldy < N) return SQ_ERR_SHAPE;
+    if (!sq::decode_layer_covers(n1, n2)) return SQ_ERR_SHAPE;
+    if (P > 0 && (!giv_i || !giv_j || !giv_theta)) return SQ_ERR_NULL;
+    if (!prepared) return SQ_ERR_NULL;
+    if (T > 0 && N > 0 && (!X || !Qw || !sw || !Y || !workspace)) return SQ_ERR_NULL;
+    const sq::ListCache *cache = nullptr;
+    const sq_status list_status = sq::cached_list(giv_i, giv_j, giv_theta, P, K, n2, &cache);
+    if (list_status != SQ_OK) return list_status;
+    if (!cache->plan_ok) return SQ_ERR_SHAPE;
+    if ((ldx % 8) != 0 || ((uintptr_t)X & 15) || ((uintptr_t)prepared & 15) || ((uintptr_t)Qw & 15) ||
+        ((uintptr_t)sw & 3) || ((uintptr_t)Y & 1) || ((uintptr_t)workspace & 255))
+        return SQ_ERR_ALIGN;
+    if (T == 0 || N == 0) return SQ_OK;
+    const sq::PreparedLayout l = sq::prepared_layout(n1, n2);
+    const char *base = static_cast<const char *>(prepared);
+    char *ws = static_cast<char *>(workspace);
+    return sq::decode_layer_dispatch(static_cast<const __half *>(X), ldx, (int)T, n1, n2, cache->plan,
+                                     reinterpret_cast<const __half *>(base + l.off_f1),
+                                     reinterpret_cast<const __half *>(base + l.off_f2),
+                                     reinterpret_cast<uint8_t *>(ws + 512), reinterpret_cast<float *>(ws + 256),
+                                     reinterpret_cast<int *>(ws), Qw, sw, N, static_cast<__half *>(Y), ldy,
+                                     static_cast<hipStream_t>(stream));
 }

@@ -52,4 +52,12 @@ size_t rotq_fragment_bytes_r2(int n2);
 sq_status rotq_write_fragments(const __half *R1, int n1, const __half *R2, int n2, void *f1, void *f2,
                                hipStream_t st);
 
+// The layer in one launch for a few tokens (sq_decode_layer.hip): shapes it is built for, and
+// the launch.  F1 / F2: operand fragments of a prepared rotation; Qx / sx / ctr: the caller's
+// workspace (codes, steps, four counters that are zero between launches).
+bool decode_layer_covers(int n1, int n2);
+sq_status decode_layer_dispatch(const __half *X, int64_t ldx, int T, int n1, int n2, const RotqPlan &plan,
+                                const __half *F1, const __half *F2, uint8_t *Qx, float *sx, int *ctr,
+                                const uint8_t *Qw, const float *sw, int N, __half *Y, int64_t ldy, hipStream_t st);
+
 }  // namespace sq

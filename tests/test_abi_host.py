@@ -104,6 +104,36 @@ def test_prepared_rotation_argument_errors_and_sizes(lib):
     assert size(9, 4) == 0 and size(0, 8) == 0 and size(128, 256) == 0
 
 
+def _dl(lib, T=4, K=512, ldx=512, gi=(1,), gj=(2,), gt=(0.1,), n1=16, n2=32, X=FAKE, prepared=FAKE, Qw=FAKE, sw=FAKE,
+        N=64, Y=FAKE, ldy=64, ws=FAKE - 0x1000 + 0x2000):
+    gi_a, gj_a = np.asarray(gi, np.int32), np.asarray(gj, np.int32)
+    gt_a = np.asarray(gt, np.float32)
+    return lib.sq_decode_layer(X, T, K, ldx, gi_a.ctypes.data, gj_a.ctypes.data, gt_a.ctypes.data, len(gi_a),
+                               prepared, n1, n2, Qw, sw, N, Y, ldy, ws, None)
+
+
+def test_decode_layer_argument_errors_and_workspace_size(lib):
+    assert _dl(lib, T=33) == 2                      # more tokens than the single launch takes
+    assert _dl(lib, T=-1) == 2
+    assert _dl(lib, K=500) == 2                     # K != n1*n2
+    assert _dl(lib, K=64, n1=8, n2=8, ldx=64) == 2  # a shape only the two calls take
+    assert _dl(lib, K=11008, n1=86, n2=128, ldx=11008) == 2
+    assert _dl(lib, ldx=256) == 2
+    assert _dl(lib, ldy=32) == 2
+    assert _dl(lib, gi=(512,)) == 3
+    assert _dl(lib, gi=(7,), gj=(7,)) == 3
+    assert _dl(lib, prepared=None) == 1
+    assert _dl(lib, X=None) == 1 and _dl(lib, Qw=None) == 1 and _dl(lib, Y=None) == 1 and _dl(lib, ws=None) == 1
+    assert _dl(lib, X=FAKE + 2) == 4
+    assert _dl(lib, ws=FAKE + 16) == 4              # workspace must be 256-byte aligned
+    assert _dl(lib, Y=FAKE + 1) == 4
+    assert _dl(lib, T=0) == 0 and _dl(lib, N=0) == 0
+    size = lib.sq_decode_layer_workspace_bytes
+    assert size(8, 8192) == 512 + 8 * 4096
+    assert size(32, 512) == 512 + 32 * 256
+    assert size(33, 512) == 0 and size(4, 0) == 0 and size(-1, 512) == 0
+
+
 def _gemm(lib, T=4, K=64, N=8, ldy=8, Qx=FAKE, sx=FAKE, Qw=FAKE, sw=FAKE, Y=FAKE):
     return lib.sq_w4a4_gemm(Qx, sx, T, K, Qw, sw, N, Y, ldy, None, None)
 
