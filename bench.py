@@ -242,6 +242,8 @@ def main() -> int:
     ap.add_argument("--no-extra", action="store_true", help="skip the other layer shapes")
     ap.add_argument("--only-build-rotation", action="store_true",
                     help="time only the offline constructor on --workload and print its numbers")
+    ap.add_argument("--only-single-launch", action="store_true",
+                    help="time only sq_decode_layer (the layer in one launch, at most 32 tokens) on --workload")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run three plain 256 MiB device copies (known traffic: the scale for "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -272,6 +274,13 @@ def main() -> int:
         del src, dst
     if args.only_build_rotation:
         print(json.dumps({"build_rotation": measure_build_rotation(cfg, torch, sq, synth, args.steps, args.warmup)}))
+        return 0
+    if args.only_single_launch:
+        B = LayerBuffers(cfg, torch, sq, synth)
+        settle(torch, B.single_launch, B.sets)
+        _, ms = timed(torch, B.single_launch, B.sets, args.steps, args.warmup)
+        print(json.dumps({"workload": cfg.name, "layer_us_single_launch": ms * 1e3, "ring_sets": B.sets,
+                          "weight_stream_GBps": cfg.N * cfg.K / 2 / (ms * 1e-3) / 1e9}))
         return 0
     head = measure_layer(cfg, torch, sq, synth, args.steps, args.warmup)
     extra = {}

@@ -163,7 +163,13 @@ sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T, int32_t K,
  *              further clearing.  Calls that may overlap need a workspace each.
  *              Bytes 12..15 are an error word: a workgroup that waited about a
  *              second for the rotated tokens gives up, leaves its outputs
- *              unwritten and sets the word to 1; it stays 0 otherwise.
+ *              unwritten and sets the word to 1; it stays 0 otherwise.  (The
+ *              workgroups with the lowest indices rotate the tokens and the
+ *              others wait for them; the bound is what a dispatch order other
+ *              than lowest-index-first would run into.)
+ * On one MI355X the call takes as long as the two calls it replaces (33.9 us
+ * against 33.8 us at T = 8, K = 8192, N = 28672): what it saves is one host
+ * call per layer.
  * Needs at least as many blocks of 32 (N < 16384) or 64 output channels as there
  * are token groups (N >= 32 T is always enough), else SQ_ERR_SHAPE.
  */
