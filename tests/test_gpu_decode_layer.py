@@ -170,3 +170,43 @@ def test_decode_layer_gives_up_instead_of_waiting_forever():
     lay.ws[:16] = 0
     assert torch.equal(lay.one_launch(X), want)
     assert list(lay.counters()) == [0, 0, 0, 0]
+
+
+def test_decode_layer_captured_in_a_graph_replays_correctly():
+    """The call records into a HIP graph (it allocates nothing, clears nothing from the host and
+    leaves its counters ready for the next launch): three replays in a row on fresh contents of
+    the static input buffer, with eager work and a synchronization in between, equal the two eager
+    calls bit for bit."""
+    print("case decode layer graph capture", flush=True)
+    import torch
+    import paper_2511_22316_amd as sq
+    L = _layer_of("decode")
+    T, N = 8, 4096
+    lay = Layer(L, N, T)
+    X3 = synth.activations(synth.CONFIGS["decode"], 24)
+    Xin = torch.empty((T, lay.K), dtype=torch.float16, device="cuda")
+    Y = torch.full((T, N), -5.0, dtype=torch.float16, device="cuda")
+
+    def call(stream):
+        sq.sq_decode_layer(Xin, L.giv_i, L.giv_j, L.giv_theta, lay.prepared, lay.n1, lay.n2, lay.Qw, lay.sw, Y, lay.ws,
+                           stream=stream)
+
+    side = torch.cuda.Stream()
+    Xin.copy_(dev(X3[:T]))
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):                   # warm-up outside capture (one-time kernel attributes)
+        call(side)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        call(side)
+    for k in range(3):
+        X = X3[8 * k: 8 * k + 8]
+        Xin.copy_(dev(X))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = Y.clone()
+        want = lay.two_calls(X)                     # eager work between the replays
+        assert torch.equal(got, want), f"replay {k}"
+        assert list(lay.counters()) == [0, 0, 0, 0]
