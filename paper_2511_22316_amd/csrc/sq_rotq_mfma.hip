@@ -79,7 +79,10 @@ static sq_status launch_rotq_mfma_qs(const __half *X, int64_t ldx, int T, const 
         // the ring of three at two workgroups per CU from 4096 tokens on (4 % there, 12 % at 32768),
         // 3 % slower below.  SQ_ROTQ_RING=2 or 3 forces one of them (tuning aid).
         static const int forced = [] { const char *e = getenv("SQ_ROTQ_RING"); return e ? atoi(e) : 0; }();
-        const bool ring2 = forced == 2 || (forced != 3 && T >= 4096);
+        // With prepared operands the prologue is shorter and the third workgroup pays earlier: in a
+        // stream of such launches T = 2048 10.0 -> 9.6 us, 3072 14.3 -> 12.6, 4096 16.7 -> 14.1.  At
+        // 2048 the layer (this launch behind a GEMM) was 0.35 us slower with it, so it starts at 3072.
+        const bool ring2 = forced == 2 || (forced != 3 && T >= (prepared ? 3072 : 4096));
         if (ring2) return launch_rotq_mfma_ring<N1, N2, QS_MAX, 2, 3>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st, prepared);
     }
     if constexpr (MB == 3 && QS_MAX == 4) {       // more than 64 q-slots never leave room for two workgroups
