@@ -220,6 +220,13 @@ __global__ __launch_bounds__(KG *WM *WN *kWave, OCC) void w4a4_gemm_kernel(
 #pragma unroll
         for (int g = 0; g < B_LOADS; ++g) load_to_lds_16_if(b_src[g] + kb0, sb + g * NW * 1024, kt, limit);
     };
+    // one of those loads: index 0 .. A_LOADS-1 the tokens' part, then the weights' part
+    auto issue_one = [&](int idx, int kt, int stage, int limit) {
+        const uint32_t sa = lds_base + (uint32_t)stage * (KG * STAGE_SLOTS * 16) + group_byte + wave_u * 1024;
+        const int kb0 = kt * BKB;
+        if (idx < A_LOADS) load_to_lds_16_if(a_src[idx] + kb0, sa + idx * NW * 1024, kt, limit);
+        else load_to_lds_16_if(b_src[idx - A_LOADS] + kb0, sa + A_SLOTS * 16 + (idx - A_LOADS) * NW * 1024, kt, limit);
+    };
 
     v16i acc[FM][FN];
 #pragma unroll
@@ -265,8 +272,16 @@ __global__ __launch_bounds__(KG *WM *WN *kWave, OCC) void w4a4_gemm_kernel(
     // raw is refilled from (stage_byte, s_read) as soon as its last dword has been widened.
     // The scheduling barriers keep the compiler from regrouping the units.
     constexpr int NMFMA = 2 * FM * FN, NDW = 4 * (FM + FN);
-#define SQ_GEMM_STEP(C, stage_byte, s_read)                                                          \
+    // DPART: -1, or which half of the loads of the tile three ahead this step issues (0 / 1): a
+    // global -> LDS load costs the wave some tens of ns to issue, and six of them in a row right
+    // behind the barrier, in all eight waves at once, leave the matrix cores idle; spread over the
+    // MFMAs of the two steps that follow the barrier they do not.
+    constexpr int DMA_FIRST_HALF = (LOADS + 1) / 2;
+#define SQ_GEMM_STEP(C, stage_byte, s_read, DPART)                                                   \
     do {                                                                                             \
+        constexpr int dn = (DPART) < 0 ? 0 : ((DPART) == 0 ? DMA_FIRST_HALF : LOADS - DMA_FIRST_HALF); \
+        constexpr int dbase = (DPART) == 1 ? DMA_FIRST_HALF : 0;                                     \
+        static_assert(dn <= NMFMA, "at most one load behind each MFMA");                             \
         _Pragma("unroll") for (int m = 0; m < NMFMA; ++m) {                                          \
             const int u = m / (FM * FN), i = (m / FN) % FM, j = m % FN;                              \
             acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(frag[C][i][u], frag[C][FM + j][u],     \
@@ -282,6 +297,8 @@ __global__ __launch_bounds__(KG *WM *WN *kWave, OCC) void w4a4_gemm_kernel(
                     raw[c] = *reinterpret_cast<const uint4 *>(lds + (stage_byte) + off);             \
                 }                                                                                    \
             }                                                                                        \
+            _Pragma("unroll") for (int q = 0; q < dn; ++q)                                           \
+                if (m == q * NMFMA / (dn > 0 ? dn : 1)) issue_one(dbase + q, kt + NS, st_cur, ktiles); \
             __builtin_amdgcn_sched_barrier(0);                                                       \
         }                                                                                            \
     } while (0)
@@ -289,11 +306,7 @@ __global__ __launch_bounds__(KG *WM *WN *kWave, OCC) void w4a4_gemm_kernel(
     // tile kt+2 (if it exists) are outstanding.  After the barrier every wave's share of tile kt+1
     // is in LDS and nobody reads tile kt any more (all its reads were issued, and the barrier
     // drains them), so its stage can take tile kt+3.
-#define SQ_GEMM_TURN()                                                                               \
-    do {                                                                                             \
-        wait_tile_and_barrier<LOADS, NS>(ktiles - kt - 2);                                           \
-        issue_tile(kt + NS, st_cur, ktiles);                                                         \
-    } while (0)
+#define SQ_GEMM_TURN() wait_tile_and_barrier<LOADS, NS>(ktiles - kt - 2)
 
     // prologue: tiles 0 and 1 in flight, wait for tile 0, start tile 2, first fragments ready
 #pragma unroll
@@ -325,15 +338,15 @@ __global__ __launch_bounds__(KG *WM *WN *kWave, OCC) void w4a4_gemm_kernel(
         // the LDS reads run two steps ahead of the MFMAs, so the last two steps of a tile already
         // read the next tile (for the very last tile they read a stale stage; never used)
         if constexpr (STEPS == 4) {
-            SQ_GEMM_STEP(0, cur_byte, 2);
-            SQ_GEMM_STEP(1, cur_byte, 3);
+            SQ_GEMM_STEP(0, cur_byte, 2, -1);
+            SQ_GEMM_STEP(1, cur_byte, 3, -1);
             SQ_GEMM_TURN();
-            SQ_GEMM_STEP(0, next_byte, 0);
-            SQ_GEMM_STEP(1, next_byte, 1);
+            SQ_GEMM_STEP(0, next_byte, 0, 0);
+            SQ_GEMM_STEP(1, next_byte, 1, 1);
         } else {
             SQ_GEMM_TURN();
-            SQ_GEMM_STEP(0, next_byte, 0);
-            SQ_GEMM_STEP(1, next_byte, 1);
+            SQ_GEMM_STEP(0, next_byte, 0, 0);
+            SQ_GEMM_STEP(1, next_byte, 1, 1);
         }
         st_cur = st_next;
     }
