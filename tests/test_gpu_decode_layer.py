@@ -210,3 +210,21 @@ def test_decode_layer_captured_in_a_graph_replays_correctly():
         want = lay.two_calls(X)                     # eager work between the replays
         assert torch.equal(got, want), f"replay {k}"
         assert list(lay.counters()) == [0, 0, 0, 0]
+
+
+@pytest.mark.parametrize("name,T,N", [("attn_proj", 32, 4096), ("decode", 9, 1024)])
+def test_decode_layer_without_a_givens_list(name, T, N):
+    """P = 0: the rotation is the Kronecker factors alone; and an odd number of tokens with two
+    tokens per group (the last group is half empty)."""
+    print(f"case decode layer no list {name} T={T}", flush=True)
+    import torch
+    cfg = synth.CONFIGS[name]
+    L0 = synth.layer(cfg)
+    e = np.zeros(0, np.int32)
+    L = synth.Layer(cfg, L0.X, e, e, np.zeros(0, np.float32), L0.R1, L0.R2, L0.R1_f64, L0.R2_f64)
+    X = synth.activations(cfg, T)
+    lay = Layer(L, N, T)
+    assert torch.equal(lay.one_launch(X), lay.two_calls(X))
+    if name == "attn_proj":                       # 31 tokens: sixteen groups, the last one half empty
+        assert torch.equal(lay.one_launch(X[:31]), lay.two_calls(X[:31]))
+    assert list(lay.counters()) == [0, 0, 0, 0]
