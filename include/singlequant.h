@@ -242,9 +242,12 @@ sq_status sq_kron_factor(int32_t n, int32_t *n1, int32_t *n2);
  *      column vectors; with rows acted on as in Eq. 18 (R1 enters as R1^T) the
  *      factor that sends the columns of C to their uniform target is R^U
  *      itself.
- * Index decisions (steps 1, 2 and the rank order of step 3) are taken on fp32
- * values rounded once per operation in index order; matrices are fp32, rounded
- * to fp16 at the end.
+ * Index decisions (steps 1, 2 and the rank order of step 3) are taken on fp64
+ * values.  Several ART steps make near-ties by themselves (a massive entry a
+ * rotated against a tiny entry b leaves a (1 + b^2/2a^2) / sqrt(2) in both
+ * channels, so the halves of two outliers can agree to 15 digits or more);
+ * which of two channels that close counts as the larger is not defined beyond
+ * fp64 rounding.  Matrices are fp32, rounded to fp16 at the end.
  *
  *   X          device, fp16 [T, ldx], T >= 1; rows 16-byte aligned (ldx % 8 == 0)
  *   n1, n2     2 <= n1 <= 128; n2 a power of two, 8 <= n2 <= 256; K = n1*n2 <= 16384

@@ -27,18 +27,28 @@ they are the same ones the library documents for ``sq_build_rotation``):
         (rows: x -> rvec(R1^T X_mat R2)) the factor that sends the columns of X_mat to their
         uniform target is R^U_1 itself.
 
-Precision.  Where floating point decides an index (the ART channels, the rank order of the
-URT), the decision is taken in fp32, one rounding per operation, in index order -- the
-precision of the kernel.  Everything downstream of the decisions is fp64.
+Precision.  Everything is fp64, the decisions included: the paper defines the ART channels and
+the rank order of the URT over the reals.
+
+Close calls.  Multi-step ART produces them by itself: a massive entry a rotated against a tiny
+entry b leaves a (1 + b^2 / 2a^2) / sqrt(2) in both channels, so the halves of two outliers, or
+of one outlier met twice, differ only in their 13th to 16th digit, and which of them is "the
+largest" next is then not a property of the method but of the last bits.  ``art_select``
+(With a = 19712 and b = 1e-4 the difference is below fp64 resolution altogether: two such halves
+come out "equal" or not depending on how the square root was evaluated.)  ``art_select``
+therefore reports its closest call (``margin``: the smallest relative distance between a winner
+and the best candidate that is not tied with it by construction -- equal inputs, or the two
+outputs of one step, which the index rule decides in any arithmetic), and it can be told to
+``follow`` another implementation's choices: a followed choice is accepted if it is the oracle's
+own or if its magnitude lies within the relative ``band`` of the oracle's winner and is not a
+tie by construction, and is counted as a departure; any other choice raises.  The rank order of the URT has a margin of its own
+(``rank_margin``).
 """
 from __future__ import annotations
 
 import math
 
 import numpy as np
-
-F32 = np.float32
-_INV_SQRT2_F32 = F32(0.70710678118654752440)
 
 
 def calibration_row(X_f16: np.ndarray) -> int:
@@ -47,26 +57,70 @@ def calibration_row(X_f16: np.ndarray) -> int:
     return int(np.argmax(m))
 
 
-def art_select(c, P: int):
+def _tied(mag: np.ndarray, origin: np.ndarray, k: int) -> np.ndarray:
+    """Channels that hold the magnitude of channel k by construction, in any arithmetic: equal
+    values that are both inputs, or both the result of the same ART step.  (Equal values of
+    different origin are a coincidence of rounding, not a tie.)"""
+    return (mag == mag[k]) & (origin == origin[k])
+
+
+def _runner_up_gap(mag: np.ndarray, origin: np.ndarray, won: int, largest: bool, skip: int = -1) -> float:
+    """Relative distance from mag[won] to the nearest candidate that is not tied with it by
+    construction (those the index decides); inf if there is none."""
+    keep = ~_tied(mag, origin, won)
+    if skip >= 0:
+        keep[skip] = False
+    if not keep.any():
+        return math.inf
+    other = float(mag[keep].max() if largest else mag[keep].min())
+    top = max(float(mag[won]), other)
+    return 0.0 if top == 0.0 else abs(float(mag[won]) - other) / top
+
+
+def _smallest_other(mag: np.ndarray, i: int) -> int:
+    rest = mag.copy()
+    rest[i] = np.inf
+    return int(np.argmin(rest))                  # first of the smallest among the others
+
+
+def art_select(c, P: int, follow=None, band: float = 0.0):
     """P ART steps on the calibration vector c.
-    -> (i int32 [P], j int32 [P], theta float64 [P], c after the steps (float32))."""
-    c = np.array(c, dtype=np.float32)
+    follow: None, or (i [P], j [P]) chosen elsewhere, taken instead of the oracle's own channels
+    where they are within ``band`` of them (see the module text); ValueError otherwise.
+    -> (i int32 [P], j int32 [P], theta float64 [P], c after the steps, margin, departures)."""
+    c = np.array(c, dtype=np.float64)
+    origin = np.full(c.size, -1)                 # step that wrote the channel, -1: still the input
     gi = np.empty(P, np.int32)
     gj = np.empty(P, np.int32)
     gt = np.empty(P, np.float64)
+    margin = math.inf
+    departures = 0
     for p in range(P):
         mag = np.abs(c)
-        i = int(np.argmax(mag))                  # first of the largest
-        rest = mag.copy()
-        rest[i] = np.inf
-        j = int(np.argmin(rest))                 # first of the smallest among the others
+        i = own_i = int(np.argmax(mag))          # first of the largest
+        j = own_j = _smallest_other(mag, i)
+        margin = min(margin, _runner_up_gap(mag, origin, i, True), _runner_up_gap(mag, origin, j, False, skip=i))
+        if follow is not None:
+            fi, fj = int(follow[0][p]), int(follow[1][p])
+            if fi != i:
+                # among channels tied by construction the lowest index wins: not a close call
+                if not (0 <= fi < c.size and mag[fi] >= mag[i] * (1.0 - band) and not _tied(mag, origin, i)[fi]):
+                    raise ValueError(f"ART step {p}: channel {fi} is not the largest (channel {i} is)")
+                i = fi
+                j = _smallest_other(mag, i)
+            if fj != j:
+                if not (0 <= fj < c.size and fj != i and mag[fj] <= mag[j] * (1.0 + band)
+                        and not _tied(mag, origin, j)[fj]):
+                    raise ValueError(f"ART step {p}: channel {fj} is not the smallest (channel {j} is)")
+                j = fj
+            departures += (i, j) != (own_i, own_j)
         a, b = c[i], c[j]
         # Lemma 1: theta* = atan2(b, a) - pi/4 and (a, b) G(theta*) = (r, r) / sqrt(2)
-        gt[p] = math.atan2(float(b), float(a)) - math.pi / 4.0
-        r = np.sqrt(a * a + b * b)               # float32 scalars: one rounding per operation
-        c[i] = c[j] = r * _INV_SQRT2_F32
+        gt[p] = math.atan2(b, a) - math.pi / 4.0
+        c[i] = c[j] = math.hypot(a, b) / math.sqrt(2.0)
+        origin[i] = origin[j] = p
         gi[p], gj[p] = i, j
-    return gi, gj, gt, c
+    return gi, gj, gt, c, margin, departures
 
 
 def uniform_template(n: int) -> np.ndarray:
@@ -119,25 +173,34 @@ def hadamard(n: int) -> np.ndarray:
     return H
 
 
-def urt_vectors(c_f32, n1: int, n2: int):
-    """(V1, V2 H) in fp32 as the rank decisions see them: means over the other dimension of the
-    n1 x n2 view of c, added up in index order; V2 H with the signs of H, added up in index order
-    and scaled by 1/sqrt(n2) at the end."""
-    Cm = np.asarray(c_f32, dtype=np.float32).reshape(n1, n2)
-    V1 = np.cumsum(Cm, axis=1, dtype=np.float32)[:, -1] / F32(n2)
-    V2 = np.cumsum(Cm, axis=0, dtype=np.float32)[-1, :] / F32(n1)
-    sign = np.sign(hadamard(n2)).astype(np.float32)                       # [a, b] = +-1
-    V2H = np.cumsum(V2[:, None] * sign, axis=0, dtype=np.float32)[-1, :] * F32(1.0 / math.sqrt(n2))
-    return V1, V2, V2H
+def rank_margin(V) -> float:
+    """Smallest gap between two different entries of V, relative to the largest |entry|
+    (inf if all entries are equal)."""
+    v = np.sort(np.asarray(V, dtype=np.float64))
+    gaps = np.diff(v)
+    gaps = gaps[gaps > 0]
+    return math.inf if gaps.size == 0 else float(gaps.min() / np.max(np.abs(v)))
 
 
-def build_rotation(X_f16, n1: int, n2: int, P: int):
+def urt_vectors(c, n1: int, n2: int):
+    """(V1, V2, V2 H): means over the other dimension of the n1 x n2 view of c; the vector of the
+    second URT goes through H first, because H acts first in R2 = H R^U_2."""
+    Cm = np.asarray(c, dtype=np.float64).reshape(n1, n2)
+    V1 = Cm.mean(axis=1)
+    V2 = Cm.mean(axis=0)
+    return V1, V2, V2 @ hadamard(n2)
+
+
+def build_rotation(X_f16, n1: int, n2: int, P: int, follow=None, band: float = 0.0):
     """The whole constructor.  -> dict with the calibration row, the Givens list, the vectors of
-    the two URTs, and R1, R2 in fp64 (round to fp16 to compare with the library)."""
+    the two URTs, R1, R2 in fp64 (round to fp16 to compare with the library), ``art_margin`` and
+    ``rank_margin`` (the closest calls among its ART and rank-order decisions) and
+    ``departures`` (see ``art_select`` for ``follow`` and ``band``)."""
     X_f16 = np.asarray(X_f16)
     t = calibration_row(X_f16)
-    gi, gj, gt, c = art_select(X_f16[t].astype(np.float32), P)
+    gi, gj, gt, c, art_margin, departures = art_select(X_f16[t].astype(np.float64), P, follow, band)
     V1, V2, V2H = urt_vectors(c, n1, n2)
     R1 = urt(V1)
     R2 = hadamard(n2) @ urt(V2H)
-    return dict(row=t, giv_i=gi, giv_j=gj, giv_theta=gt, c=c, V1=V1, V2=V2, V2H=V2H, R1=R1, R2=R2)
+    return dict(row=t, giv_i=gi, giv_j=gj, giv_theta=gt, c=c, V1=V1, V2=V2, V2H=V2H, R1=R1, R2=R2,
+                art_margin=art_margin, rank_margin=min(rank_margin(V1), rank_margin(V2H)), departures=departures)

@@ -13,10 +13,10 @@
 //   hadamard_left_kernel  R2 = H R^U_2
 //
 // Wherever floating point decides an index -- the ART channels and the rank order of the URT --
-// the deciding values are computed in fp32 with one rounding per operation, in index order: every
-// such product and sum passes through an opaque register, so the compiler can neither fuse a
-// multiply with an add nor reorder a sum (square root and division are the correctly rounded ones
-// hipcc uses by default).
+// the deciding values (the calibration vector as the ART steps rewrite it, the means, the Hadamard
+// image) are kept and compared in fp64: the paper defines these choices over the reals, and at
+// fp64 only values that agree to about fifteen digits could be ordered differently from that.
+// The matrices that follow the decisions are fp32.
 #include "sq_common.h"
 
 #include <math.h>
@@ -30,7 +30,9 @@ constexpr int kBuildWaves = kBuildThreads / kWave;
 constexpr int kMaxSide = 256;                 // n1 <= 128, n2 <= 256
 static_assert(kBuildThreads == 4 * kMaxSide, "one thread per step of each of the four chains");
 static_assert(SQ_MAX_N1 <= kMaxSide && SQ_MAX_N2 <= kMaxSide && SQ_MAX_GIVENS <= kBuildThreads, "limits");
-constexpr int kBuildSmallBytes = 4 * kBuildWaves * 4 + 5 * kMaxSide * 4 + 2 * SQ_MAX_GIVENS * 4;
+// reduction slots (two sets of three words per wave), five small fp64 vectors, the ART pairs
+constexpr int kBuildSmallBytes = 6 * kBuildWaves * 4 + 5 * kMaxSide * 8 + 2 * SQ_MAX_GIVENS * 8;
+static_assert(kBuildSmallBytes % 8 == 0, "the fp64 vectors behind the slots are 8-byte aligned");
 
 // workspace, in floats
 struct BuildWorkspace {
@@ -67,21 +69,6 @@ __host__ BuildWorkspace carve_workspace(void *workspace, int64_t T, int n1, int 
 }
 
 typedef unsigned short v2us __attribute__((ext_vector_type(2)));
-
-// fp32 product / sum rounded once, to nearest: the empty statement hides the value from the
-// optimiser, so it is a result in a register before anything else uses it
-__device__ __forceinline__ float rn_mul(float a, float b)
-{
-    float r = a * b;
-    asm volatile("" : "+v"(r));
-    return r;
-}
-__device__ __forceinline__ float rn_add(float a, float b)
-{
-    float r = a + b;
-    asm volatile("" : "+v"(r));
-    return r;
-}
 
 // max |x| per token row.  One wave per row; a lane reads 16 bytes at a time, four loads in
 // flight.  |fp16| bit patterns order like unsigned integers, so the maximum is taken on the
@@ -136,27 +123,47 @@ __device__ __forceinline__ uint32_t wave_extreme(uint32_t v)
     return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
-// Channel of the largest (or smallest) magnitude in the workgroup, the lowest channel among equal
-// magnitudes; every thread passes the best (magnitude bits, channel) of its own elements and gets
-// the result.  `slots` ([2][kBuildWaves] words) must not be rewritten before every thread has
-// passed a later barrier.
+// Index of the largest (or smallest) 64-bit key (hi, lo) in the workgroup, the lowest index among
+// equal keys; every thread passes the best (key, index) of its own elements and gets the result.
+// Magnitudes of finite fp64 (and fp32) values order like their bit patterns read as unsigned
+// integers.  `slots` ([3][kBuildWaves] words) must not be rewritten before every thread has passed
+// a later barrier.
 template <bool LARGEST>
-__device__ __forceinline__ uint32_t block_arg(uint32_t mag, uint32_t idx, uint32_t *slots)
+__device__ __forceinline__ uint32_t wave_arg(uint32_t hi, uint32_t lo, uint32_t idx, uint32_t &best_hi,
+                                             uint32_t &best_lo)
+{
+    constexpr uint32_t kNone = LARGEST ? 0u : 0xFFFFFFFFu;
+    best_hi = wave_extreme<LARGEST>(hi);
+    best_lo = wave_extreme<LARGEST>(hi == best_hi ? lo : kNone);
+    return wave_extreme<false>((hi == best_hi && lo == best_lo) ? idx : 0xFFFFFFFFu);
+}
+
+template <bool LARGEST>
+__device__ __forceinline__ uint32_t block_arg(uint32_t hi, uint32_t lo, uint32_t idx, uint32_t *slots)
 {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
     constexpr uint32_t kNone = LARGEST ? 0u : 0xFFFFFFFFu;
-    uint32_t best = wave_extreme<LARGEST>(mag);
-    uint32_t who = wave_extreme<false>(mag == best ? idx : 0xFFFFFFFFu);
+    uint32_t bh, bl;
+    const uint32_t who = wave_arg<LARGEST>(hi, lo, idx, bh, bl);
     if (lane == 0) {
-        slots[wave] = best;
-        slots[kBuildWaves + wave] = who;
+        slots[wave] = bh;
+        slots[kBuildWaves + wave] = bl;
+        slots[2 * kBuildWaves + wave] = who;
     }
     __syncthreads();
-    // every wave combines the per-wave results on its own
-    const uint32_t m2 = lane < kBuildWaves ? slots[lane] : kNone;
-    const uint32_t i2 = lane < kBuildWaves ? slots[kBuildWaves + lane] : 0xFFFFFFFFu;
-    best = wave_extreme<LARGEST>(m2);
-    return wave_extreme<false>(m2 == best ? i2 : 0xFFFFFFFFu);
+    // every wave combines the per-wave results on its own; a wave whose threads had no element
+    // passes index 0xFFFFFFFF and never wins against one that had
+    const bool in = lane < kBuildWaves;
+    const uint32_t i2 = in ? slots[2 * kBuildWaves + lane] : 0xFFFFFFFFu;
+    const bool has = i2 != 0xFFFFFFFFu;
+    return wave_arg<LARGEST>(has ? slots[lane] : kNone, has ? slots[kBuildWaves + lane] : kNone, i2, bh, bl);
+}
+
+__device__ __forceinline__ void magnitude_key(double v, uint32_t &hi, uint32_t &lo)
+{
+    const uint64_t bits = (uint64_t)__double_as_longlong(fabs(v));
+    hi = (uint32_t)(bits >> 32);
+    lo = (uint32_t)bits;
 }
 
 // Step k of the Givens chain that takes `vec` (n entries) to ||vec|| e_1: entry k is zeroed by a
@@ -165,30 +172,30 @@ __device__ __forceinline__ uint32_t block_arg(uint32_t mag, uint32_t idx, uint32
 //   cos_k = v_{k-1} / sqrt(S_{k-1}),   sin_k = sqrt(S_k / S_{k-1})     (cos = 1, sin = 0 if S_{k-1} = 0;
 //   sin_{n-1} = v_{n-1} / sqrt(S_{n-2}), because the last entry enters with its sign)
 // and the steps can be computed independently of one another.  Stored at cs[k], cs[kMaxSide + k].
-__device__ __forceinline__ void chain_step(const float *vec, int n, int k, float *cs)
+__device__ __forceinline__ void chain_step(const double *vec, int n, int k, float *cs)
 {
     double tail = 0.0;
-    for (int m = n - 1; m >= k; --m) tail += (double)vec[m] * (double)vec[m];
+    for (int m = n - 1; m >= k; --m) tail += vec[m] * vec[m];
     const double x = vec[k - 1], all = tail + x * x;
     cs[k] = (all == 0.0) ? 1.f : (float)(x / sqrt(all));
     // the first step (k = n-1) meets the last entry itself, sign included; later ones meet a norm
-    cs[kMaxSide + k] = (all == 0.0) ? 0.f : (float)(k == n - 1 ? (double)vec[k] / sqrt(all) : sqrt(tail / all));
+    cs[kMaxSide + k] = (all == 0.0) ? 0.f : (float)(k == n - 1 ? vec[k] / sqrt(all) : sqrt(tail / all));
 }
 
-// One workgroup.  All of its LDS is dynamic (kBuildSmallBytes + 4K bytes): the reduction slots,
-// the small vectors, then the calibration vector.
+// One workgroup.  All of its LDS is dynamic (kBuildSmallBytes + 8K bytes): the reduction slots,
+// the small vectors, then the calibration vector, in fp64.
 __global__ __launch_bounds__(kBuildThreads) void art_urt_kernel(
-    const __half *__restrict__ X, int64_t ldx, int T, int K, int n1, int n2, int P, float inv_sqrt_n2,
+    const __half *__restrict__ X, int64_t ldx, int T, int K, int n1, int n2, int P, double inv_sqrt_n2,
     const float *__restrict__ rowmax, int32_t *__restrict__ giv_i, int32_t *__restrict__ giv_j,
     float *__restrict__ giv_theta, float *__restrict__ chain)
 {
     extern __shared__ uint32_t build_lds[];
-    uint32_t *slots_a = build_lds, *slots_b = build_lds + 2 * kBuildWaves;
-    float(*vec)[kMaxSide] = reinterpret_cast<float(*)[kMaxSide]>(build_lds + 4 * kBuildWaves);   // V1 | V2 H
-    float *v2 = vec[2];
-    float(*target)[kMaxSide] = reinterpret_cast<float(*)[kMaxSide]>(vec[3]);                     // U1 | U2
-    float *pair_a = vec[5], *pair_b = pair_a + SQ_MAX_GIVENS;      // (c_i, c_j) each ART angle is made for
-    float *cvec = pair_b + SQ_MAX_GIVENS;
+    uint32_t *slots_a = build_lds, *slots_b = build_lds + 3 * kBuildWaves;
+    double(*vec)[kMaxSide] = reinterpret_cast<double(*)[kMaxSide]>(build_lds + 6 * kBuildWaves);   // V1 | V2 H
+    double *v2 = vec[2];
+    double(*target)[kMaxSide] = reinterpret_cast<double(*)[kMaxSide]>(vec[3]);                     // U1 | U2
+    double *pair_a = vec[5], *pair_b = pair_a + SQ_MAX_GIVENS;     // (c_i, c_j) each ART angle is made for
+    double *cvec = pair_b + SQ_MAX_GIVENS;
     const int tid = threadIdx.x;
 
     // calibration row: the largest row maximum, lowest row among equals
@@ -197,30 +204,32 @@ __global__ __launch_bounds__(kBuildThreads) void art_urt_kernel(
         const uint32_t m = __float_as_uint(rowmax[t]);
         if (m > top || top_at == 0xFFFFFFFFu) top = m, top_at = (uint32_t)t;      // t ascends: ties keep the lower row
     }
-    const int t_star = (int)block_arg<true>(top, top_at, slots_a);
-    for (int k = tid; k < K; k += kBuildThreads) cvec[k] = __half2float(X[(int64_t)t_star * ldx + k]);
+    const int t_star = (int)block_arg<true>(top, 0u, top_at, slots_a);
+    for (int k = tid; k < K; k += kBuildThreads) cvec[k] = (double)__half2float(X[(int64_t)t_star * ldx + k]);
     __syncthreads();
 
     // ART (Sec. 4.2; several steps as in the "ART steps" study): largest against smallest
     // magnitude, angle of Lemma 1, after which both channels hold r / sqrt(2)
     for (int p = 0; p < P; ++p) {
         // k ascends within a thread, so strict comparisons keep the lower channel among equals
-        uint32_t hi = 0, hi_at = 0xFFFFFFFFu;
+        uint32_t hi_h = 0, hi_l = 0, hi_at = 0xFFFFFFFFu;
         for (int k = tid; k < K; k += kBuildThreads) {
-            const uint32_t m = __float_as_uint(fabsf(cvec[k]));
-            if (m > hi || hi_at == 0xFFFFFFFFu) hi = m, hi_at = (uint32_t)k;
+            uint32_t h, l;
+            magnitude_key(cvec[k], h, l);
+            if (hi_at == 0xFFFFFFFFu || h > hi_h || (h == hi_h && l > hi_l)) hi_h = h, hi_l = l, hi_at = (uint32_t)k;
         }
-        const int i = (int)block_arg<true>(hi, hi_at, slots_a);
-        uint32_t lo = 0xFFFFFFFFu, lo_at = 0xFFFFFFFFu;
+        const int i = (int)block_arg<true>(hi_h, hi_l, hi_at, slots_a);
+        uint32_t lo_h = 0xFFFFFFFFu, lo_l = 0xFFFFFFFFu, lo_at = 0xFFFFFFFFu;
         for (int k = tid; k < K; k += kBuildThreads) {
-            const uint32_t m = __float_as_uint(fabsf(cvec[k]));
-            if (k != i && (m < lo || lo_at == 0xFFFFFFFFu)) lo = m, lo_at = (uint32_t)k;
+            uint32_t h, l;
+            magnitude_key(cvec[k], h, l);
+            if (k != i && (lo_at == 0xFFFFFFFFu || h < lo_h || (h == lo_h && l < lo_l)))
+                lo_h = h, lo_l = l, lo_at = (uint32_t)k;
         }
-        const int j = (int)block_arg<false>(lo, lo_at, slots_b);
+        const int j = (int)block_arg<false>(lo_h, lo_l, lo_at, slots_b);
         if (tid == 0) {
-            const float a = cvec[i], b = cvec[j];
-            const float r = sqrtf(rn_add(rn_mul(a, a), rn_mul(b, b)));
-            const float e = rn_mul(r, 0.70710678118654752440f);
+            const double a = cvec[i], b = cvec[j];
+            const double e = sqrt(a * a + b * b) * 0.70710678118654752440;
             giv_i[p] = i;
             giv_j[p] = j;
             pair_a[p] = a;
@@ -231,24 +240,24 @@ __global__ __launch_bounds__(kBuildThreads) void art_urt_kernel(
         __syncthreads();
     }
 
-    // vectors of the two URTs: means of the n1 x n2 view over the other dimension, added in index
-    // order; the second one goes through the Hadamard matrix first, because H acts first in R2
+    // vectors of the two URTs: means of the n1 x n2 view over the other dimension; the second one
+    // goes through the Hadamard matrix first, because H acts first in R2
     if (tid < n1) {
-        float s = 0.f;
-        for (int q = 0; q < n2; ++q) s = rn_add(s, cvec[tid * n2 + q]);
-        vec[0][tid] = s / (float)n2;
+        double s = 0.0;
+        for (int q = 0; q < n2; ++q) s += cvec[tid * n2 + q];
+        vec[0][tid] = s / (double)n2;
     }
     if (tid >= 512 && tid - 512 < n2) {
         const int q = tid - 512;
-        float s = 0.f;
-        for (int pp = 0; pp < n1; ++pp) s = rn_add(s, cvec[pp * n2 + q]);
-        v2[q] = s / (float)n1;
+        double s = 0.0;
+        for (int pp = 0; pp < n1; ++pp) s += cvec[pp * n2 + q];
+        v2[q] = s / (double)n1;
     }
     __syncthreads();
     if (tid < n2) {
-        float s = 0.f;
-        for (int a = 0; a < n2; ++a) s = rn_add(s, (__popc(a & tid) & 1) ? -v2[a] : v2[a]);
-        vec[1][tid] = rn_mul(s, inv_sqrt_n2);
+        double s = 0.0;
+        for (int a = 0; a < n2; ++a) s += (__popc(a & tid) & 1) ? -v2[a] : v2[a];
+        vec[1][tid] = s * inv_sqrt_n2;
     }
     __syncthreads();
 
@@ -257,17 +266,17 @@ __global__ __launch_bounds__(kBuildThreads) void art_urt_kernel(
     {
         const int side = tid >= 512, k = tid - 512 * side, n = side ? n2 : n1;
         if (k < n) {
-            const float *v = vec[side];
-            const float mine = v[k];
+            const double *v = vec[side];
+            const double mine = v[k];
             int rank = 0;
             double norm2 = 0.0;
             for (int m = 0; m < n; ++m) {
-                const float o = v[m];
+                const double o = v[m];
                 rank += (o < mine) || (o == mine && m < k);
-                norm2 += (double)o * (double)o;
+                norm2 += o * o;
             }
             const double qnorm2 = ((double)n * n - 1.0) / (3.0 * n);
-            target[side][k] = (float)(sqrt(norm2 / qnorm2) * (2.0 * (rank + 1) - n - 1.0) / n);
+            target[side][k] = sqrt(norm2 / qnorm2) * (2.0 * (rank + 1) - n - 1.0) / n;
         }
     }
     __syncthreads();
@@ -280,7 +289,7 @@ __global__ __launch_bounds__(kBuildThreads) void art_urt_kernel(
     }
 
     // the angles of Lemma 1, one thread per ART step
-    if (tid < P) giv_theta[tid] = (float)(atan2((double)pair_b[tid], (double)pair_a[tid]) - 0.78539816339744830962);
+    if (tid < P) giv_theta[tid] = (float)(atan2(pair_b[tid], pair_a[tid]) - 0.78539816339744830962);
 }
 
 // Entry (r, k) of the product of a chain (step n-1 first).  Row r starts as e_r; step r+1 leaves
@@ -370,14 +379,15 @@ extern "C" sq_status sq_kron_factor(int32_t n, int32_t *n1, int32_t *n2)
 {
     if (!n1 || !n2) return SQ_ERR_NULL;
     if (n < 1) return SQ_ERR_SHAPE;
-    // Alg. 1: the power of two dividing n that is closest to sqrt(n); the earlier (smaller) one
-    // of two equally close candidates stays
-    const double root = sqrt((double)n);
-    int64_t best = 1;
-    for (int64_t a = 1; a <= n; a *= 2) {
-        if (n % a != 0) continue;
-        if (fabs((double)a - root) < fabs((double)best - root)) best = a;
-    }
+    // Alg. 1 asks for the power of two dividing n nearest to sqrt(n).  Distances to sqrt(n) shrink
+    // while a^2 <= n and grow afterwards, so only two candidates matter: the largest divisor `below`
+    // with below^2 <= n, and its double if that divides n as well.  2 below - sqrt(n) < sqrt(n) - below
+    // is 3 below < 2 sqrt(n), i.e. 9 below^2 < 4 n, in integers; equality keeps the smaller one.
+    const int64_t m = n;
+    int64_t below = 1;
+    while (m % (2 * below) == 0 && 4 * below * below <= m) below *= 2;
+    const bool above_divides = m % (2 * below) == 0;
+    const int64_t best = (above_divides && 9 * below * below < 4 * m) ? 2 * below : below;
     *n2 = (int32_t)best;
     *n1 = (int32_t)(n / best);
     return SQ_OK;
@@ -402,14 +412,14 @@ extern "C" sq_status sq_build_rotation(const void *X, int64_t T, int32_t K, int6
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const sq::BuildWorkspace w = sq::carve_workspace(workspace, T, n1, n2);
-    const float inv_sqrt_n2 = (float)(1.0 / sqrt((double)n2));
+    const double inv_sqrt_n2 = 1.0 / sqrt((double)n2);
     const __half *Xh = static_cast<const __half *>(X);
 
     const int64_t row_groups = (T + 3) / 4;
     hipLaunchKernelGGL(sq::row_absmax_kernel, dim3((unsigned)(row_groups < 4096 ? row_groups : 4096)), dim3(256), 0,
                        st, Xh, ldx, (int)T, K, w.rowmax);
     auto art = sq::art_urt_kernel;
-    const size_t lds = sq::kBuildSmallBytes + (size_t)K * sizeof(float);      // 69.4 KiB at the largest K
+    const size_t lds = sq::kBuildSmallBytes + (size_t)K * sizeof(double);     // 139.4 KiB at the largest K
     if (!sq::allow_large_lds(reinterpret_cast<const void *>(art))) return SQ_ERR_LAUNCH;
     hipLaunchKernelGGL(art, dim3(1), dim3(sq::kBuildThreads), lds, st, Xh, ldx, (int)T, K, n1, n2, P, inv_sqrt_n2,
                        w.rowmax, giv_i, giv_j, giv_theta, w.chain);
@@ -419,7 +429,7 @@ extern "C" sq_status sq_build_rotation(const void *X, int64_t T, int32_t K, int6
     const unsigned tiles = (unsigned)((big + 15) / 16), tiles2 = (unsigned)((n2 + 15) / 16);
     hipLaunchKernelGGL(sq::urt_product_kernel, dim3(tiles, tiles, 2), dim3(256), 0, st, w.rmap[0], w.rmap[1],
                        w.rmap[2], w.rmap[3], n1, n2, static_cast<__half *>(R1), w.ru2);
-    hipLaunchKernelGGL(sq::hadamard_left_kernel, dim3(tiles2, tiles2), dim3(256), 0, st, w.ru2, n2, inv_sqrt_n2,
+    hipLaunchKernelGGL(sq::hadamard_left_kernel, dim3(tiles2, tiles2), dim3(256), 0, st, w.ru2, n2, (float)inv_sqrt_n2,
                        static_cast<__half *>(R2));
     return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }

@@ -38,8 +38,9 @@ def host(t) -> np.ndarray:
     return t.detach().cpu().numpy()
 
 
-def run_rotate_quantize(L, X=None, want_xrot=True):
-    """Call the library on layer L (optionally on other rows X).  -> (Q, scales, xrot) numpy."""
+def run_rotate_quantize(L, X=None, want_xrot=True, xrot_rows=None):
+    """Call the library on layer L (optionally on other rows X).  -> (Q, scales, xrot) numpy;
+    xrot_rows: bring back only these rows of the rotated activations (full-size runs)."""
     import torch
     import paper_2511_22316_amd as sq
     X = L.X if X is None else X
@@ -64,6 +65,8 @@ def run_rotate_quantize(L, X=None, want_xrot=True):
     assert torch.equal(Qp, Q) and torch.equal(sp, s), "prepared rotation: codes or steps differ from the plain call"
     if want_xrot:
         assert torch.equal(xp, xr), "prepared rotation: rotated activations differ from the plain call"
+    if want_xrot and xrot_rows is not None:
+        xr = xr[torch.from_numpy(np.asarray(xrot_rows, dtype=np.int64)).cuda()]
     return host(Q), host(s), (host(xr) if want_xrot else None)
 
 

@@ -1,11 +1,21 @@
 """GPU parity of sq_build_rotation (closed-form rotation constructor, Sec. 4.2) against its CPU
 oracle on the same seeded calibration activations.
 
-Bars: the calibration row, the ART channels (and through them the rank orders) are integer
-decisions and must be identical; angles within 2e-6 rad (fp32 rounding of an fp64 atan2 on both
-sides, one ulp at |theta| < 4); R1 and R2 are fp32 products of up to 2(n-1) plane rotations and a
-Hadamard matrix, rounded to fp16: |gpu - oracle| <= 2^-10 |oracle| + 5e-5 (one fp16 rounding
-plus n * 2^-24 of accumulated fp32 error at n = 256)."""
+The oracle decides in fp64 with numpy's own reductions, as Sec. 4.2 defines the choices over the
+reals; the library decides in fp64 too, with its own order of operations.  The integer decisions
+(calibration row, ART channels, and through them the rank orders) must be the oracle's own --
+except where the oracle itself reports a close call.  Multi-step ART makes those by itself (the
+halves of two massive outliers agree to 13-16 digits, see oracle/construct.py), so the oracle
+follows the library's channels, accepts a channel other than its own pick only if the two
+magnitudes agree to ART_BAND = 1e-12 relative (fp64 evaluations of at most 64 chained steps
+differ by some 1e-14), refuses anything else, and the matrices are then compared for the list
+both sides agree on.  Where the oracle's closest call is wider than the band no departure is
+allowed at all.  The rank orders must not be close calls (RANK_MARGIN = 1e-9, against fp64 sums
+of at most 256 terms that differ by some 1e-14): a seeded case that fails this needs another
+seed.  Angles within 2e-6 rad (fp32 rounding of an fp64 atan2, one ulp at |theta| < 4); R1 and
+R2 are fp32 products of up to 2(n-1) plane rotations and a Hadamard matrix, rounded to fp16:
+|gpu - oracle| <= 2^-10 |oracle| + 5e-5 (one fp16 rounding plus n * 2^-24 of accumulated fp32
+error at n = 256)."""
 import numpy as np
 import pytest
 
@@ -14,6 +24,19 @@ from paper_2511_22316_amd import synth
 from parity_util import check_codes, check_rotation, dev, host, run_rotate_quantize
 
 pytestmark = pytest.mark.gpu
+
+ART_BAND = 1e-12
+RANK_MARGIN = 1e-9
+
+
+def oracle_for(g, X, n1, n2, P):
+    """The oracle's constructor on X, following the library's ART channels inside the band."""
+    o = oc.build_rotation(X, n1, n2, P, follow=(g["giv_i"], g["giv_j"]), band=ART_BAND)
+    assert o["rank_margin"] > RANK_MARGIN, "seeded case has a close call in a rank order: pick another seed"
+    if o["art_margin"] > ART_BAND:
+        assert o["departures"] == 0
+    print(f"  closest ART call {o['art_margin']:.1e}, departures inside the band {o['departures']}", flush=True)
+    return o
 
 
 def run_build(X, n1, n2, P, dX=None):
@@ -53,9 +76,8 @@ def test_build_rotation_matches_oracle(oracle, name, T):
     print(f"case build_rotation {name} T={T}", flush=True)
     cfg = synth.CONFIGS[name]
     X = synth.activations(cfg, T)
-    o = oc.build_rotation(X, cfg.n1, cfg.n2, cfg.P)
     g = run_build(X, cfg.n1, cfg.n2, cfg.P)
-    check_against_oracle(g, o)
+    check_against_oracle(g, oracle_for(g, X, cfg.n1, cfg.n2, cfg.P))
 
 
 @pytest.mark.parametrize("n1,n2,P,T", [(2, 8, 3, 5), (128, 64, 64, 40), (128, 128, 17, 9), (64, 256, 32, 6),
@@ -64,9 +86,8 @@ def test_build_rotation_other_shapes(oracle, n1, n2, P, T):
     print(f"case build_rotation shape {n1}x{n2} P={P}", flush=True)
     cfg = synth.LayerConfig(f"b_{n1}x{n2}", T, n1, n2, 64, P, "student_t3", 3, 300.0, 0.02, 20.0, 0.02, 555 + n1 + n2)
     X = synth.activations(cfg, T)
-    o = oc.build_rotation(X, n1, n2, P)
     g = run_build(X, n1, n2, P)
-    check_against_oracle(g, o)
+    check_against_oracle(g, oracle_for(g, X, n1, n2, P))
 
 
 def test_build_rotation_edge_cases(oracle):
@@ -78,22 +99,25 @@ def test_build_rotation_edge_cases(oracle):
     wide = torch.full((16, cfg.K + 24), 60000.0, dtype=torch.float16, device="cuda")
     wide[:, : cfg.K] = dev(X)
     g = run_build(X, cfg.n1, cfg.n2, cfg.P, dX=wide[:, : cfg.K])
-    check_against_oracle(g, oc.build_rotation(X, cfg.n1, cfg.n2, cfg.P))
+    check_against_oracle(g, oracle_for(g, X, cfg.n1, cfg.n2, cfg.P))
     # one row
-    check_against_oracle(run_build(X[3:4], cfg.n1, cfg.n2, 4), oc.build_rotation(X[3:4], cfg.n1, cfg.n2, 4))
+    g = run_build(X[3:4], cfg.n1, cfg.n2, 4)
+    check_against_oracle(g, oracle_for(g, X[3:4], cfg.n1, cfg.n2, 4))
     # two rows share the largest entry: the first one is the calibration row
     Y = X.copy()
     Y[2] = Y[9]
     top = np.float16(np.max(np.abs(Y.astype(np.float32))) * 1.5)
     Y[2, 5] = top
     Y[9, 400] = -top
-    o = oc.build_rotation(Y, cfg.n1, cfg.n2, 2)
-    assert o["row"] == 2 and o["giv_i"][0] == 5
-    check_against_oracle(run_build(Y, cfg.n1, cfg.n2, 2), o)
+    g = run_build(Y, cfg.n1, cfg.n2, 2)
+    o = oracle_for(g, Y, cfg.n1, cfg.n2, 2)
+    assert o["row"] == 2 and o["giv_i"][0] == 5 and o["departures"] == 0
+    check_against_oracle(g, o)
     # all zeros: every magnitude ties (channels 0 and 1), both URTs are the identity, R2 = H
     Z = np.zeros((4, cfg.K), np.float16)
     g = run_build(Z, cfg.n1, cfg.n2, 2)
-    o = oc.build_rotation(Z, cfg.n1, cfg.n2, 2)
+    o = oracle_for(g, Z, cfg.n1, cfg.n2, 2)
+    assert o["departures"] == 0
     check_against_oracle(g, o)
     assert list(g["giv_i"]) == [0, 0] and list(g["giv_j"]) == [1, 1]
     assert np.array_equal(g["R1"], np.eye(cfg.n1, dtype=np.float16))
@@ -106,8 +130,8 @@ def test_build_rotation_full_size_and_its_use_on_the_hot_path(oracle):
     print("case build_rotation attn_proj full, then rotate+quantize with it", flush=True)
     cfg = synth.CONFIGS["attn_proj"]
     L = synth.layer(cfg)
-    o = oc.build_rotation(L.X, cfg.n1, cfg.n2, cfg.P)
     g = run_build(L.X, cfg.n1, cfg.n2, cfg.P)
+    o = oracle_for(g, L.X, cfg.n1, cfg.n2, cfg.P)
     check_against_oracle(g, o)
     rows = np.unique(np.concatenate([[0, cfg.T - 1, o["row"]], np.random.default_rng(3).integers(0, cfg.T, 40)]))
     L2 = synth.Layer(cfg, L.X[rows], g["giv_i"], g["giv_j"], g["giv_theta"], g["R1"], g["R2"], o["R1"], o["R2"])

@@ -18,21 +18,65 @@ def test_art_hand_worked_steps(oracle):
     # |c| = (3, 0.5, 4, 1): step 1 takes i = 2 (largest), j = 1 (smallest): r = sqrt(16.25);
     # then the largest is r/sqrt(2) = 2.85.. < 3, so step 2 takes i = 0 and j = 3 (|c_3| = 1 is
     # now the smallest), r = sqrt(10)
-    c0 = np.array([3.0, -0.5, -4.0, 1.0], np.float32)
-    gi, gj, gt, c = oc.art_select(c0, 2)
+    c0 = np.array([3.0, -0.5, -4.0, 1.0])
+    gi, gj, gt, c, margin, _ = oc.art_select(c0, 2)
     assert list(gi) == [2, 0] and list(gj) == [1, 3]
     assert gt[0] == pytest.approx(math.atan2(-0.5, -4.0) - math.pi / 4, abs=1e-15)
     assert gt[1] == pytest.approx(math.atan2(1.0, 3.0) - math.pi / 4, abs=1e-15)
     e1, e2 = math.sqrt(16.25 / 2), math.sqrt(10.0 / 2)
-    assert np.allclose(c, [e2, e1, e1, e2], rtol=3e-7)
+    assert np.allclose(c, [e2, e1, e1, e2], rtol=1e-15)
+    # closest calls, by hand: step 1, largest 4 against 3 (gap 1/4), smallest 0.5 against 1 (1/2);
+    # step 2, largest 3 against sqrt(8.125) = 2.850.. (the two equal entries), smallest 1 against
+    # 2.850..: the tightest is (3 - 2.850..) / 3
+    assert margin == pytest.approx((3.0 - e1) / 3.0, rel=1e-12)
 
 
 def test_art_ties_go_to_the_lowest_channel(oracle):
-    gi, gj, _, _ = oc.art_select(np.array([1.0, -7.0, 7.0, 0.25, -0.25, 2.0], np.float32), 1)
+    gi, gj, _, _, margin, _ = oc.art_select(np.array([1.0, -7.0, 7.0, 0.25, -0.25, 2.0]), 1)
     assert (gi[0], gj[0]) == (1, 3)
+    # exact ties are decided by the index and do not count as close calls: 7 against 2, 0.25 against 1
+    assert margin == pytest.approx(min(5.0 / 7.0, 0.75), rel=1e-12)
     # largest and smallest may not be the same channel even if every entry is equal
-    gi, gj, _, _ = oc.art_select(np.full(5, 2.0, np.float32), 1)
-    assert (gi[0], gj[0]) == (0, 1)
+    gi, gj, _, _, margin, _ = oc.art_select(np.full(5, 2.0), 1)
+    assert (gi[0], gj[0]) == (0, 1) and margin == math.inf
+
+
+def test_margins_flag_decisions_that_hang_on_the_last_digits(oracle):
+    gi, _, _, _, margin, _ = oc.art_select(np.array([5.0, 5.0 * (1 + 1e-13), 0.1, 1.0]), 1)
+    assert gi[0] == 1 and margin == pytest.approx(1e-13, rel=1e-2)
+    assert oc.rank_margin([1.0, 3.0, 3.0 + 3e-12, -2.0]) == pytest.approx(1e-12, rel=1e-3)
+    assert oc.rank_margin([2.0, 2.0, 2.0]) == math.inf
+
+
+def test_following_other_choices_is_allowed_only_inside_the_band(oracle):
+    """Two outliers whose halves differ in the 13th digit: either may be called the largest, and
+    a follower inside the band is taken and counted; anything else is refused -- a channel
+    outside the band, an exactly equal magnitude at a higher index (the index rule is not a
+    close call), the largest channel as its own partner."""
+    c0 = np.array([5.0, 0.01, 5.0 * (1 + 1e-13), 0.02, 1.0, 0.01])
+    gi, gj, _, c_own, margin, dep = oc.art_select(c0, 1)
+    assert (gi[0], gj[0], dep) == (2, 1, 0) and margin == pytest.approx(1e-13, rel=1e-2)
+    gi, gj, gt, c, _, dep = oc.art_select(c0, 1, follow=([0], [1]), band=1e-12)
+    assert (gi[0], gj[0], dep) == (0, 1, 1)
+    assert gt[0] == pytest.approx(math.atan2(0.01, 5.0) - math.pi / 4, abs=1e-15)
+    assert c[0] == c[1] == pytest.approx(math.sqrt((25.0 + 1e-4) / 2), rel=1e-15) and c[2] == c0[2]
+    _, _, _, c, _, dep = oc.art_select(c0, 1, follow=([2], [1]), band=1e-12)
+    assert dep == 0 and np.array_equal(c, c_own)
+    for bad in (([0], [1], 1e-14), ([4], [1], 1e-12), ([2], [5], 1e-12), ([2], [3], 1e-12), ([2], [2], 1e-12)):
+        with pytest.raises(ValueError):
+            oc.art_select(c0, 1, follow=(bad[0], bad[1]), band=bad[2])
+    # the two outputs of one step are tied by construction: after step 1 channels 2 and 1 hold the
+    # same value, step 2 must take the lower one, whatever the band
+    with pytest.raises(ValueError):
+        oc.art_select(c0, 2, follow=([2, 2], [1, 5]), band=1e-3)
+    gi, gj, _, _, _, dep = oc.art_select(c0, 2, follow=([2, 0], [1, 5]), band=1e-12)
+    assert list(gi) == [2, 0] and dep == 0          # 5 > 5 (1 + 1e-13) / sqrt 2: channel 0 is next, no close call
+    # equal values of different origin are a coincidence of rounding: either index may follow
+    c1 = np.array([8.0, 0.0, math.hypot(8.0, 0.0) / math.sqrt(2.0), 0.5, 0.25])
+    _, _, _, c, margin, _ = oc.art_select(c1, 1)    # channels 0, 1 <- 8 / sqrt 2, beside an input of that value
+    assert c[0] == c[1] == c[2] and margin > 0.25
+    gi, _, _, _, margin, dep = oc.art_select(c1, 2, follow=([0, 2], [1, 4]), band=1e-12)
+    assert list(gi) == [0, 2] and dep == 1 and margin == 0.0
 
 
 def test_art_list_replayed_as_givens_rotations_gives_the_same_vector(oracle):
@@ -40,26 +84,26 @@ def test_art_list_replayed_as_givens_rotations_gives_the_same_vector(oracle):
     returned (i, j, theta) does: replay the list with the oracle's Givens routine, whose sign
     convention is pinned against an explicit matrix elsewhere."""
     g = np.random.default_rng(3)
-    c0 = (g.standard_normal(300) * np.where(g.random(300) < 0.02, 200.0, 1.0)).astype(np.float32)
+    c0 = g.standard_normal(300) * np.where(g.random(300) < 0.02, 200.0, 1.0)
     P = 24
-    gi, gj, gt, c = oc.art_select(c0, P)
-    v = c0.astype(np.float64)
+    gi, gj, gt, c, _, _ = oc.art_select(c0, P)
+    v = c0.copy()
     peak = [np.max(np.abs(v))]
     for p in range(P):
         v = oracle.givens_apply(v, int(gi[p]), int(gj[p]), float(gt[p]))
-        assert abs(v[gi[p]] - v[gj[p]]) <= 1e-5 * abs(v[gi[p]])        # equalised (fp32 vector, fp64 replay)
+        assert abs(v[gi[p]] - v[gj[p]]) <= 1e-13 * abs(v[gi[p]])       # equalised
         peak.append(np.max(np.abs(v)))
-    assert np.allclose(v, c, rtol=2e-5, atol=1e-6)
-    assert abs(np.linalg.norm(v) - np.linalg.norm(c0.astype(np.float64))) <= 1e-9 * np.linalg.norm(v)
+    assert np.allclose(v, c, rtol=1e-12, atol=0)
+    assert abs(np.linalg.norm(v) - np.linalg.norm(c0)) <= 1e-12 * np.linalg.norm(v)
     assert all(b <= a * (1 + 1e-12) for a, b in zip(peak, peak[1:]))   # the peak never grows
     assert peak[-1] < 0.5 * peak[0]                                   # and the outliers are spread
 
 
 def test_art_each_angle_is_the_brute_force_minimiser(oracle):
     g = np.random.default_rng(4)
-    c0 = (g.standard_normal(64) * np.where(g.random(64) < 0.05, 50.0, 1.0)).astype(np.float32)
-    gi, gj, gt, _ = oc.art_select(c0, 6)
-    v = c0.astype(np.float64)
+    c0 = g.standard_normal(64) * np.where(g.random(64) < 0.05, 50.0, 1.0)
+    gi, gj, gt, _, _, _ = oc.art_select(c0, 6)
+    v = c0.copy()
     grid = np.linspace(0.0, 2 * math.pi, 100001)
     for p in range(6):
         a, b = v[gi[p]], v[gj[p]]
@@ -146,13 +190,14 @@ def test_hadamard_matches_scipy(n):
 
 def test_urt_vectors_are_plain_means(oracle):
     g = np.random.default_rng(11)
-    c = g.standard_normal(16 * 32).astype(np.float32)
+    c = g.standard_normal(16 * 32)
     V1, V2, V2H = oc.urt_vectors(c, 16, 32)
-    Cm = c.astype(np.float64).reshape(16, 32)
-    assert np.allclose(V1, Cm.mean(axis=1), rtol=0, atol=2e-6)
-    assert np.allclose(V2, Cm.mean(axis=0), rtol=0, atol=2e-6)
-    assert np.allclose(V2H, Cm.mean(axis=0) @ (scipy.linalg.hadamard(32) / math.sqrt(32)), rtol=0, atol=2e-6)
-    assert V1.dtype == np.float32 and V2H.dtype == np.float32
+    # written out entry by entry, independent of numpy's reductions
+    for p in range(16):
+        assert V1[p] == pytest.approx(math.fsum(c[p * 32 + q] for q in range(32)) / 32, abs=1e-15)
+    for q in range(32):
+        assert V2[q] == pytest.approx(math.fsum(c[p * 32 + q] for p in range(16)) / 16, abs=1e-15)
+    assert np.allclose(V2H, V2 @ (scipy.linalg.hadamard(32) / math.sqrt(32)), rtol=0, atol=1e-14)
 
 
 @pytest.mark.parametrize("n1,n2", [(4, 8), (16, 32), (12, 16)])
@@ -179,8 +224,8 @@ def test_constructor_flattens_a_rank_one_calibration_matrix(oracle, n1, n2):
     U1, U2 = oc.uniform_target(out["V1"]), oc.uniform_target(out["V2H"])
     want = np.outer(U1, U2) / Cm.mean()
     assert np.max(np.abs(got - want)) <= 1.5e-3 * np.linalg.norm(Cm)
-    assert np.allclose(out["V1"], V1, atol=1e-5 * np.max(np.abs(V1)))
-    assert np.allclose(out["V2H"], V2 @ H, atol=1e-5 * np.max(np.abs(V2 @ H)) + 1e-6)
+    assert np.allclose(out["V1"], V1, rtol=0, atol=1e-13 * np.max(np.abs(V1)))
+    assert np.allclose(out["V2H"], V2 @ H, rtol=0, atol=1e-13 * np.max(np.abs(V2)) * math.sqrt(n2))
     for R in (out["R1"], out["R2"]):
         assert np.max(np.abs(R.T @ R - np.eye(R.shape[0]))) <= 1e-12
     # the point of it all: each uniform target has a peak-to-rms ratio below sqrt 3, so the peak of
