@@ -182,6 +182,33 @@ sq_status sq_decode_layer(const void *X, int64_t T, int32_t K, int64_t ldx,
                           void *Y, int64_t ldy, void *workspace, void *stream);
 
 /*
+ * sq_decode_layer_static -- sq_decode_layer for callers that cannot allocate
+ * device memory or have nowhere to keep a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments without `workspace`, same limits, same error codes, same results
+ * bit for bit.  The counters, steps and codes live in a device array inside the
+ * library instead, sized for the largest call the entry point accepts
+ * (SQ_DECODE_MAX_TOKENS tokens of SQ_MAX_K channels: 512 + 32 * 8192 = 262656
+ * bytes; larger T or K is SQ_ERR_SHAPE as in sq_decode_layer).  Every GPU the
+ * library runs on holds its own copy from the first call on it until the
+ * process ends.  The call allocates and frees nothing; its first call on a
+ * device looks the array's address up (hipGetSymbolAddress), which fails with
+ * SQ_ERR_LAUNCH if the runtime refuses.
+ * All calls on one GPU share that array, which keeps the last call's codes:
+ * calls that may overlap on one GPU (two streams, two threads) race, and
+ * must use sq_decode_layer with a workspace each.  The counters start at zero
+ * when the library is loaded and every call leaves them zero, as with a
+ * caller's workspace; the error word of a workgroup that gave up waiting
+ * stays set for the life of the process.
+ */
+sq_status sq_decode_layer_static(const void *X, int64_t T, int32_t K, int64_t ldx,
+                                 const int32_t *giv_i, const int32_t *giv_j,
+                                 const float *giv_theta, int32_t P,
+                                 const void *prepared, int32_t n1, int32_t n2,
+                                 const uint8_t *Qw, const float *sw, int32_t N,
+                                 void *Y, int64_t ldy, void *stream);
+
+/*
  * sq_prepare_weights -- offline weight path of Sec. 4.2: the rotation that is
  * applied to the activations online is folded into the weights,
  * W~ = R^T W with R = G_1 ... G_P (R1 (x) R2), stored as Flat(W~_R) = W^T R, one

@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     sq_build_rotation,
     sq_build_rotation_workspace_bytes,
     sq_decode_layer,
+    sq_decode_layer_static,
     sq_decode_layer_workspace_bytes,
     sq_kron_factor,
     sq_prepare_rotation,

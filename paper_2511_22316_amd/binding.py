@@ -61,6 +61,12 @@ def _load():
             C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
             C.c_void_p, C.c_int32, C.c_int32,
             C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
+        lib.sq_decode_layer_static.restype = C.c_int
+        lib.sq_decode_layer_static.argtypes = [
+            C.c_void_p, C.c_int64, C.c_int32, C.c_int64,
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+            C.c_void_p, C.c_int32, C.c_int32,
+            C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p]
         lib.sq_w4a4_gemm.restype = C.c_int
         lib.sq_w4a4_gemm.argtypes = [
             C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
@@ -199,6 +205,27 @@ def sq_decode_layer(X, giv_i, giv_j, giv_theta, prepared, n1, n2, Qw, sw, Y, wor
         None if gt is None else gt.ctypes.data, P,
         _dev_ptr(prepared), int(n1), int(n2),
         _dev_ptr(Qw), _dev_ptr(sw), N, _dev_ptr(Y), ldy, _dev_ptr(workspace), _stream_handle(stream))
+    _check(code)
+
+
+def sq_decode_layer_static(X, giv_i, giv_j, giv_theta, prepared, n1, n2, Qw, sw, Y, stream=None) -> None:
+    """sq_decode_layer with the workspace inside the library (no device allocation anywhere on
+    the way: the binding passes pointers of existing tensors only)."""
+    gi, gj, gt = _host(giv_i, np.int32), _host(giv_j, np.int32), _host(giv_theta, np.float32)
+    P = 0 if gi is None else int(gi.size)
+    T, K = int(X.shape[0]), int(X.shape[1])
+    N = int(Qw.shape[0])
+    ldx = int(X.stride(0)) if T > 1 else K
+    ldy = int(Y.stride(0)) if T > 1 else max(N, 1)
+    need_p = sq_prepared_rotation_bytes(n1, n2)
+    if prepared is not None and need_p > 0 and prepared.numel() * prepared.element_size() < need_p:
+        raise ValueError("prepared is smaller than sq_prepared_rotation_bytes")
+    code = _load().sq_decode_layer_static(
+        _dev_ptr(X), T, K, ldx,
+        None if gi is None else gi.ctypes.data, None if gj is None else gj.ctypes.data,
+        None if gt is None else gt.ctypes.data, P,
+        _dev_ptr(prepared), int(n1), int(n2),
+        _dev_ptr(Qw), _dev_ptr(sw), N, _dev_ptr(Y), ldy, _stream_handle(stream))
     _check(code)
 
 

@@ -397,26 +397,66 @@ extern "C" int64_t sq_decode_layer_workspace_bytes(int64_t T, int32_t K)
     return 512 + T * (int64_t)(K / 2);       // counters, steps, codes
 }
 
-extern "C" sq_status sq_decode_layer(const void *X, int64_t T, int32_t K, int64_t ldx,
-                                     const int32_t *giv_i, const int32_t *giv_j, const float *giv_theta,
-                                     int32_t P, const void *prepared, int32_t n1, int32_t n2,
-                                     const uint8_t *Qw, const float *sw, int32_t N, void *Y, int64_t ldy,
-                                     void *workspace, void *stream)
+// ---- workspace of sq_decode_layer_static ----------------------------------------------------------
+// Counters, steps and codes of the largest legal call (SQ_DECODE_MAX_TOKENS tokens of SQ_MAX_K
+// channels) in device memory that belongs to the loaded code object: 256.5 KiB per GPU, there
+// from the moment the library is loaded on that GPU until the process ends, zero-filled by the
+// loader (which is the state the counters must start from).
+namespace sq {
+constexpr size_t kStaticDecodeBytes = 512 + (size_t)SQ_DECODE_MAX_TOKENS * (SQ_MAX_K / 2);
+}
+static __device__ __align__(256) unsigned char sq_decode_scratch[sq::kStaticDecodeBytes];
+
+namespace sq {
+
+// Device address of sq_decode_scratch on the current device.  The array's name is only a handle
+// on the host: every GPU holds its own copy at its own address, looked up once per device.
+static void *decode_scratch_address()
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex guard;
+    static void *address[kMaxDevices] = {};
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(guard);
+    if (address[device] == nullptr) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(sq_decode_scratch)) != hipSuccess) return nullptr;
+        address[device] = p;
+    }
+    return address[device];
+}
+
+}  // namespace sq
+
+// Validation and launch shared by sq_decode_layer and sq_decode_layer_static.  `workspace` is
+// device memory (counters, steps, codes: sq_decode_layer_workspace_bytes of it), or null for the
+// array inside the library, whose address is looked up once every check has passed.
+static sq_status decode_layer_any(const void *X, int64_t T, int32_t K, int64_t ldx, const int32_t *giv_i,
+                                  const int32_t *giv_j, const float *giv_theta, int32_t P, const void *prepared,
+                                  int32_t n1, int32_t n2, const uint8_t *Qw, const float *sw, int32_t N, void *Y,
+                                  int64_t ldy, void *workspace, bool use_static, void *stream)
 {
     if (T < 0 || T > SQ_DECODE_MAX_TOKENS || N < 0 || P < 0 || P > SQ_MAX_GIVENS) return SQ_ERR_SHAPE;
     if (!sq::rotation_shape_ok(K, n1, n2) || ldx < K || ldy < N) return SQ_ERR_SHAPE;
     if (!sq::decode_layer_covers(n1, n2)) return SQ_ERR_SHAPE;
     if (P > 0 && (!giv_i || !giv_j || !giv_theta)) return SQ_ERR_NULL;
     if (!prepared) return SQ_ERR_NULL;
-    if (T > 0 && N > 0 && (!X || !Qw || !sw || !Y || !workspace)) return SQ_ERR_NULL;
+    if (T > 0 && N > 0 && (!X || !Qw || !sw || !Y || (!use_static && !workspace))) return SQ_ERR_NULL;
     const sq::ListCache *cache = nullptr;
     const sq_status list_status = sq::cached_list(giv_i, giv_j, giv_theta, P, K, n2, &cache);
     if (list_status != SQ_OK) return list_status;
     if (!cache->plan_ok) return SQ_ERR_SHAPE;
     if ((ldx % 8) != 0 || ((uintptr_t)X & 15) || ((uintptr_t)prepared & 15) || ((uintptr_t)Qw & 15) ||
-        ((uintptr_t)sw & 3) || ((uintptr_t)Y & 1) || ((uintptr_t)workspace & 255))
+        ((uintptr_t)sw & 3) || ((uintptr_t)Y & 1) || (!use_static && ((uintptr_t)workspace & 255)))
         return SQ_ERR_ALIGN;
     if (T == 0 || N == 0) return SQ_OK;
+    if (use_static) {
+        // every size that got here fits: T <= SQ_DECODE_MAX_TOKENS and K <= SQ_MAX_K were checked
+        static_assert(512 + SQ_DECODE_MAX_TOKENS * (SQ_MAX_K / 2) <= sq::kStaticDecodeBytes, "largest call fits");
+        workspace = sq::decode_scratch_address();
+        if (!workspace) return SQ_ERR_LAUNCH;
+    }
     const sq::PreparedLayout l = sq::prepared_layout(n1, n2);
     const char *base = static_cast<const char *>(prepared);
     char *ws = static_cast<char *>(workspace);
@@ -426,4 +466,24 @@ extern "C" sq_status sq_decode_layer(const void *X, int64_t T, int32_t K, int64_
                                      reinterpret_cast<uint8_t *>(ws + 512), reinterpret_cast<float *>(ws + 256),
                                      reinterpret_cast<int *>(ws), Qw, sw, N, static_cast<__half *>(Y), ldy,
                                      static_cast<hipStream_t>(stream));
+}
+
+extern "C" sq_status sq_decode_layer(const void *X, int64_t T, int32_t K, int64_t ldx,
+                                     const int32_t *giv_i, const int32_t *giv_j, const float *giv_theta,
+                                     int32_t P, const void *prepared, int32_t n1, int32_t n2,
+                                     const uint8_t *Qw, const float *sw, int32_t N, void *Y, int64_t ldy,
+                                     void *workspace, void *stream)
+{
+    return decode_layer_any(X, T, K, ldx, giv_i, giv_j, giv_theta, P, prepared, n1, n2, Qw, sw, N, Y, ldy, workspace,
+                            false, stream);
+}
+
+extern "C" sq_status sq_decode_layer_static(const void *X, int64_t T, int32_t K, int64_t ldx,
+                                            const int32_t *giv_i, const int32_t *giv_j,
+                                            const float *giv_theta, int32_t P, const void *prepared,
+                                            int32_t n1, int32_t n2, const uint8_t *Qw, const float *sw,
+                                            int32_t N, void *Y, int64_t ldy, void *stream)
+{
+    return decode_layer_any(X, T, K, ldx, giv_i, giv_j, giv_theta, P, prepared, n1, n2, Qw, sw, N, Y, ldy, nullptr,
+                            true, stream);
 }

@@ -134,6 +134,24 @@ def test_decode_layer_argument_errors_and_workspace_size(lib):
     assert size(33, 512) == 0 and size(4, 0) == 0 and size(-1, 512) == 0
 
 
+def test_decode_layer_static_argument_errors(lib):
+    """The entry point with the workspace inside the library: the same checks in the same order
+    (every case here returns before anything touches a device)."""
+    def call(T=8, K=512, ldx=512, gi=(1,), gj=(2,), gt=(0.1,), prepared=FAKE, n1=16, n2=32, X=FAKE, Qw=FAKE, sw=FAKE,
+             N=64, Y=FAKE, ldy=64):
+        gi_a, gj_a, gt_a = np.asarray(gi, np.int32), np.asarray(gj, np.int32), np.asarray(gt, np.float32)
+        return lib.sq_decode_layer_static(X, T, K, ldx, gi_a.ctypes.data, gj_a.ctypes.data, gt_a.ctypes.data,
+                                          len(gi_a), prepared, n1, n2, Qw, sw, N, Y, ldy, None)
+    assert call(T=33) == 2 and call(T=-1) == 2      # beyond what the array inside the library holds
+    assert call(K=32768, n1=128, n2=256, ldx=32768) == 2
+    assert call(K=500) == 2 and call(ldx=256) == 2 and call(ldy=32) == 2
+    assert call(K=64, n1=8, n2=8, ldx=64) == 2
+    assert call(gi=(512,)) == 3
+    assert call(prepared=None) == 1 and call(X=None) == 1 and call(Qw=None) == 1 and call(Y=None) == 1
+    assert call(X=FAKE + 2) == 4 and call(Y=FAKE + 1) == 4
+    assert call(T=0) == 0 and call(N=0) == 0
+
+
 def _gemm(lib, T=4, K=64, N=8, ldy=8, Qx=FAKE, sx=FAKE, Qw=FAKE, sw=FAKE, Y=FAKE):
     return lib.sq_w4a4_gemm(Qx, sx, T, K, Qw, sw, N, Y, ldy, None, None)
 
