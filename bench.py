@@ -9,15 +9,28 @@ The headline workload is the attention-projection shape T=2048, K=N=4096.  Input
 HBM before the clock starts, and the step cycles through a ring of buffer sets larger than the
 256 MB last-level cache so that "HBM" numbers are not cache numbers.
 
+How the times are taken.  Every figure comes from HIP events recorded on the stream the kernels
+run on.  After W warm-up steps the step is timed in blocks of exactly K steps (--steps), as many
+blocks as it takes to reach 100 steps (at least three): the headline `value` is the median
+block's time per step, the minimum is beside it.  Each kernel is also timed alone, the same
+way; where a kernel is shorter than the host's Python -> C call path (about 10 us per call: the
+rotate+quantize kernel at 2048 tokens is just that long, at 8 tokens it takes 6 us) the host
+enqueues whole batches while a spin kernel holds the stream, so that the GPU runs them back to
+back between two events.  The roofline figures come from these per-kernel times.  (A HIP graph of
+the same launches was tried for this and replays 1-5 us per node slower than the stream runs
+them; the held stream is used only where needed because the clocks sag during the hold.)
+
 Prints ONE JSON line: layer time (us), the per-kernel rates, the roofline of the dominant kernel
 (the GEMM: int8 MFMA) and of the rotate+quantize kernel (HBM), and the CPU oracle timed on this
-box's host cores beside them.
+box's host cores beside them (all cores and one thread; the headline layer and large_prefill).
 """
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -30,10 +43,12 @@ import numpy as np
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 INT8_MFMA_PEAK_TOPS = 5000.0    # MI355X dense int8 matrix peak
 RING_BYTES = 640 << 20          # > 2x the 256 MB Infinity Cache
+MIN_TIMED_STEPS = 100           # per figure, whatever --steps says
+MIN_BLOCKS = 3
 
-# HBM-side bytes per launch, from the rocprofv3 --pmc runs summarised in
-# profiles/w4a4_gemm_<workload>.md and profiles/rotate_quantize_<workload>.md (FETCH_SIZE and
-# WRITE_SIZE, each scaled by what the counter reads for a plain 256 MiB copy: x2.000 and x1.000).
+# HBM-side bytes per launch.  NOT measured in this run: constants copied from the rocprofv3 --pmc
+# summaries profiles/w4a4_gemm_<workload>.md and profiles/rotate_quantize_<workload>.md (FETCH_SIZE
+# and WRITE_SIZE, each scaled by what the counter reads for a plain 256 MiB copy: x2.000, x1.000).
 PROFILED_TRAFFIC = {
     "attn_proj": {"gemm": {"fetch": 33797816, "write": 16777216},
                   "rotate_quantize": {"fetch": 17064267, "write": 4227072}},
@@ -137,42 +152,134 @@ def settle(torch, fn, sets):
     return n
 
 
+def _summary(per_call_ms, blocks, calls_per_block):
+    us = [m * 1e3 for m in per_call_ms]
+    return {"median_us": statistics.median(us), "min_us": min(us), "mean_us": sum(us) / len(us),
+            "blocks": blocks, "calls_per_block": calls_per_block}
+
+
 def timed(torch, fn, sets, steps, warmup):
-    """(wall ms per call, event ms per call): events are recorded on the stream the kernels use."""
+    """Eager launches.  W warm-up calls, then blocks of exactly `steps` calls each, enough of them
+    for MIN_TIMED_STEPS calls (at least MIN_BLOCKS), an event between blocks and one host
+    synchronization at the end.  -> summary of the per-call times of the blocks, with the wall
+    time per call over all blocks beside it."""
     for w in range(warmup):
         fn(w % sets)
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    blocks = max(MIN_BLOCKS, -(-MIN_TIMED_STEPS // steps))
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(blocks + 1)]
     t0 = time.perf_counter()
-    e0.record()
-    for k in range(steps):
-        fn(k % sets)
-    e1.record()
+    ev[0].record()
+    k = 0
+    for b in range(blocks):
+        for _ in range(steps):
+            fn(k % sets)
+            k += 1
+        ev[b + 1].record()
     torch.cuda.synchronize()
-    wall = (time.perf_counter() - t0) * 1e3 / steps
-    return wall, e0.elapsed_time(e1) / steps
+    wall_ms = (time.perf_counter() - t0) * 1e3 / (blocks * steps)
+    out = _summary([ev[b].elapsed_time(ev[b + 1]) / steps for b in range(blocks)], blocks, steps)
+    out["wall_us"] = wall_ms * 1e3
+    return out
+
+
+_SLEEP_CYCLES_PER_MS = None
+
+
+def _hold_stream(torch, ms):
+    """Keep the current stream busy for about `ms` milliseconds with torch's spin kernel (one
+    wave), so that launches enqueued meanwhile pile up behind it."""
+    global _SLEEP_CYCLES_PER_MS
+    if _SLEEP_CYCLES_PER_MS is None:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda._sleep(1000000)
+        e0.record()
+        torch.cuda._sleep(10000000)
+        e1.record()
+        torch.cuda.synchronize()
+        _SLEEP_CYCLES_PER_MS = 10000000 / max(e0.elapsed_time(e1), 1e-3)
+    torch.cuda._sleep(int(ms * _SLEEP_CYCLES_PER_MS))
+
+
+HOST_CALL_US = 16.0             # a Python -> C launch call costs the host 8-11 us; kernels at least this long
+                                # are never waiting for the host in a plain eager loop
+
+
+def timed_queued(torch, fn, sets, steps, kernel_us):
+    """Eager launches with the host taken out of the timed region, for kernels shorter than the
+    host's call path (about 10 us per Python -> C call; the kernel at hand takes about kernel_us):
+    the stream is held by a spin kernel just long enough for the host to get ahead, the host
+    enqueues a whole batch of launches meanwhile, and the GPU then runs the batch back to back
+    between two events.  Batches of max(steps, MIN_TIMED_STEPS) launches (at most 400, to stay
+    inside the hardware queue), MIN_BLOCKS of them.  The hold is kept short because the clocks sag
+    while the one-wave spin kernel runs (after a hold of 2.5 ms a batch of GEMMs ran 3-10 % slower
+    than in a plain eager loop).  -> summary of the per-launch times of the batches."""
+    n = min(400, max(MIN_TIMED_STEPS, steps))
+    for i in range(min(sets, 4)):
+        fn(i)
+    torch.cuda.synchronize()
+    ev = []
+    for b in range(MIN_BLOCKS):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for k in range(40):                    # the clocks' working point: the same launches, untimed
+            fn(k % sets)
+        _hold_stream(torch, (n + 40) * max(0.5, HOST_CALL_US - kernel_us) * 1e-3)
+        e0.record()
+        for k in range(n):
+            fn(k % sets)
+        e1.record()
+        torch.cuda.synchronize()
+        ev.append((e0, e1))
+    return _summary([e0.elapsed_time(e1) / n for e0, e1 in ev], MIN_BLOCKS, n)
+
+
+def kernel_time(torch, fn, sets, steps, warmup):
+    """Launch duration of one call in a stream of the same calls.  Plain eager blocks (timed) when
+    the call keeps the GPU busy longer than the host needs for the next call; otherwise batches
+    enqueued behind a held stream (timed_queued).  -> summary with the method named."""
+    eager = timed(torch, fn, sets, steps, warmup)
+    if eager["median_us"] >= HOST_CALL_US:
+        eager["method"] = "eager blocks (host call path shorter than the kernel)"
+        eager["eager_median_us"] = eager["median_us"]
+        return eager
+    queued = timed_queued(torch, fn, sets, steps, eager["median_us"])
+    queued["method"] = "batches enqueued behind a held stream"
+    queued["eager_median_us"] = eager["median_us"]
+    if queued["median_us"] > eager["median_us"]:           # the host was not the limit after all
+        eager["method"] = "eager blocks (no slower than queued batches)"
+        eager["eager_median_us"] = eager["median_us"]
+        return eager
+    return queued
 
 
 def measure_layer(cfg, torch, sq, synth, steps, warmup):
     B = LayerBuffers(cfg, torch, sq, synth)
     T, K, N = cfg.T, cfg.K, cfg.N
     settled = settle(torch, B.step, B.sets)
-    wall_ms, ev_ms = timed(torch, B.step, B.sets, steps, warmup)
-    _, rq_ms = timed(torch, B.rotate_quantize, B.sets, steps, warmup)
-    _, gm_ms = timed(torch, B.gemm, B.sets, steps, warmup)
-    _, rq_plain_ms = timed(torch, B.rotate_quantize_plain, B.sets, steps, warmup)
-    single_ms = None
+    layer = timed(torch, B.step, B.sets, steps, warmup)
+    rq = kernel_time(torch, B.rotate_quantize, B.sets, steps, warmup)
+    gm = kernel_time(torch, B.gemm, B.sets, steps, warmup)
+    rq_plain = kernel_time(torch, B.rotate_quantize_plain, B.sets, steps, warmup)
+    single = single_k = None
     if T <= 32 and (cfg.n1, cfg.n2) in ((16, 32), (32, 32), (32, 64), (64, 64), (64, 128)):
-        single_ms, _ = timed(torch, B.single_launch, B.sets, steps, warmup)
+        single = timed(torch, B.single_launch, B.sets, steps, warmup)
+        single_k = kernel_time(torch, B.single_launch, B.sets, steps, warmup)
+    rq_us, gm_us = rq["mean_us"], gm["mean_us"]
     out = {
         "workload": cfg.name, "T": T, "K": K, "N": N, "n1": cfg.n1, "n2": cfg.n2, "givens_pairs": cfg.P,
-        "layer_us": wall_ms * 1e3, "layer_us_events": ev_ms * 1e3,
-        "rotate_quant_us": rq_ms * 1e3, "gemm_us": gm_ms * 1e3,
-        "rotate_quant_us_unprepared_entry": rq_plain_ms * 1e3,
-        "layer_us_single_launch": None if single_ms is None else single_ms * 1e3,
-        "rotate_quant_GBps": rq_bytes(T, K) / (rq_ms * 1e-3) / 1e9,
-        "gemm_int_TOPS": gemm_ops(T, K, N) / (gm_ms * 1e-3) / 1e12,
-        "gemm_weight_stream_GBps": (N * K / 2) / (gm_ms * 1e-3) / 1e9,
+        "layer_us": layer["median_us"], "layer_us_min": layer["min_us"], "layer_us_wall": layer["wall_us"],
+        "timing_blocks": layer["blocks"], "steps_per_block": steps,
+        # per kernel: mean = the average launch duration the rooflines use
+        "rotate_quant_us": rq_us, "rotate_quant_us_median": rq["median_us"], "rotate_quant_us_min": rq["min_us"],
+        "rotate_quant_timing": rq["method"], "rotate_quant_us_eager": rq["eager_median_us"],
+        "gemm_us": gm_us, "gemm_us_median": gm["median_us"], "gemm_us_min": gm["min_us"],
+        "gemm_timing": gm["method"], "gemm_us_eager": gm["eager_median_us"],
+        "rotate_quant_us_unprepared_entry": rq_plain["mean_us"],
+        "layer_us_single_launch": None if single is None else single["median_us"],
+        "single_launch_kernel_us": None if single_k is None else single_k["mean_us"],
+        "rotate_quant_GBps": rq_bytes(T, K) / (rq_us * 1e-6) / 1e9,
+        "gemm_int_TOPS": gemm_ops(T, K, N) / (gm_us * 1e-6) / 1e12,
+        "gemm_weight_stream_GBps": (N * K / 2) / (gm_us * 1e-6) / 1e9,
         "ring_sets": B.sets, "settle_steps": settled,
         "massive_channels": [int(c) for c in synth.massive_channels(cfg)],
     }
@@ -200,42 +307,69 @@ def measure_build_rotation(cfg, torch, sq, synth, steps, warmup):
     ws = torch.empty((sq.sq_build_rotation_workspace_bytes(cfg.T, cfg.n1, cfg.n2),), dtype=torch.uint8, device=dev)
     call = lambda i: sq.sq_build_rotation(Xs[i], cfg.n1, cfg.n2, gi, gj, gt, R1, R2, ws)
     settle(torch, call, sets)
-    _, ms = timed(torch, call, sets, steps, warmup)
-    return {"workload": cfg.name, "T": cfg.T, "n1": cfg.n1, "n2": cfg.n2, "art_steps": cfg.P, "us": ms * 1e3,
-            "calibration_bytes": 2.0 * cfg.T * cfg.K, "whole_call_GBps": 2.0 * cfg.T * cfg.K / (ms * 1e-3) / 1e9,
+    us = timed(torch, call, sets, steps, warmup)["median_us"]
+    return {"workload": cfg.name, "T": cfg.T, "n1": cfg.n1, "n2": cfg.n2, "art_steps": cfg.P, "us": us,
+            "calibration_bytes": 2.0 * cfg.T * cfg.K, "whole_call_GBps": 2.0 * cfg.T * cfg.K / (us * 1e-6) / 1e9,
             "ring_sets": sets}
 
 
-def cpu_baseline(cfg, synth):
-    """The CPU oracle, as it stands, on this machine's host cores: rotate+quantize of every token, then
-    the integer GEMM with its dequantization on every token (for layers much larger than the
-    headline one the GEMM is timed on the first 2048 tokens and scaled linearly in T)."""
-    import oracle
-    oracle.build()
-    L = synth.layer(cfg)
-    Ts = min(cfg.T, 2048)
-    Wt = synth.weights_t(cfg)
-    Qw, sw = oracle.prepare_weights(Wt, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)   # offline, untimed
+def _oracle_sample(oracle, synth, cfg, L, Qw, sw, tokens_rq, tokens_gemm):
+    """Seconds the oracle needs for rotate+quantize of the first tokens_rq tokens and for its GEMM
+    of the first tokens_gemm tokens against the weight rows in Qw."""
     t0 = time.perf_counter()
-    Qx, sx = oracle.quantize_rows(oracle.rotate(L.X, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2))
+    Qx, sx = oracle.quantize_rows(oracle.rotate(L.X[:tokens_rq], L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2))
     t_rq = time.perf_counter() - t0
     t0 = time.perf_counter()
-    oracle.gemm(Qx[:Ts], sx[:Ts], Qw, sw)
-    t_gemm = (time.perf_counter() - t0) * (cfg.T / Ts)
-    gemm_note = (f"GEMM of all {cfg.T} tokens x {cfg.N} outputs timed in full" if Ts == cfg.T else
-                 f"GEMM timed on the first {Ts} tokens x all {cfg.N} outputs and scaled by {cfg.T / Ts:g}")
-    return {
-        "value": (t_rq + t_gemm) * 1e6, "unit": "us", "cores": oracle.num_threads(), "kind": "oracle",
-        "sample": f"one layer: rotate+quantize of all {cfg.T} tokens timed in full; {gemm_note}",
-        "rotate_quant_GBps": rq_bytes(cfg.T, cfg.K) / t_rq / 1e9,
-        "gemm_int_TOPS": gemm_ops(cfg.T, cfg.K, cfg.N) / t_gemm / 1e12,
-    }
+    oracle.gemm(Qx[:tokens_gemm], sx[:tokens_gemm], Qw, sw)
+    return t_rq, time.perf_counter() - t0
+
+
+def cpu_baseline(cfg, synth, channels=None, tokens_rq=None, tokens_gemm=None, one_thread_fraction=16):
+    """The CPU oracle, as it stands, on this machine's host cores, on a bounded sample of the layer:
+    rotate+quantize of the first tokens_rq tokens, then the integer GEMM with its dequantization of
+    the first tokens_gemm tokens against the first `channels` output channels (defaults: the
+    whole layer); each part is scaled linearly to the whole layer, and the sample is named.
+    Once with every core and once, on a sample one_thread_fraction times smaller, with one thread
+    (the thread count is set through the OpenMP runtime the oracle library is linked with)."""
+    import oracle
+    oracle.build()
+    T, K, N = cfg.T, cfg.K, cfg.N
+    channels = N if channels is None else min(N, channels)
+    tokens_rq = T if tokens_rq is None else min(T, tokens_rq)
+    tokens_gemm = T if tokens_gemm is None else min(T, tokens_gemm)
+    L = synth.layer(cfg, max(tokens_rq, tokens_gemm))
+    Wt = synth.weight_rows_t(cfg, np.arange(channels))
+    Qw, sw = oracle.prepare_weights(Wt, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)   # offline, untimed
+    cores = oracle.num_threads()
+
+    def run(trq, tgm, label):
+        t_rq, t_gm = _oracle_sample(oracle, synth, cfg, L, Qw, sw, trq, tgm)
+        t_rq_full, t_gm_full = t_rq * (T / trq), t_gm * (T / tgm) * (N / channels)
+        return {"value": (t_rq_full + t_gm_full) * 1e6, "unit": "us", "kind": "oracle",
+                "sample": (f"{label}: rotate+quantize of {trq} of {T} tokens (scaled x{T / trq:g}); GEMM of "
+                           f"{tgm} tokens x {channels} of {N} output channels (scaled x{T / tgm * N / channels:g})"),
+                "sampled_seconds": t_rq + t_gm,
+                "rotate_quant_GBps": rq_bytes(T, K) / t_rq_full / 1e9,
+                "gemm_int_TOPS": gemm_ops(T, K, N) / t_gm_full / 1e12}
+
+    out = run(tokens_rq, tokens_gemm, f"one {cfg.name} layer")
+    out["cores"] = cores
+    omp = ctypes.CDLL("libgomp.so.1")
+    omp.omp_set_num_threads(1)
+    try:
+        single = run(max(1, tokens_rq // one_thread_fraction), max(1, tokens_gemm // one_thread_fraction),
+                     f"one {cfg.name} layer, one thread")
+    finally:
+        omp.omp_set_num_threads(cores)
+    single["cores"] = 1
+    out["one_thread"] = single
+    return out
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="attn_proj", help="layer shape for the headline number")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -244,6 +378,9 @@ def main() -> int:
                     help="time only the offline constructor on --workload and print its numbers")
     ap.add_argument("--only-single-launch", action="store_true",
                     help="time only sq_decode_layer (the layer in one launch, at most 32 tokens) on --workload")
+    ap.add_argument("--only-kernels", action="store_true",
+                    help="run only the two kernels of --workload, each in queued batches (what the rocprofv3 "
+                         "summaries under profiles/ are taken from)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run three plain 256 MiB device copies (known traffic: the scale for "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -278,9 +415,17 @@ def main() -> int:
     if args.only_single_launch:
         B = LayerBuffers(cfg, torch, sq, synth)
         settle(torch, B.single_launch, B.sets)
-        _, ms = timed(torch, B.single_launch, B.sets, args.steps, args.warmup)
-        print(json.dumps({"workload": cfg.name, "layer_us_single_launch": ms * 1e3, "ring_sets": B.sets,
-                          "weight_stream_GBps": cfg.N * cfg.K / 2 / (ms * 1e-3) / 1e9}))
+        us = kernel_time(torch, B.single_launch, B.sets, args.steps, args.warmup)["mean_us"]
+        print(json.dumps({"workload": cfg.name, "layer_us_single_launch": us, "ring_sets": B.sets,
+                          "weight_stream_GBps": cfg.N * cfg.K / 2 / (us * 1e-6) / 1e9}))
+        return 0
+    if args.only_kernels:
+        B = LayerBuffers(cfg, torch, sq, synth)
+        settle(torch, B.step, B.sets)
+        rq = kernel_time(torch, B.rotate_quantize, B.sets, args.steps, args.warmup)
+        gm = kernel_time(torch, B.gemm, B.sets, args.steps, args.warmup)
+        print(json.dumps({"workload": cfg.name, "ring_sets": B.sets, "rotate_quant_us": rq["mean_us"],
+                          "gemm_us": gm["mean_us"], "launches_each": rq["blocks"] * rq["calls_per_block"]}))
         return 0
     head = measure_layer(cfg, torch, sq, synth, args.steps, args.warmup)
     extra = {}
@@ -293,16 +438,21 @@ def main() -> int:
     gemm_tops = head["gemm_int_TOPS"]
     prof = PROFILED_TRAFFIC.get(cfg.name, {})
     traffic = lambda k: (prof[k]["fetch"] + prof[k]["write"]) if k in prof else None
+    source = lambda stem: (f"constant from profiles/{stem}_{cfg.name}.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE), "
+                           "not measured in this run") if cfg.name in PROFILED_TRAFFIC else None
+    timing_note = "average launch duration between HIP events on the launch stream; "
     if cfg.T <= 64:      # decode-shaped GEMM: one pass over the weights, HBM-bound
         gemm_roofline = {"kernel": "w4a4_gemm_skinny_kernel", "bound": "hbm", "achieved": head["gemm_weight_stream_GBps"],
                          "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": head["gemm_weight_stream_GBps"] / HBM_PEAK_GBPS,
-                         "bytes_per_launch": cfg.N * cfg.K / 2.0, "traffic": traffic("gemm"),
-                         "traffic_detail": prof.get("gemm")}
+                         "bytes_per_launch": cfg.N * cfg.K / 2.0, "launch_us": head["gemm_us"], "timing": timing_note + head["gemm_timing"],
+                         "traffic": traffic("gemm"), "traffic_detail": prof.get("gemm"),
+                         "traffic_source": source("w4a4_gemm")}
     else:
         gemm_roofline = {"kernel": "w4a4_gemm_kernel", "bound": "mfma", "achieved": gemm_tops,
                          "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": gemm_tops / INT8_MFMA_PEAK_TOPS,
-                         "ops_per_launch": gemm_ops(cfg.T, cfg.K, cfg.N), "traffic": traffic("gemm"),
-                         "traffic_detail": prof.get("gemm")}
+                         "ops_per_launch": gemm_ops(cfg.T, cfg.K, cfg.N), "launch_us": head["gemm_us"],
+                         "timing": timing_note + head["gemm_timing"], "traffic": traffic("gemm"), "traffic_detail": prof.get("gemm"),
+                         "traffic_source": source("w4a4_gemm")}
     result = {
         "metric": f"layer time, rotate+quant then W4A4 GEMM, T={cfg.T} K={cfg.K} N={cfg.N} (also: rotate+quant HBM GB/s, GEMM int TOPS)",
         "value": head["layer_us"], "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -311,18 +461,24 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: T={cfg.T} K={cfg.K} ({cfg.n1}x{cfg.n2}) N={cfg.N}, {cfg.P} Givens pairs",
                    "ring_sets": head["ring_sets"], "settle_steps_before_warmup": head["settle_steps"],
+                   "value_is": f"median over {head['timing_blocks']} blocks of {args.steps} eager steps each, HIP events",
                    "massive_channels": head["massive_channels"]},
+        "layer_us_min": head["layer_us_min"], "layer_us_wall": head["layer_us_wall"],
         "rotate_quant_GBps": head["rotate_quant_GBps"], "gemm_int_TOPS": gemm_tops,
         "rotate_quant_us": head["rotate_quant_us"], "gemm_us": head["gemm_us"],
+        "rotate_quant_us_min": head["rotate_quant_us_min"], "gemm_us_min": head["gemm_us_min"],
+        "rotate_quant_us_eager": head["rotate_quant_us_eager"], "gemm_us_eager": head["gemm_us_eager"],
         "rotate_quant_us_unprepared_entry": head["rotate_quant_us_unprepared_entry"],
         "layer_us_single_launch": head["layer_us_single_launch"],
         "roofline": gemm_roofline,
-        "roofline_rotate_quant": {"kernel": "rotate_quantize", "bound": "hbm", "achieved": head["rotate_quant_GBps"],
-                                  "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+        "roofline_rotate_quant": {"kernel": "rotate_quantize_mfma_kernel", "bound": "hbm",
+                                  "achieved": head["rotate_quant_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                                   "frac": head["rotate_quant_GBps"] / HBM_PEAK_GBPS,
-                                  "bytes_per_launch": rq_bytes(cfg.T, cfg.K),
+                                  "bytes_per_launch": rq_bytes(cfg.T, cfg.K), "launch_us": head["rotate_quant_us"],
+                                  "timing": timing_note + head["rotate_quant_timing"],
                                   "traffic": traffic("rotate_quantize"),
-                                  "traffic_detail": prof.get("rotate_quantize")},
+                                  "traffic_detail": prof.get("rotate_quantize"),
+                                  "traffic_source": source("rotate_quantize")},
         "other_workloads": extra,
     }
     if not args.no_extra and cfg.n2 & (cfg.n2 - 1) == 0:
@@ -330,6 +486,11 @@ def main() -> int:
                                                           max(2, args.warmup // 4))
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, synth)
+        if not args.no_extra and cfg.name != "large_prefill":
+            # beside the large layer as well: 1024 of its 8192 tokens through rotate+quantize, 64 tokens
+            # x 4096 of its 28672 output channels through the GEMM
+            result["cpu_baseline_large_prefill"] = cpu_baseline(synth.CONFIGS["large_prefill"], synth, channels=4096,
+                                                                tokens_rq=1024, tokens_gemm=64, one_thread_fraction=8)
     print(json.dumps(result))
     return 0
 

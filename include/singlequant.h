@@ -40,7 +40,8 @@ typedef enum {
                             the limits below                                            */
     SQ_ERR_INDEX = 3,    /* a Givens index outside [0, K) or i == j                     */
     SQ_ERR_ALIGN = 4,    /* a pointer or leading dimension breaks the stated alignment  */
-    SQ_ERR_LAUNCH = 5    /* the HIP runtime refused the launch                          */
+    SQ_ERR_LAUNCH = 5,   /* the HIP runtime refused the launch                          */
+    SQ_ERR_TIMEOUT = 6   /* sq_decode_layer_status only: a workgroup gave up its wait   */
 } sq_status;
 
 /* Limits (SQ_ERR_SHAPE beyond them): n1 <= 128, n2 <= 256 and n2 a multiple
@@ -182,6 +183,21 @@ sq_status sq_decode_layer(const void *X, int64_t T, int32_t K, int64_t ldx,
                           void *Y, int64_t ldy, void *workspace, void *stream);
 
 /*
+ * sq_decode_layer_status -- has any sq_decode_layer call on this workspace given
+ * up a wait (see the error word above)?  The one call of this library that
+ * waits: it blocks until `stream` has finished all work enqueued so far, copies
+ * the error word to the host and, if it was set, clears it.
+ *   workspace  the workspace of the calls in question, or NULL for the array
+ *              inside the library that sq_decode_layer_static uses (on the
+ *              current device)
+ * Returns SQ_OK (no call gave up: every Y was written), SQ_ERR_TIMEOUT (at
+ * least one workgroup of at least one call since the last check left its part
+ * of Y unwritten) or SQ_ERR_LAUNCH (the runtime refused the wait or the copy).
+ * Not capturable in a HIP graph.
+ */
+sq_status sq_decode_layer_status(void *workspace, void *stream);
+
+/*
  * sq_decode_layer_static -- sq_decode_layer for callers that cannot allocate
  * device memory or have nowhere to keep a workspace: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same
@@ -199,7 +215,7 @@ sq_status sq_decode_layer(const void *X, int64_t T, int32_t K, int64_t ldx,
  * must use sq_decode_layer with a workspace each.  The counters start at zero
  * when the library is loaded and every call leaves them zero, as with a
  * caller's workspace; the error word of a workgroup that gave up waiting
- * stays set for the life of the process.
+ * stays set until sq_decode_layer_status(NULL, stream) reads and clears it.
  */
 sq_status sq_decode_layer_static(const void *X, int64_t T, int32_t K, int64_t ldx,
                                  const int32_t *giv_i, const int32_t *giv_j,
@@ -297,6 +313,43 @@ int64_t sq_build_rotation_workspace_bytes(int64_t T, int32_t n1, int32_t n2);
 
 /* Static, human-readable name of a status code. */
 const char *sq_status_string(sq_status status);
+
+/* ---- Debug and test aids ------------------------------------------------------
+ * Not needed in normal use and not part of the method: switches that force a
+ * launch variant the library would not pick by itself (so that tests and tuning
+ * runs can reach every variant), and a view of the host-side launch plan.  The
+ * library reads no environment variables.
+ *
+ * sq_debug_set_option   process-wide; takes effect from the next call on.
+ *                       value 0 always means "the library decides".
+ *                       SQ_ERR_SHAPE for an unknown option.
+ */
+typedef enum {
+    SQ_DEBUG_GEMM_LAUNCH_SHAPE = 0,     /* 1 + case number of sq_w4a4_gemm's dispatcher; shapes the
+                                           case does not fit fall back to the normal choice      */
+    SQ_DEBUG_ROTQ_RING = 1,             /* 2 or 3: LDS tiles per token slot of the rotate kernel     */
+    SQ_DEBUG_ROTQ_R1_IN_REGISTERS = 2,  /* 1: never keep R1's operand fragments in LDS              */
+    SQ_DEBUG_ROTQ_PLAIN_KERNEL = 3,     /* 1: every shape takes the plain-FMA rotate kernel         */
+    SQ_DEBUG_DECODE_SPIN_LIMIT = 4,     /* polls after which a waiting workgroup of sq_decode_layer
+                                           gives up (default 2^20, about a second)                */
+    SQ_DEBUG_OPTION_COUNT = 5
+} sq_debug_option;
+sq_status sq_debug_set_option(sq_debug_option option, int32_t value);
+
+/*
+ * sq_debug_rotq_plan -- how the host regroups a Givens list (Sec. 4.1 / 4.2;
+ * list order is part of the definition) for the matrix-core rotate kernel:
+ * touched channels get slots, distinct values of channel % n2 get q-slots, and
+ * pair p goes to level 1 + the latest level of an earlier pair sharing a
+ * channel with it, so that the pairs of a level are disjoint and level order
+ * equals list order.  Host only.  Every out array has room for
+ * 2 * SQ_MAX_GIVENS entries (pair_* are indexed by list position).  Returns the
+ * number of levels, or -1 if P is out of range or the list cannot be planned.
+ */
+int32_t sq_debug_rotq_plan(const int32_t *giv_i, const int32_t *giv_j, int32_t P, int32_t n2,
+                           int32_t *n_slots, int32_t *n_qslots, int32_t *slot_chan,
+                           int32_t *slot_qslot, int32_t *qslot_q, int32_t *pair_slot_i,
+                           int32_t *pair_slot_j, int32_t *pair_level);
 
 #ifdef __cplusplus
 }

@@ -6,13 +6,16 @@ offline weight path and the closed-form construction of the rotation.
 ``synth`` draws the seeded synthetic layers used by tests and the benchmark.
 """
 from . import synth  # noqa: F401
+from . import binding  # noqa: F401
 from .binding import (  # noqa: F401
     SQError,
     library_path,
     sq_build_rotation,
+    sq_debug_set_option,
     sq_build_rotation_workspace_bytes,
     sq_decode_layer,
     sq_decode_layer_static,
+    sq_decode_layer_status,
     sq_decode_layer_workspace_bytes,
     sq_kron_factor,
     sq_prepare_rotation,

@@ -67,6 +67,8 @@ def _load():
             C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
             C.c_void_p, C.c_int32, C.c_int32,
             C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p]
+        lib.sq_decode_layer_status.restype = C.c_int
+        lib.sq_decode_layer_status.argtypes = [C.c_void_p, C.c_void_p]
         lib.sq_w4a4_gemm.restype = C.c_int
         lib.sq_w4a4_gemm.argtypes = [
             C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
@@ -78,6 +80,8 @@ def _load():
             C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
             C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.sq_debug_set_option.restype = C.c_int
+        lib.sq_debug_set_option.argtypes = [C.c_int, C.c_int32]
         lib.sq_kron_factor.restype = C.c_int
         lib.sq_kron_factor.argtypes = [C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         lib.sq_build_rotation.restype = C.c_int
@@ -94,6 +98,19 @@ def _load():
 
 def sq_status_string(code: int) -> str:
     return _load().sq_status_string(int(code)).decode()
+
+
+# sq_debug_option of singlequant.h
+SQ_DEBUG_GEMM_LAUNCH_SHAPE = 0
+SQ_DEBUG_ROTQ_RING = 1
+SQ_DEBUG_ROTQ_R1_IN_REGISTERS = 2
+SQ_DEBUG_ROTQ_PLAIN_KERNEL = 3
+SQ_DEBUG_DECODE_SPIN_LIMIT = 4
+
+
+def sq_debug_set_option(option: int, value: int) -> None:
+    """Force a launch variant (test and tuning aid; 0 = the library decides)."""
+    _check(_load().sq_debug_set_option(int(option), int(value)))
 
 
 def _check(code: int) -> None:
@@ -206,6 +223,12 @@ def sq_decode_layer(X, giv_i, giv_j, giv_theta, prepared, n1, n2, Qw, sw, Y, wor
         _dev_ptr(prepared), int(n1), int(n2),
         _dev_ptr(Qw), _dev_ptr(sw), N, _dev_ptr(Y), ldy, _dev_ptr(workspace), _stream_handle(stream))
     _check(code)
+
+
+def sq_decode_layer_status(workspace=None, stream=None) -> None:
+    """Waits for the stream, then raises SQError (status 6) if a workgroup of any sq_decode_layer
+    call on this workspace (None: the array inside the library) gave up its wait; clears the word."""
+    _check(_load().sq_decode_layer_status(_dev_ptr(workspace), _stream_handle(stream)))
 
 
 def sq_decode_layer_static(X, giv_i, giv_j, giv_theta, prepared, n1, n2, Qw, sw, Y, stream=None) -> None:

@@ -34,6 +34,9 @@ struct GivensList {
     float s[SQ_MAX_GIVENS];
 };
 
+// Current value of a debug option of singlequant.h (0 = the library decides).
+int32_t debug_option(sq_debug_option option);
+
 // Workgroup id -> logical work item such that each XCD (which owns one L2) receives a contiguous
 // range of logical ids.  Hardware deals workgroup i to XCD i % 8.
 __device__ __forceinline__ int xcd_contiguous_id(int wg, int nwg)

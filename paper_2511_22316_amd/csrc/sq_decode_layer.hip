@@ -15,16 +15,19 @@
 // that the blocks with the lowest indices are not dispatched after the others (every block of a
 // decode-sized launch is resident at once anyway: two per CU, 512 on the chip).
 // Device-wide atomics and cache maintenance are expensive on this part (eight L2s): a ticket per
-// block instead of the block index cost 7 us, an acquire fence in every block 11 us, an exit
-// count with acquire-release ordering 16 us of a 34 us layer; what is left is one release per
-// rotating block, relaxed polls, and one relaxed add per block that nobody waits for.
+// block instead of the block index cost 7 us and an exit count with acquire-release ordering 16 us
+// of a 34 us layer, and even a single acquire load per block behind the last poll (one cache
+// invalidation per block) 1.7 us.  What is left: one release per rotating block (its stores are
+// written back before its count becomes visible), relaxed polls, reads of the codes and steps by
+// agent-scope coherent loads behind the poll and the block barrier (they go to the point where the
+// written-back data is, so no invalidation is needed), and one relaxed add per block that nobody
+// waits for.
 // The launch ramp of a second kernel, the drain between the two and the first weight latency are
 // what is saved; the codes still go through memory (32 KB for 8 tokens of 8192 channels).
 #include "sq_rotq_body.h"
 
 #include "singlequant.h"
 
-#include <stdlib.h>
 
 namespace sq {
 
@@ -42,7 +45,7 @@ __device__ __forceinline__ void widen_codes(const uint4 w, v4i &first, v4i &seco
 template <int N1, int N2, int QS_MAX, int FN>
 __global__ __launch_bounds__(256, 2) void decode_layer_kernel(
     const __half *__restrict__ X, int64_t ldx, int T, RotqPlan plan, const __half *__restrict__ F1,
-    const __half *__restrict__ F2, uint8_t *__restrict__ Qx, float *__restrict__ sx, int *__restrict__ ctr,
+    const __half *__restrict__ F2, uint8_t *Qx, float *sx, int *__restrict__ ctr,
     const uint8_t *__restrict__ Qw, const float *__restrict__ sw, int N, __half *__restrict__ Y, int64_t ldy,
     int lds_main, int spin_limit)
 {
@@ -68,7 +71,13 @@ __global__ __launch_bounds__(256, 2) void decode_layer_kernel(
     // ---- decode-shaped GEMM on channels [col0, col0 + BN) ----------------------------------------
     const int lane = tid & (kWave - 1), wave = tid / kWave, l32 = lane & 31, g = lane >> 5;
     const int col0 = block * BN;
-    const uint8_t *a_ptr = Qx + (int64_t)min(l32, T - 1) * Kb + g * 64;   // rows past the end: never stored
+    // The codes and steps were written by other workgroups of this launch, on other XCDs.  They
+    // are read with agent-scope coherent loads (the sc1 form, which is what a relaxed agent-scope
+    // atomic load compiles to, here 16 bytes wide through a buffer descriptor): such a load
+    // cannot be served by a stale line of this XCD's caches, so nothing has to be invalidated.
+    constexpr int kAgentCoherent = 16;                                    // cache-policy bit sc1
+    const __amdgpu_buffer_rsrc_t qx_rsrc = __builtin_amdgcn_make_buffer_rsrc(Qx, 0, T * Kb, 0x00020000);
+    const int a_off = min(l32, T - 1) * Kb + g * 64;                      // rows past the end: never stored
     const uint8_t *b_ptr[FN];
 #pragma unroll
     for (int j = 0; j < FN; ++j) b_ptr[j] = Qw + (int64_t)min(col0 + 32 * j + l32, N - 1) * Kb + g * 64;
@@ -90,7 +99,8 @@ __global__ __launch_bounds__(256, 2) void decode_layer_kernel(
 #define SQ_DECODE_FETCH_A(BUF, SL)                                                                   \
     do {                                                                                             \
         _Pragma("unroll") for (int c = 0; c < 4; ++c)                                                \
-            ra[BUF][c] = *reinterpret_cast<const uint4 *>(a_ptr + (SL) * SLICE + 16 * c);            \
+            ra[BUF][c] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(            \
+                qx_rsrc, a_off + (SL) * SLICE + 16 * c, 0, kAgentCoherent));                        \
     } while (0)
 #define SQ_DECODE_MULTIPLY(BUF)                                                                      \
     do {                                                                                             \
@@ -127,9 +137,6 @@ __global__ __launch_bounds__(256, 2) void decode_layer_kernel(
     }
     __syncthreads();
     const bool gave_up = note[0] != 0;
-    // No cache invalidation here (it costs every workgroup about 10 us of this launch): codes and
-    // steps are read for the first time in this launch, after the writers' release, and no cache
-    // keeps lines from an earlier launch across the launch boundary.
 
     if (!gave_up && sl < slices) SQ_DECODE_FETCH_A(0, sl);
     // This block no longer looks at the count.  No value comes back and the add is queued behind the
@@ -167,7 +174,10 @@ __global__ __launch_bounds__(256, 2) void decode_layer_kernel(
 #pragma unroll
             for (int w = 0; w < NW; ++w) sum += red[((w * FN + j) * 16 + e) * kWave + ln];
             const int t = 8 * (e / 4) + 4 * (ln >> 5) + (e % 4), n = col0 + 32 * j + (ln & 31);
-            if (t < T && n < N) Y[(int64_t)t * ldy + n] = __float2half_rn((float)sum * (sx[t] * 0.00390625f) * sw[n]);
+            if (t < T && n < N) {
+                const float sxt = __hip_atomic_load(&sx[t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                Y[(int64_t)t * ldy + n] = __float2half_rn((float)sum * (sxt * 0.00390625f) * sw[n]);
+            }
         }
     }
 #undef SQ_DECODE_FETCH_A
@@ -208,10 +218,11 @@ sq_status launch_decode_layer(const __half *X, int64_t ldx, int T, const RotqPla
     const int tiles = (N + BN - 1) / BN, groups = (T + S::TPP - 1) / S::TPP;
     // every token group needs a block
     if (tiles < groups) return SQ_ERR_SHAPE;
-    // about a second of polling before a workgroup gives up; SQ_DECODE_SPIN_LIMIT sets another bound
-    // (test aid: the give-up path with a workspace whose "done" counter can never be reached)
-    const char *env = getenv("SQ_DECODE_SPIN_LIMIT");
-    const int spin_limit = env ? atoi(env) : (1 << 20);
+    // about a second of polling before a workgroup gives up; the debug option SQ_DEBUG_DECODE_SPIN_LIMIT
+    // sets another bound (test aid: the give-up path with a workspace whose "done" counter can never
+    // be reached)
+    const int option = debug_option(SQ_DEBUG_DECODE_SPIN_LIMIT);
+    const int spin_limit = option > 0 ? option : (1 << 20);
     hipLaunchKernelGGL(kernel, dim3((unsigned)tiles), dim3(256), lds, st, X, ldx, T, plan, F1, F2, Qx, sx, ctr, Qw, sw,
                        N, Y, ldy, lds_main, spin_limit);
     return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;

@@ -4,7 +4,6 @@
 #include "sq_rotq_plan.h"
 
 #include <math.h>
-#include <stdlib.h>
 #include <string.h>
 
 namespace sq {
@@ -167,11 +166,10 @@ static bool build_rotq_plan(const GivensList &giv, int n2, RotqPlan &plan)
 
 }  // namespace sq
 
-// Test hook, not part of the public header: the launch plan the matrix-core kernel would get for a
-// Givens list, flattened into int32 arrays so that host-only tests can check the regrouping.
-// Returns the number of levels, or -1 if the list cannot be planned.  Every out array has room
-// for 2 * SQ_MAX_GIVENS entries.
-extern "C" int32_t sq_internal_rotq_plan(const int32_t *giv_i, const int32_t *giv_j, int32_t P, int32_t n2,
+// The launch plan the matrix-core kernel would get for a Givens list, flattened into int32 arrays
+// so that host-only tests can check the regrouping (declared in the debug section of
+// singlequant.h).  Returns the number of levels, or -1 if the list cannot be planned.
+extern "C" int32_t sq_debug_rotq_plan(const int32_t *giv_i, const int32_t *giv_j, int32_t P, int32_t n2,
                                          int32_t *n_slots, int32_t *n_qslots, int32_t *slot_chan,
                                          int32_t *slot_qslot, int32_t *qslot_q, int32_t *pair_slot_i,
                                          int32_t *pair_slot_j, int32_t *pair_level)
@@ -344,8 +342,8 @@ static sq_status rotate_quantize_any(const void *X, int64_t T, int32_t K, int64_
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     // matrix-core kernel for the shapes it covers (n2 in {32, 64, 128}, n1 <= 128); the plain-FMA
-    // kernel takes every other shape.  SQ_ROTQ_GENERIC=1 forces the latter (tuning aid).
-    static const bool force_generic = [] { const char *e = getenv("SQ_ROTQ_GENERIC"); return e && e[0] == '1'; }();
+    // kernel takes every other shape.  The debug option SQ_DEBUG_ROTQ_PLAIN_KERNEL forces the latter.
+    const bool force_generic = sq::debug_option(SQ_DEBUG_ROTQ_PLAIN_KERNEL) != 0;
     if (!force_generic && prep.plan_ok) {
         sq_status status = SQ_OK;
         const bool prepared = frag1 != nullptr;
@@ -486,4 +484,19 @@ extern "C" sq_status sq_decode_layer_static(const void *X, int64_t T, int32_t K,
 {
     return decode_layer_any(X, T, K, ldx, giv_i, giv_j, giv_theta, P, prepared, n1, n2, Qw, sw, N, Y, ldy, nullptr,
                             true, stream);
+}
+
+extern "C" sq_status sq_decode_layer_status(void *workspace, void *stream)
+{
+    if (((uintptr_t)workspace & 255) != 0) return SQ_ERR_ALIGN;
+    char *ws = static_cast<char *>(workspace ? workspace : sq::decode_scratch_address());
+    if (!ws) return SQ_ERR_LAUNCH;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (hipStreamSynchronize(st) != hipSuccess) return SQ_ERR_LAUNCH;
+    int32_t word = 0;
+    if (hipMemcpy(&word, ws + 12, sizeof(word), hipMemcpyDeviceToHost) != hipSuccess) return SQ_ERR_LAUNCH;
+    if (word == 0) return SQ_OK;
+    word = 0;
+    if (hipMemcpy(ws + 12, &word, sizeof(word), hipMemcpyHostToDevice) != hipSuccess) return SQ_ERR_LAUNCH;
+    return SQ_ERR_TIMEOUT;
 }

@@ -28,8 +28,6 @@
 // The first wave of a token does this for the next token.
 #include "sq_rotq_body.h"
 
-#include <stdlib.h>
-
 namespace sq {
 
 // QS_MAX: repair steps of 16 q-slots each the kernel holds rotation rows for (4 or 8).
@@ -77,8 +75,8 @@ static sq_status launch_rotq_mfma_qs(const __half *X, int64_t ldx, int T, const 
     if constexpr (N1 == 64 && N2 == 64) {
         // 168 registers: three workgroups fit a CU if the ring has two tiles.  Measured faster than
         // the ring of three at two workgroups per CU from 4096 tokens on (4 % there, 12 % at 32768),
-        // 3 % slower below.  SQ_ROTQ_RING=2 or 3 forces one of them (tuning aid).
-        static const int forced = [] { const char *e = getenv("SQ_ROTQ_RING"); return e ? atoi(e) : 0; }();
+        // 3 % slower below.  The debug option SQ_DEBUG_ROTQ_RING (2 or 3) forces one of them.
+        const int forced = debug_option(SQ_DEBUG_ROTQ_RING);
         // With prepared operands the prologue is shorter and the third workgroup pays earlier: in a
         // stream of such launches T = 2048 10.0 -> 9.6 us, 3072 14.3 -> 12.6, 4096 16.7 -> 14.1.  At
         // 2048 the layer (this launch behind a GEMM) was 0.35 us slower with it, so it starts at 3072.
@@ -88,9 +86,9 @@ static sq_status launch_rotq_mfma_qs(const __half *X, int64_t ldx, int T, const 
     if constexpr (MB == 3 && QS_MAX == 4) {       // more than 64 q-slots never leave room for two workgroups
         // With R1 in registers three row blocks need more than 256 of them: one workgroup per CU.
         // With the shared copy in LDS and a ring of two tiles, two fit if the list's side tiles are
-        // small enough.  SQ_ROTQ_R1=reg forces the register variant (tuning aid).
+        // small enough.  The debug option SQ_DEBUG_ROTQ_R1_IN_REGISTERS forces the register variant.
         using S2 = RotqShape<N1, N2, 2, true>;
-        static const bool force_reg = [] { const char *e = getenv("SQ_ROTQ_R1"); return e && e[0] == 'r'; }();
+        const bool force_reg = debug_option(SQ_DEBUG_ROTQ_R1_IN_REGISTERS) != 0;
         if (!force_reg && 2 * S2::lds_bytes((plan.n_qslots + 15) / 16) <= 160 * 1024)
             return launch_rotq_mfma_ring<N1, N2, QS_MAX, 2, 2, true>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st, prepared);
     }

@@ -12,7 +12,6 @@
 // does not see.
 #include "sq_common.h"
 
-#include <stdlib.h>
 
 namespace sq {
 
@@ -710,8 +709,9 @@ extern "C" sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T,
     // Kernel choice, from few tokens to many.  The two large tile shapes run eight waves per CU
     // (two per SIMD): the VALU work of widening nibbles issues nearly twice as fast from two waves
     // as from one.  256x256 tiles (64x128 per wave: fewer VALU ops per MFMA) or 128x256 tiles,
-    // whichever needs less time for its rounds over the CUs.  SQ_GEMM_TILE=0..15 overrides the choice (tuning aid).
-    static const int forced = [] { const char *e = getenv("SQ_GEMM_TILE"); return e ? atoi(e) : -1; }();
+    // whichever needs less time for its rounds over the CUs.  The debug option SQ_DEBUG_GEMM_LAUNCH_SHAPE (case number
+    // below plus one) overrides the choice.
+    const int forced = sq::debug_option(SQ_DEBUG_GEMM_LAUNCH_SHAPE) - 1;
     const int Ti = (int)T;
     int choice = forced;
     // At most 64 tokens: one pass over the weights by the decode-shaped kernel; its launch shape

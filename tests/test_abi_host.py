@@ -198,6 +198,17 @@ def test_prepare_weights_argument_errors(lib):
     assert _pw(lib, N=0) == 0                       # nothing to do, nothing enqueued
 
 
+def test_debug_options(lib):
+    lib.sq_debug_set_option.restype = C.c_int
+    lib.sq_debug_set_option.argtypes = [C.c_int, C.c_int32]
+    assert lib.sq_debug_set_option(5, 1) == 2 and lib.sq_debug_set_option(-1, 1) == 2     # unknown options
+    for option in range(5):
+        assert lib.sq_debug_set_option(option, 0) == 0
+    # a forced shape never changes what is checked before the launch
+    assert lib.sq_debug_set_option(0, 5) == 0 and _gemm(lib, K=48) == 2 and _gemm(lib, T=0) == 0
+    assert lib.sq_debug_set_option(0, 0) == 0
+
+
 # ------------------------------------------------------------------ launch plan of the Givens list -----
 
 def _plan(lib, gi, gj, n2):
@@ -206,7 +217,7 @@ def _plan(lib, gi, gj, n2):
     ns, nq = C.c_int32(), C.c_int32()
     arr = lambda: np.full(128, -1, np.int32)
     chan, qslot, qq, si, sj, lv = arr(), arr(), arr(), arr(), arr(), arr()
-    fn = lib.sq_internal_rotq_plan
+    fn = lib.sq_debug_rotq_plan
     fn.restype = C.c_int32
     fn.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p] + [C.c_void_p] * 6
     levels = fn(gi.ctypes.data, gj.ctypes.data, P, n2, C.addressof(ns), C.addressof(nq), chan.ctypes.data,

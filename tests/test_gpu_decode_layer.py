@@ -4,7 +4,6 @@ CPU oracle of the whole layer.
 
 The weights here are random codes and random steps (the GEMM is exact on any codes); the
 activations, lists and rotation factors are the seeded layers of the other tests."""
-import os
 
 import numpy as np
 import pytest
@@ -159,17 +158,25 @@ def test_decode_layer_gives_up_instead_of_waiting_forever():
     lay = Layer(L, N, T)
     X = L.X[:T]
     want = lay.two_calls(X)
-    os.environ["SQ_DECODE_SPIN_LIMIT"] = "40"
+    import paper_2511_22316_amd as sq
+    sq.sq_debug_set_option(sq.binding.SQ_DEBUG_DECODE_SPIN_LIMIT, 40)
     try:
         lay.ws[:16] = torch.from_numpy(np.array([-5, 0, 0, 0], np.int32).view(np.uint8)).cuda()
         Y = lay.one_launch(X)
         assert torch.all(Y == -5.0)
         assert list(lay.counters()) == [0, 0, 0, 1]
+        # the status call reports it once and clears the word
+        with pytest.raises(sq.SQError) as e:
+            sq.sq_decode_layer_status(lay.ws)
+        assert e.value.code == 6
+        sq.sq_decode_layer_status(lay.ws)
+        assert list(lay.counters()) == [0, 0, 0, 0]
     finally:
-        del os.environ["SQ_DECODE_SPIN_LIMIT"]
+        sq.sq_debug_set_option(sq.binding.SQ_DEBUG_DECODE_SPIN_LIMIT, 0)
     lay.ws[:16] = 0
     assert torch.equal(lay.one_launch(X), want)
     assert list(lay.counters()) == [0, 0, 0, 0]
+    sq.sq_decode_layer_status(lay.ws)
 
 
 def test_decode_layer_captured_in_a_graph_replays_correctly():

@@ -232,31 +232,23 @@ def test_rotate_quantize_64x64_many_tokens(oracle, T, with_list):
 
 
 def test_rotate_quantize_generic_kernel_on_benchmark_shape(oracle):
-    """The generic kernel, forced on a shape the matrix-core kernel normally takes, must agree with
-    the oracle as well (it is the fallback for every shape without an instantiation)."""
-    print("case rotate_quantize generic kernel forced", flush=True)
-    import subprocess
-    import sys
-    import textwrap
-    # the switch is read once per process, so the forced run needs a process of its own
-    code = textwrap.dedent("""
-        import sys, numpy as np
-        sys.path[:0] = [%r, %r]
-        import oracle
-        from paper_2511_22316_amd import synth
-        from parity_util import run_rotate_quantize, check_rotation, check_codes
-        oracle.build()
-        L = synth.layer(synth.CONFIGS["attn_proj"], 20)
+    """The plain-FMA kernel, forced on a shape the matrix-core kernel normally takes, must agree
+    with the oracle as well (it is the fallback for every shape without an instantiation)."""
+    print("case rotate_quantize plain kernel forced", flush=True)
+    import paper_2511_22316_amd as sq
+    L = synth.layer(synth.CONFIGS["attn_proj"], 20)
+    sq.sq_debug_set_option(sq.binding.SQ_DEBUG_ROTQ_PLAIN_KERNEL, 1)
+    try:
         Qg, sg, xg = run_rotate_quantize(L)
-        xr = oracle.rotate(L.X, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)
-        Qo, so = oracle.quantize_rows(xr)
-        check_rotation(xg, xr)
-        check_codes(Qg, sg, Qo, so)
-        print("generic ok")
-    """) % (ROOT, os.path.join(ROOT, "tests"))
-    env = dict(os.environ, SQ_ROTQ_GENERIC="1")
-    r = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=110, cwd=ROOT)
-    assert r.returncode == 0 and "generic ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
+    finally:
+        sq.sq_debug_set_option(sq.binding.SQ_DEBUG_ROTQ_PLAIN_KERNEL, 0)
+    xo, Qo, so = _oracle_rq(oracle, L)
+    check_rotation(xg, xo)
+    check_codes(Qg, sg, Qo, so)
+    # the two kernels round their sums differently, so the forced run is not the normal one
+    _, _, xm = run_rotate_quantize(L)
+    assert not np.array_equal(xm, xg)
+    check_rotation(xm, xo)
 
 
 def test_rotate_quantize_identity_rotation_is_exact(oracle):

@@ -64,6 +64,7 @@ def test_static_workspace_entry_matches_the_workspace_entry():
     torch.cuda.synchronize()
     for k, c in enumerate(cases):
         assert torch.equal(c["got"], c["want"]), f"second round, call {k} differs from sq_decode_layer"
+    sq.sq_decode_layer_status(None)          # no workgroup of any of these calls gave up its wait
 
 
 def test_static_workspace_entry_rejects_what_does_not_fit():
