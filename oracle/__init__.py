@@ -64,6 +64,11 @@ def _load():
                                  C.c_void_p, C.c_int64, C.c_void_p]
         lib.sqo_gemm_acc_at.restype = C.c_int64
         lib.sqo_gemm_acc_at.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int64, C.c_int64]
+        lib.sqo_round_rows_to_half.restype = None
+        lib.sqo_round_rows_to_half.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_int64]
+        lib.sqo_gemm_w4a16.restype = C.c_int
+        lib.sqo_gemm_w4a16.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int64, C.c_void_p, C.c_void_p, C.c_int,
+                                       C.c_void_p, C.c_int64, C.c_void_p]
         lib.sqo_kron_factor.restype = None
         lib.sqo_kron_factor.argtypes = [C.c_int64, C.c_void_p, C.c_void_p]
         lib.sqo_num_threads.restype = C.c_int
@@ -206,6 +211,37 @@ def prepare_weights(Wt_f16, giv_i, giv_j, giv_theta, R1, R2):
     Flat(W~_R) = W^T R, then round-to-nearest 4-bit per output channel (Table 1, 'RTN').
     Wt: [N, K] float16 (= W transposed).  -> (Qw [N, K/2], sw [N])."""
     return quantize_rows(rotate(Wt_f16, giv_i, giv_j, giv_theta, R1, R2))
+
+
+# ------------------------------------------- weight-only variant (Table B.3) ---
+
+def rotate_f16(X_f16, giv_i, giv_j, giv_theta, R1, R2) -> np.ndarray:
+    """The 16-bit activations of the weight-only setting (W4A16): the rotated rows X R of
+    Eq. 1, each entry rounded once from fp64 to fp16.  -> [T, K] float16."""
+    xr = rotate(X_f16, giv_i, giv_j, giv_theta, R1, R2)
+    T, K = xr.shape
+    out = np.empty((T, K), np.uint16)
+    _load().sqo_round_rows_to_half(_ptr(xr), T, K, _ptr(out), K)
+    return out.view(np.float16)
+
+
+def gemm_w4a16(Xh, Qw, sw, want_abs_sum=False):
+    """Y = fp16(sw[n] * sum_k x[t,k] qw[n,k]) with fp16 activations and 4-bit weight codes; sums in
+    fp64.  -> Y float16 [T, N] (and sw[n] * sum_k |x qw| as float64 [T, N] if asked)."""
+    Xh = np.ascontiguousarray(Xh)
+    assert Xh.dtype == np.float16 and Xh.ndim == 2
+    Qw = _c(Qw, np.uint8)
+    sw = _c(sw, np.float32)
+    T, K = Xh.shape
+    N = Qw.shape[0]
+    assert Qw.shape[1] * 2 == K and sw.size == N
+    Y = np.empty((T, N), np.uint16)
+    m = np.empty((T, N), np.float64) if want_abs_sum else None
+    rc = _load().sqo_gemm_w4a16(_ptr(Xh.view(np.uint16)), T, K, K, _ptr(Qw), _ptr(sw), N, _ptr(Y), N,
+                                None if m is None else _ptr(m))
+    if rc != 0:
+        raise ValueError("sqo_gemm_w4a16: bad argument")
+    return (Y.view(np.float16), m) if want_abs_sum else Y.view(np.float16)
 
 
 # ------------------------------------------------------------------ Alg. 1 ---

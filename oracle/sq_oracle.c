@@ -307,6 +307,46 @@ int64_t sqo_gemm_acc_at(const uint8_t *Qx, const uint8_t *Qw, int K,
     return a;
 }
 
+/* ------------------------------- weight-only variant (W4A16, Table B.3) ---- */
+
+/* Round T rows of K doubles to fp16 (nearest even): the 16-bit activations of
+   the weight-only setting are the rotated rows X R of Eq. 1 kept in fp16. */
+void sqo_round_rows_to_half(const double *Xrot, int64_t T, int K,
+                            uint16_t *Xh, int64_t ldo)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t)
+        for (int k = 0; k < K; ++k)
+            Xh[t * ldo + k] = sqo_double_to_half(Xrot[t * (int64_t)K + k]);
+}
+
+/* Y[t,n] = fp16( sw[n] * sum_k x[t,k] qw[n,k] ): Eq. 1 with only the weight
+   operand quantized (4-bit codes and per-output-channel steps, Sec. 3.2),
+   the activations fp16 values read as exact reals; sums in fp64, one rounding
+   to fp16 at the end.  abs_sum (may be NULL) receives sw[n] * sum_k |x qw|,
+   the size that bounds the error of any other summation order. */
+int sqo_gemm_w4a16(const uint16_t *Xh, int64_t T, int K, int64_t ldx,
+                   const uint8_t *Qw, const float *sw, int N,
+                   uint16_t *Y, int64_t ldy, double *abs_sum)
+{
+    if (K <= 0 || (K & 1) || T < 0 || N < 0 || ldy < N || ldx < K) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        for (int n = 0; n < N; ++n) {
+            const uint8_t *qw = Qw + (int64_t)n * (K / 2);
+            double a = 0.0, m = 0.0;
+            for (int k = 0; k < K; ++k) {
+                double term = sqo_half_to_double(Xh[t * ldx + k]) * (double)code_at(qw, k);
+                a += term;
+                m += fabs(term);
+            }
+            Y[t * ldy + n] = sqo_double_to_half(a * (double)sw[n]);
+            if (abs_sum) abs_sum[t * (int64_t)N + n] = m * (double)sw[n];
+        }
+    }
+    return 0;
+}
+
 /* --------------------------------------------------------- Alg. 1 -------- */
 
 /* n2 = the power of two dividing n that is closest to sqrt(n) (first found

@@ -331,3 +331,69 @@ def test_kron_factor_values(oracle):
     assert oracle.kron_factor(5120) == (80, 64)
     assert oracle.kron_factor(77) == (77, 1)
     assert oracle.kron_factor(1) == (1, 1)
+
+
+# ------------------------------------------------- weight-only variant (W4A16, Table B.3) --
+
+def test_rotate_f16_is_the_rotation_rounded_once(oracle):
+    """The 16-bit activations are the fp64 rotated rows rounded to the nearest fp16: checked
+    against numpy's own float64 -> float16 conversion (correctly rounded, ties to even)."""
+    L = synth.layer(synth.CONFIGS["tiny"], 5)
+    xr = oracle.rotate(L.X, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)
+    xh = oracle.rotate_f16(L.X, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)
+    assert xh.dtype == np.float16 and np.array_equal(xh, xr.astype(np.float16))
+    # an exact tie between two fp16 neighbours goes to the even one
+    lib = oracle._load()
+    out = np.empty((1, 2), np.uint16)
+    ties = np.array([[1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11]])
+    lib.sqo_round_rows_to_half(ties.ctypes.data, 1, 2, out.ctypes.data, 2)
+    assert list(out.view(np.float16)[0]) == [1.0, 1.0 + 2.0 ** -9]
+
+
+def test_gemm_w4a16_against_brute_force(oracle):
+    """Y = fp16(sw * sum_k x q) against a plain numpy evaluation on decoded codes (code -8
+    included), non-square so that a transposed operand cannot hide; Eq. 1 with exact activations
+    reproduces X W' for the dequantized weights W'."""
+    g = np.random.default_rng(8)
+    T, K, N = 5, 64, 7
+    X = (g.standard_normal((T, K)) * 3).astype(np.float16)
+    Qw = synth.random_codes(N, K, 9)
+    sw = g.uniform(1e-3, 1e-2, N).astype(np.float32)
+    Y, m = oracle.gemm_w4a16(X, Qw, sw, want_abs_sum=True)
+    lo = (Qw & 0xF).astype(np.int64)
+    hi = (Qw >> 4).astype(np.int64)
+    q = np.empty((N, K), np.int64)
+    q[:, 0::2] = np.where(lo >= 8, lo - 16, lo)
+    q[:, 1::2] = np.where(hi >= 8, hi - 16, hi)
+    assert q.min() == -8 and q.max() == 7
+    Wd = q.astype(np.float64) * sw.astype(np.float64)[:, None]           # dequantized W^T
+    want = X.astype(np.float64) @ Wd.T
+    got = Y.astype(np.float64)
+    assert np.all(np.abs(got - want) <= 2.0 ** -11 * np.abs(want) + 1e-300)     # one rounding to fp16
+    assert np.allclose(m, np.abs(X.astype(np.float64)) @ np.abs(Wd).T, rtol=1e-12)
+    # one hand-worked element: x = (1.5, -2), codes (-8, 7), step 0.5 -> 0.5 (1.5 * -8 + -2 * 7) = -13
+    y1 = oracle.gemm_w4a16(np.array([[1.5, -2.0]], np.float16), np.array([[0x78]], np.uint8), np.array([0.5], np.float32))
+    assert y1[0, 0] == np.float16(-13.0)
+
+
+def test_weight_only_pipeline_reproduces_xw(oracle):
+    """Eq. 1 with only the weights quantized: (X R)(R^T W) with 4-bit R^T W stays close to X W,
+    and the only error is the weight quantizer's (the rotation is orthogonal): with the step
+    halved (codes from a finer grid emulated by scaling W) the error halves."""
+    cfg = synth.CONFIGS["tiny"]
+    L = synth.layer(cfg)
+    Wt = synth.weights_t(cfg, 64)
+    ref = L.X.astype(np.float64) @ Wt.astype(np.float64).T
+    xh = oracle.rotate_f16(L.X, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)
+    Qw, sw = oracle.prepare_weights(Wt, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)
+    Y = oracle.gemm_w4a16(xh, Qw, sw).astype(np.float64)
+    err = np.linalg.norm(Y - ref) / np.linalg.norm(ref)
+    assert err < 0.2
+    # the same weights through the unquantized rotated product: (X R)(R^T W) = X W up to the fp16
+    # roundings of R1, R2 and of X R (R is orthogonal only to 1e-3 after its fp16 rounding)
+    wr = oracle.rotate(Wt, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)
+    exact = xh.astype(np.float64) @ wr.T
+    assert np.linalg.norm(exact - ref) / np.linalg.norm(ref) < 5e-3
+    # and the quantized product differs from that one by the weight rounding only: |dW| <= s/2
+    bound = np.abs(xh.astype(np.float64)) @ np.tile((sw.astype(np.float64) / 2)[None, :], (cfg.K, 1))
+    assert np.all(np.abs(Y - exact) <= bound * (1 + 1e-6) + 2.0 ** -10 * np.abs(exact))
