@@ -291,6 +291,39 @@ def measure_layer(cfg, torch, sq, synth, steps, warmup):
     return out
 
 
+FP16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense fp16 matrix peak
+
+
+def measure_weight_only(cfg, torch, sq, synth, steps, warmup):
+    """The weight-only setting (W4A16, the paper's appendix): sq_rotate_fp16 then sq_w4a16_gemm on
+    the same layer, same ring of buffer sets.  Rotation: HBM-bound, 2 T K bytes in and 2 T K out;
+    GEMM: 2 T K N flops on the fp16 matrix cores."""
+    B = LayerBuffers(cfg, torch, sq, synth)
+    T, K, N = cfg.T, cfg.K, cfg.N
+    L = B.L
+    Xr = [torch.empty((T, K), dtype=torch.float16, device=B.Y[0].device) for _ in range(B.sets)]
+    rot = lambda i: sq.sq_rotate_fp16(B.X[i], L.giv_i, L.giv_j, L.giv_theta, B.R1, B.R2, Xr[i])
+    mm = lambda i: sq.sq_w4a16_gemm(Xr[i], B.Qw[i], B.sw[i], B.Y[i])
+
+    def both(i):
+        rot(i)
+        mm(i)
+    settle(torch, both, B.sets)
+    layer = timed(torch, both, B.sets, steps, warmup)
+    r = kernel_time(torch, rot, B.sets, steps, warmup)
+    g = kernel_time(torch, mm, B.sets, steps, warmup)
+    flops = 2.0 * T * K * N
+    out = {"workload": cfg.name, "layer_us": layer["median_us"], "layer_us_min": layer["min_us"],
+           "rotate_fp16_us": r["mean_us"], "rotate_fp16_GBps": 4.0 * T * K / (r["mean_us"] * 1e-6) / 1e9,
+           "rotate_fp16_frac_of_hbm_peak": 4.0 * T * K / (r["mean_us"] * 1e-6) / 1e9 / HBM_PEAK_GBPS,
+           "gemm_us": g["mean_us"], "gemm_TFLOPS": flops / (g["mean_us"] * 1e-6) / 1e12,
+           "gemm_frac_of_fp16_peak": flops / (g["mean_us"] * 1e-6) / 1e12 / FP16_MFMA_PEAK_TFLOPS,
+           "ring_sets": B.sets}
+    del B, Xr
+    torch.cuda.empty_cache()
+    return out
+
+
 def measure_build_rotation(cfg, torch, sq, synth, steps, warmup):
     """The offline constructor (sq_build_rotation) on the workload's activations as calibration
     batch.  Not part of the layer time.  Its one large kernel reads X once (2*T*K bytes); the rest
@@ -483,6 +516,9 @@ def main() -> int:
     }
     if not args.no_extra and cfg.n2 & (cfg.n2 - 1) == 0:
         result["build_rotation"] = measure_build_rotation(cfg, torch, sq, synth, max(10, args.steps // 4),
+                                                          max(2, args.warmup // 4))
+    if not args.no_extra:
+        result["weight_only_w4a16"] = measure_weight_only(cfg, torch, sq, synth, max(10, args.steps // 2),
                                                           max(2, args.warmup // 4))
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, synth)

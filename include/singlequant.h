@@ -143,6 +143,41 @@ sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T, int32_t K,
                        void *Y, int64_t ldy, int32_t *acc_dbg, void *stream);
 
 /*
+ * sq_rotate_fp16 / sq_w4a16_gemm -- the weight-only setting (W4A16) of the
+ * paper's appendix (paragraph "Weight-only Quantization" and its table): Eq. 1,
+ * X W = (X R)(R^T W), with only the weight operand quantized.  The weight codes
+ * and steps are the ones sq_prepare_weights writes (or sq_rotate_quantize on
+ * the rows of W^T); the activations stay 16-bit.  Reading (the paper gives
+ * perplexities only): the online rotation is the same as in the W4A4 path and
+ * its result is kept in fp16.
+ *
+ * sq_rotate_fp16   steps 1 and 2 of sq_rotate_quantize (Givens list, then the
+ *   Kronecker rotation of Eq. 18) with fp32-or-better arithmetic, each entry of
+ *   the rotated row then rounded once to fp16 (nearest even; beyond the fp16
+ *   range the result is infinite).  No quantizer.
+ *     X, T, K, ldx, giv_*, P, R1, n1, R2, n2   as sq_rotate_quantize
+ *     Xrot   device out, fp16 [T, ldo], 16-byte aligned, ldo >= K, ldo % 8 == 0
+ *
+ * sq_w4a16_gemm    Y[t, n] = fp16( sw[n] * sum_k X[t, k] * Qw[n, k] ), products
+ *   exact, sums in fp32 on the matrix cores.
+ *     X        device, fp16 [T, ldx] (what sq_rotate_fp16 wrote); rows 16-byte
+ *              aligned (ldx % 8 == 0), ldx >= K
+ *     Qw, sw   device, uint8 [N, K/2] (16-byte aligned) and float [N]
+ *     Y        device out, fp16 [T, ldy], ldy >= N
+ *   Requires K % 64 == 0, K <= 131072.  T == 0 or N == 0 is legal and enqueues
+ *   nothing.
+ * W3A16 (three-bit codes) is not provided.
+ */
+sq_status sq_rotate_fp16(const void *X, int64_t T, int32_t K, int64_t ldx,
+                         const int32_t *giv_i, const int32_t *giv_j,
+                         const float *giv_theta, int32_t P,
+                         const void *R1, int32_t n1, const void *R2, int32_t n2,
+                         void *Xrot, int64_t ldo, void *stream);
+sq_status sq_w4a16_gemm(const void *X, int64_t T, int32_t K, int64_t ldx,
+                        const uint8_t *Qw, const float *sw, int32_t N,
+                        void *Y, int64_t ldy, void *stream);
+
+/*
  * sq_decode_layer -- sq_rotate_quantize_prepared followed by sq_w4a4_gemm in one
  * launch, for at most SQ_DECODE_MAX_TOKENS tokens (decoding, Sec. 5.4 "Inference
  * Efficiency",

@@ -21,8 +21,10 @@ from .binding import (  # noqa: F401
     sq_prepare_rotation,
     sq_prepare_weights,
     sq_prepared_rotation_bytes,
+    sq_rotate_fp16,
     sq_rotate_quantize,
     sq_rotate_quantize_prepared,
     sq_w4a4_gemm,
+    sq_w4a16_gemm,
     sq_status_string,
 )

@@ -67,6 +67,16 @@ def _load():
             C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
             C.c_void_p, C.c_int32, C.c_int32,
             C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p]
+        lib.sq_rotate_fp16.restype = C.c_int
+        lib.sq_rotate_fp16.argtypes = [
+            C.c_void_p, C.c_int64, C.c_int32, C.c_int64,
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+            C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
+            C.c_void_p, C.c_int64, C.c_void_p]
+        lib.sq_w4a16_gemm.restype = C.c_int
+        lib.sq_w4a16_gemm.argtypes = [
+            C.c_void_p, C.c_int64, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_int32,
+            C.c_void_p, C.c_int64, C.c_void_p]
         lib.sq_decode_layer_status.restype = C.c_int
         lib.sq_decode_layer_status.argtypes = [C.c_void_p, C.c_void_p]
         lib.sq_w4a4_gemm.restype = C.c_int
@@ -194,6 +204,33 @@ def sq_w4a4_gemm(Qx, sx, Qw, sw, Y, acc_dbg=None, stream=None) -> None:
         _dev_ptr(Qx), _dev_ptr(sx), T, 2 * Kh, _dev_ptr(Qw), _dev_ptr(sw), N,
         _dev_ptr(Y), ldy, _dev_ptr(acc_dbg), _stream_handle(stream))
     _check(code)
+
+
+def sq_rotate_fp16(X, giv_i, giv_j, giv_theta, R1, R2, Xrot, stream=None) -> None:
+    """Weight-only setting: the rotated rows as fp16, no quantizer.  X fp16 [T, K]; Xrot fp16
+    [T, K] (row stride = Xrot.stride(0)); the rest as sq_rotate_quantize."""
+    gi, gj, gt = _host(giv_i, np.int32), _host(giv_j, np.int32), _host(giv_theta, np.float32)
+    P = 0 if gi is None else int(gi.size)
+    T, K = int(X.shape[0]), int(X.shape[1])
+    ldx = int(X.stride(0)) if T > 1 else K
+    ldo = int(Xrot.stride(0)) if T > 1 else K
+    code = _load().sq_rotate_fp16(
+        _dev_ptr(X), T, K, ldx,
+        None if gi is None else gi.ctypes.data, None if gj is None else gj.ctypes.data,
+        None if gt is None else gt.ctypes.data, P,
+        _dev_ptr(R1), int(R1.shape[0]), _dev_ptr(R2), int(R2.shape[0]), _dev_ptr(Xrot), ldo, _stream_handle(stream))
+    _check(code)
+
+
+def sq_w4a16_gemm(X, Qw, sw, Y, stream=None) -> None:
+    """Weight-only setting: X fp16 [T, K] times weight codes Qw uint8 [N, K/2] with steps sw
+    fp32 [N] -> Y fp16 [T, N]."""
+    T, K = int(X.shape[0]), int(X.shape[1])
+    N = int(Qw.shape[0])
+    ldx = int(X.stride(0)) if T > 1 else K
+    ldy = int(Y.stride(0)) if T > 1 else max(N, 1)
+    _check(_load().sq_w4a16_gemm(_dev_ptr(X), T, K, ldx, _dev_ptr(Qw), _dev_ptr(sw), N, _dev_ptr(Y), ldy,
+                                 _stream_handle(stream)))
 
 
 def sq_decode_layer_workspace_bytes(T: int, K: int) -> int:

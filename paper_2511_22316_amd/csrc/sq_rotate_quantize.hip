@@ -21,7 +21,7 @@ constexpr int kGenThreads = 256;
 __global__ __launch_bounds__(kGenThreads) void rotate_quantize_generic_kernel(
     const __half *__restrict__ X, int64_t ldx, int K, int n1, int n2, GivensList giv,
     const __half *__restrict__ R1, const __half *__restrict__ R2, uint8_t *__restrict__ Q,
-    float *__restrict__ scales, float *__restrict__ xrot)
+    float *__restrict__ scales, float *__restrict__ xrot, __half *__restrict__ xout, int64_t ldo)
 {
     extern __shared__ float smem[];
     float *xs = smem;          // [K]  token row, then reused for Y
@@ -89,6 +89,11 @@ __global__ __launch_bounds__(kGenThreads) void rotate_quantize_generic_kernel(
     amax = wave_max(amax);
     if ((tid & (kWave - 1)) == 0) red[tid / kWave] = amax;
     __syncthreads();
+    if (xout != nullptr) {       // weight-only setting: the rotated row leaves as fp16, no quantizer
+        __half *orow = xout + t * ldo;
+        for (int k = tid; k < K; k += kGenThreads) orow[k] = __float2half_rn(xs[k]);
+        return;
+    }
     amax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 
     const float step = (amax == 0.f) ? 1.0f : amax / 7.0f;
@@ -321,15 +326,17 @@ static sq_status rotate_quantize_any(const void *X, int64_t T, int32_t K, int64_
                                      const float *giv_theta, int32_t P, const void *R1,
                                      int32_t n1, const void *R2, int32_t n2, uint8_t *Q,
                                      float *scales, float *xrot_dbg, void *stream, const void *frag1,
-                                     const void *frag2)
+                                     const void *frag2, void *xout = nullptr, int64_t ldo = 0)
 {
+    const bool f16out = ldo != 0;        // sq_rotate_fp16: Q and scales are unused, xout [T, ldo] is written
     if (T < 0 || K <= 0 || n1 <= 0 || n2 <= 0 || P < 0) return SQ_ERR_SHAPE;
     if (n1 > SQ_MAX_N1 || n2 > SQ_MAX_N2 || P > SQ_MAX_GIVENS) return SQ_ERR_SHAPE;
     if ((int64_t)n1 * n2 != K || (n2 % 8) != 0 || K > SQ_MAX_K || ldx < K) return SQ_ERR_SHAPE;
     if (T > SQ_MAX_ROWS) return SQ_ERR_SHAPE;
     if (P > 0 && (!giv_i || !giv_j || !giv_theta)) return SQ_ERR_NULL;
     if (!R1 || !R2) return SQ_ERR_NULL;
-    if (T > 0 && (!X || !Q || !scales)) return SQ_ERR_NULL;
+    if (f16out && ldo < K) return SQ_ERR_SHAPE;
+    if (T > 0 && (!X || (f16out ? !xout : (!Q || !scales)))) return SQ_ERR_NULL;
     const sq::ListCache *cache = nullptr;
     const sq_status list_status = sq::cached_list(giv_i, giv_j, giv_theta, P, K, n2, &cache);
     if (list_status != SQ_OK) return list_status;
@@ -338,6 +345,7 @@ static sq_status rotate_quantize_any(const void *X, int64_t T, int32_t K, int64_
     if ((ldx % 8) != 0 || ((uintptr_t)X & 15) || ((uintptr_t)Q & 15) || ((uintptr_t)R1 & 15) ||
         ((uintptr_t)R2 & 15) || ((uintptr_t)scales & 3) || ((uintptr_t)xrot_dbg & 3))
         return SQ_ERR_ALIGN;
+    if (f16out && (((uintptr_t)xout & 15) || (ldo % 8) != 0)) return SQ_ERR_ALIGN;
     if (T == 0) return SQ_OK;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -347,7 +355,12 @@ static sq_status rotate_quantize_any(const void *X, int64_t T, int32_t K, int64_
     if (!force_generic && prep.plan_ok) {
         sq_status status = SQ_OK;
         const bool prepared = frag1 != nullptr;
-        if (sq::rotq_mfma_dispatch(static_cast<const __half *>(X), ldx, (int)T, n1, n2, prep.plan,
+        if (f16out) {
+            if (sq::rotq_mfma_dispatch_f16(static_cast<const __half *>(X), ldx, (int)T, n1, n2, prep.plan,
+                                           static_cast<const __half *>(R1), static_cast<const __half *>(R2),
+                                           static_cast<__half *>(xout), ldo, st, &status))
+                return status;
+        } else if (sq::rotq_mfma_dispatch(static_cast<const __half *>(X), ldx, (int)T, n1, n2, prep.plan,
                                    static_cast<const __half *>(prepared ? frag1 : R1),
                                    static_cast<const __half *>(prepared ? frag2 : R2), Q, scales, xrot_dbg, st,
                                    &status, prepared))
@@ -359,8 +372,18 @@ static sq_status rotate_quantize_any(const void *X, int64_t T, int32_t K, int64_
     hipLaunchKernelGGL(sq::rotate_quantize_generic_kernel, dim3((unsigned)T), dim3(sq::kGenThreads),
                        lds, st, static_cast<const __half *>(X), ldx, K, n1, n2, giv,
                        static_cast<const __half *>(R1), static_cast<const __half *>(R2), Q, scales,
-                       xrot_dbg);
+                       xrot_dbg, static_cast<__half *>(xout), ldo);
     return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
+extern "C" sq_status sq_rotate_fp16(const void *X, int64_t T, int32_t K, int64_t ldx,
+                                    const int32_t *giv_i, const int32_t *giv_j, const float *giv_theta,
+                                    int32_t P, const void *R1, int32_t n1, const void *R2, int32_t n2,
+                                    void *Xrot, int64_t ldo, void *stream)
+{
+    if (ldo <= 0) return SQ_ERR_SHAPE;
+    return rotate_quantize_any(X, T, K, ldx, giv_i, giv_j, giv_theta, P, R1, n1, R2, n2, nullptr, nullptr, nullptr,
+                               stream, nullptr, nullptr, Xrot, ldo);
 }
 
 extern "C" sq_status sq_rotate_quantize(const void *X, int64_t T, int32_t K, int64_t ldx,

@@ -93,13 +93,16 @@ struct RotqShape {
 
 // QS_MAX: repair steps of 16 q-slots each the kernel holds rotation rows for (4 or 8).
 // PREPARED: R1 and R2 point at the operand fragments written by rotation_fragments_kernel.
+// F16OUT: no quantizer; the rotated row leaves as fp16 (round to nearest even) in xout [T, ldo]
+// (the 16-bit activations of the weight-only setting), and Q, scales, xrot are not touched.
 // g0, stride: the workgroup takes token groups g0, g0 + stride, ... (a kernel of its own passes its
 // block index and grid size); smem_u4: the workgroup's dynamic LDS, RotqShape::lds_bytes() of it.
-template <int N1, int N2, int QS_MAX, int NSX_, bool R1LDS, bool PREPARED>
+template <int N1, int N2, int QS_MAX, int NSX_, bool R1LDS, bool PREPARED, bool F16OUT = false>
 __device__ __forceinline__ void rotate_quantize_mfma_body(
     const __half *__restrict__ X, int64_t ldx, int T, const RotqPlan &plan,
     const __half *__restrict__ R1, const __half *__restrict__ R2, uint8_t *__restrict__ Q,
-    float *__restrict__ scales, float *__restrict__ xrot, const int g0, const int stride, uint4 *smem_u4)
+    float *__restrict__ scales, float *__restrict__ xrot, const int g0, const int stride, uint4 *smem_u4,
+    __half *__restrict__ xout = nullptr, int64_t ldo = 0)
 {
     using S = RotqShape<N1, N2, NSX_, R1LDS>;
     constexpr bool prepared = PREPARED;
@@ -576,11 +579,13 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
 
         // ---- per-token step: wave maximum now, token maximum after the barrier --------------
         float amax = 0.f;
-#pragma unroll
-        for (int nb = 0; nb < MB; ++nb) amax = max_abs16(accy[nb], amax);
-        amax = wave_max(amax) * fz_inv;        // padded rows and columns of Y are exact zeros
         float *red = reinterpret_cast<float *>(lds + off_red) + tok_slot * 4;
-        if (lane == 0) red[cb] = amax;
+        if constexpr (!F16OUT) {
+#pragma unroll
+            for (int nb = 0; nb < MB; ++nb) amax = max_abs16(accy[nb], amax);
+            amax = wave_max(amax) * fz_inv;    // padded rows and columns of Y are exact zeros
+            if (lane == 0) red[cb] = amax;
+        }
 
         // ---- lead wave: the next row has landed (rows complete in order; only the row after it
         // may still be in flight) -> rotate its touched channels
@@ -593,13 +598,16 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
         // stage A of this token ran an iteration ago, so its ring slot is free for the row after next
         if (NSX == 3 && lead) issue_row(grp + 3 * stride, slot);
 
-        amax = red[0];
+        float inv = fz_inv;                    // F16OUT: Y = accy * fz_inv
+        if constexpr (!F16OUT) {
+            amax = red[0];
 #pragma unroll
-        for (int w = 1; w < NCB; ++w) amax = fmaxf(amax, red[w]);
-        const float step = (amax == 0.f) ? 1.0f : amax / 7.0f;
-        const float inv = fz_inv / step;       // codes = Y / step with Y = accy * fz_inv
-        if (live && lead && lane == 0) scales[t] = step;
-        if (xrot != nullptr && live) {
+            for (int w = 1; w < NCB; ++w) amax = fmaxf(amax, red[w]);
+            const float step = (amax == 0.f) ? 1.0f : amax / 7.0f;
+            inv = fz_inv / step;               // codes = Y / step with Y = accy * fz_inv
+            if (live && lead && lane == 0) scales[t] = step;
+        }
+        if (!F16OUT && xrot != nullptr && live) {
 #pragma unroll
             for (int nb = 0; nb < MB; ++nb) {
                 const int po = 32 * nb + l32;
@@ -620,6 +628,16 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
         constexpr int NU = 4 * MB;               // quantization units of 4 codes
         auto quant_unit = [&](int u) {
             const int nb = u / 4, rg = u % 4;
+            if constexpr (F16OUT) {
+                // four consecutive q' of row p' = 32nb + l32 as one 8-byte store
+                const int po = 32 * nb + l32;
+                const v2h lo2 = {(_Float16)(accy[nb][4 * rg] * inv), (_Float16)(accy[nb][4 * rg + 1] * inv)};
+                const v2h hi2 = {(_Float16)(accy[nb][4 * rg + 2] * inv), (_Float16)(accy[nb][4 * rg + 3] * inv)};
+                if (live && po < N1)
+                    *reinterpret_cast<uint2 *>(xout + (int64_t)t * ldo + po * N2 + 32 * cb + 8 * rg + 4 * g) =
+                        uint2{__builtin_bit_cast(uint32_t, lo2), __builtin_bit_cast(uint32_t, hi2)};
+                return;
+            }
             uint32_t w = 0;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -640,7 +658,7 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
         // ---- copy-out: 16 bytes (8 units of one row p') per lane, coalesced along the row -----
         constexpr int ROW_OUT_CHUNKS = K / 32;      // 16-byte chunks of one code row
         constexpr int CH_PER_P = S::OUT_UNITS / 8;  // chunks per row p'
-        for (int c = tid; c < TPP * ROW_OUT_CHUNKS; c += 256) {
+        for (int c = tid; !F16OUT && c < TPP * ROW_OUT_CHUNKS; c += 256) {
             const int ts = c / ROW_OUT_CHUNKS, cc = c % ROW_OUT_CHUNKS;
             const int tt = grp * TPP + ts;
             const int po = cc / CH_PER_P, u0 = (cc % CH_PER_P) * 8;

@@ -30,6 +30,9 @@
 
 namespace sq {
 
+// value of the launch chain's `prepared` argument that selects the fp16-output kernel
+constexpr int kRotqFp16Out = 2;
+
 // QS_MAX: repair steps of 16 q-slots each the kernel holds rotation rows for (4 or 8).
 // PREPARED: R1 and R2 point at the operand fragments written by rotation_fragments_kernel.
 template <int N1, int N2, int OCC, int QS_MAX, int NSX_, bool R1LDS, bool PREPARED>
@@ -43,25 +46,43 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
                                                                     (int)blockIdx.x, (int)gridDim.x, smem_u4);
 }
 
+// The same rotation without the quantizer: the rotated rows leave as fp16 (the 16-bit activations
+// of the weight-only setting).  Built for R1, R2 as they are only.
+template <int N1, int N2, int OCC, int QS_MAX, int NSX_, bool R1LDS>
+__global__ __launch_bounds__(256, OCC) void rotate_fp16_mfma_kernel(
+    const __half *__restrict__ X, int64_t ldx, int T, RotqPlan plan, const __half *__restrict__ R1,
+    const __half *__restrict__ R2, __half *__restrict__ xout, int64_t ldo)
+{
+    extern __shared__ uint4 smem_u4[];
+    rotate_quantize_mfma_body<N1, N2, QS_MAX, NSX_, R1LDS, false, true>(
+        X, ldx, T, plan, R1, R2, nullptr, nullptr, nullptr, (int)blockIdx.x, (int)gridDim.x, smem_u4, xout, ldo);
+}
+
 // OCC: workgroups per CU the registers allow (512 per lane and SIMD, one wave of each workgroup
 // per SIMD); the LDS the list needs may allow fewer.
 template <int N1, int N2, int QS_MAX, int NSX, int OCC, bool R1LDS = false>
 static sq_status launch_rotq_mfma_ring(const __half *X, int64_t ldx, int T, const RotqPlan &plan,
                                        const __half *R1, const __half *R2, uint8_t *Q, float *scales,
-                                       float *xrot, hipStream_t st, int prepared)
+                                       float *xrot, hipStream_t st, int prepared, __half *xout, int64_t ldo)
 {
     using S = RotqShape<N1, N2, NSX, R1LDS>;
     const int qsteps = (plan.n_qslots + 15) / 16;
     const int lds = S::lds_bytes(qsteps);
     if (lds > kMaxDynamicLds) return SQ_ERR_SHAPE;
-    auto kernel = prepared ? rotate_quantize_mfma_kernel<N1, N2, OCC, QS_MAX, NSX, R1LDS, true>
-                           : rotate_quantize_mfma_kernel<N1, N2, OCC, QS_MAX, NSX, R1LDS, false>;
-    if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return SQ_ERR_LAUNCH;
     const int groups = (T + S::TPP - 1) / S::TPP;
     const int by_lds = (160 * 1024) / lds;
     const int per_cu = by_lds < OCC ? by_lds : OCC;                       // workgroups a CU holds
     const int resident = 256 * per_cu;
     const int grid = groups < resident ? groups : resident;
+    if (prepared == kRotqFp16Out) {
+        auto kernel = rotate_fp16_mfma_kernel<N1, N2, OCC, QS_MAX, NSX, R1LDS>;
+        if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return SQ_ERR_LAUNCH;
+        hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), lds, st, X, ldx, T, plan, R1, R2, xout, ldo);
+        return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+    }
+    auto kernel = prepared ? rotate_quantize_mfma_kernel<N1, N2, OCC, QS_MAX, NSX, R1LDS, true>
+                           : rotate_quantize_mfma_kernel<N1, N2, OCC, QS_MAX, NSX, R1LDS, false>;
+    if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return SQ_ERR_LAUNCH;
     hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), lds, st, X, ldx, T, plan, R1, R2, Q, scales, xrot);
     return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
@@ -69,7 +90,7 @@ static sq_status launch_rotq_mfma_ring(const __half *X, int64_t ldx, int T, cons
 template <int N1, int N2, int QS_MAX>
 static sq_status launch_rotq_mfma_qs(const __half *X, int64_t ldx, int T, const RotqPlan &plan,
                                      const __half *R1, const __half *R2, uint8_t *Q, float *scales,
-                                     float *xrot, hipStream_t st, int prepared)
+                                     float *xrot, hipStream_t st, int prepared, __half *xout, int64_t ldo)
 {
     constexpr int MB = (N1 + 31) / 32;
     if constexpr (N1 == 64 && N2 == 64) {
@@ -80,8 +101,8 @@ static sq_status launch_rotq_mfma_qs(const __half *X, int64_t ldx, int T, const 
         // With prepared operands the prologue is shorter and the third workgroup pays earlier: in a
         // stream of such launches T = 2048 10.0 -> 9.6 us, 3072 14.3 -> 12.6, 4096 16.7 -> 14.1.  At
         // 2048 the layer (this launch behind a GEMM) was 0.35 us slower with it, so it starts at 3072.
-        const bool ring2 = forced == 2 || (forced != 3 && T >= (prepared ? 3072 : 4096));
-        if (ring2) return launch_rotq_mfma_ring<N1, N2, QS_MAX, 2, 3>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st, prepared);
+        const bool ring2 = forced == 2 || (forced != 3 && T >= (prepared == 1 ? 3072 : 4096));
+        if (ring2) return launch_rotq_mfma_ring<N1, N2, QS_MAX, 2, 3>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st, prepared, xout, ldo);
     }
     if constexpr (MB == 3 && QS_MAX == 4) {       // more than 64 q-slots never leave room for two workgroups
         // With R1 in registers three row blocks need more than 256 of them: one workgroup per CU.
@@ -90,22 +111,22 @@ static sq_status launch_rotq_mfma_qs(const __half *X, int64_t ldx, int T, const 
         using S2 = RotqShape<N1, N2, 2, true>;
         const bool force_reg = debug_option(SQ_DEBUG_ROTQ_R1_IN_REGISTERS) != 0;
         if (!force_reg && 2 * S2::lds_bytes((plan.n_qslots + 15) / 16) <= 160 * 1024)
-            return launch_rotq_mfma_ring<N1, N2, QS_MAX, 2, 2, true>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st, prepared);
+            return launch_rotq_mfma_ring<N1, N2, QS_MAX, 2, 2, true>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st, prepared, xout, ldo);
     }
-    return launch_rotq_mfma_ring<N1, N2, QS_MAX, 3, (MB <= 2) ? 2 : 1>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st, prepared);
+    return launch_rotq_mfma_ring<N1, N2, QS_MAX, 3, (MB <= 2) ? 2 : 1>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st, prepared, xout, ldo);
 }
 
 // A list touches at most min(2P, n2) distinct columns q: more than 64 only if n2 is 128.
 template <int N1, int N2>
 static sq_status launch_rotq_mfma(const __half *X, int64_t ldx, int T, const RotqPlan &plan,
                                   const __half *R1, const __half *R2, uint8_t *Q, float *scales,
-                                  float *xrot, hipStream_t st, int prepared)
+                                  float *xrot, hipStream_t st, int prepared, __half *xout, int64_t ldo)
 {
     if constexpr (N2 > 64) {
         if (plan.n_qslots > 64)
-            return launch_rotq_mfma_qs<N1, N2, 8>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st, prepared);
+            return launch_rotq_mfma_qs<N1, N2, 8>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st, prepared, xout, ldo);
     }
-    return launch_rotq_mfma_qs<N1, N2, 4>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st, prepared);
+    return launch_rotq_mfma_qs<N1, N2, 4>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st, prepared, xout, ldo);
 }
 
 // The operand fragments of R2 (stage A) and R1 (stage B) exactly as the kernel above holds them,
@@ -164,13 +185,13 @@ sq_status rotq_write_fragments(const __half *R1, int n1, const __half *R2, int n
 
 // Picks the instantiation for (n1, n2); returns false if this kernel does not cover the shape.
 // prepared: R1 and R2 point at the fragments written by rotq_write_fragments.
-bool rotq_mfma_dispatch(const __half *X, int64_t ldx, int T, int n1, int n2, const RotqPlan &plan,
-                        const __half *R1, const __half *R2, uint8_t *Q, float *scales, float *xrot,
-                        hipStream_t st, sq_status *status, bool prepared)
+static bool rotq_mfma_dispatch_mode(const __half *X, int64_t ldx, int T, int n1, int n2, const RotqPlan &plan,
+                                    const __half *R1, const __half *R2, uint8_t *Q, float *scales, float *xrot,
+                                    hipStream_t st, sq_status *status, int prepared, __half *xout, int64_t ldo)
 {
 #define SQ_ROTQ_CASE(N1, N2)                                                                         \
     if (n1 == N1 && n2 == N2) {                                                                      \
-        *status = launch_rotq_mfma<N1, N2>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st, prepared);            \
+        *status = launch_rotq_mfma<N1, N2>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st, prepared, xout, ldo);            \
         return true;                                                                                 \
     }
     SQ_ROTQ_CASE(16, 32)     // K = 512
@@ -186,6 +207,22 @@ bool rotq_mfma_dispatch(const __half *X, int64_t ldx, int T, int n1, int n2, con
     SQ_ROTQ_CASE(128, 128)   // 16384
 #undef SQ_ROTQ_CASE
     return false;
+}
+
+bool rotq_mfma_dispatch(const __half *X, int64_t ldx, int T, int n1, int n2, const RotqPlan &plan,
+                        const __half *R1, const __half *R2, uint8_t *Q, float *scales, float *xrot,
+                        hipStream_t st, sq_status *status, bool prepared)
+{
+    return rotq_mfma_dispatch_mode(X, ldx, T, n1, n2, plan, R1, R2, Q, scales, xrot, st, status, prepared ? 1 : 0,
+                                   nullptr, 0);
+}
+
+bool rotq_mfma_dispatch_f16(const __half *X, int64_t ldx, int T, int n1, int n2, const RotqPlan &plan,
+                            const __half *R1, const __half *R2, __half *xout, int64_t ldo, hipStream_t st,
+                            sq_status *status)
+{
+    return rotq_mfma_dispatch_mode(X, ldx, T, n1, n2, plan, R1, R2, nullptr, nullptr, nullptr, st, status,
+                                   kRotqFp16Out, xout, ldo);
 }
 
 }  // namespace sq

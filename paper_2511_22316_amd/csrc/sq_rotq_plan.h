@@ -44,6 +44,11 @@ bool rotq_mfma_dispatch(const __half *X, int64_t ldx, int T, int n1, int n2, con
                         const __half *R1, const __half *R2, uint8_t *Q, float *scales, float *xrot,
                         hipStream_t st, sq_status *status, bool prepared = false);
 
+// The same rotation with fp16 output and no quantizer (R1, R2 as they are).
+bool rotq_mfma_dispatch_f16(const __half *X, int64_t ldx, int T, int n1, int n2, const RotqPlan &plan,
+                            const __half *R1, const __half *R2, __half *xout, int64_t ldo, hipStream_t st,
+                            sq_status *status);
+
 // Shapes the matrix-core kernel covers, and its operand fragments of R1 / R2 in the order the
 // lanes hold them (sizes in bytes; both multiples of 1024).
 bool rotq_mfma_covers(int n1, int n2);

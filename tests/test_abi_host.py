@@ -152,6 +152,32 @@ def test_decode_layer_static_argument_errors(lib):
     assert call(T=0) == 0 and call(N=0) == 0
 
 
+def test_weight_only_argument_errors(lib):
+    def rot(T=4, K=64, ldx=64, gi=(1,), gj=(2,), gt=(0.1,), n1=8, n2=8, X=FAKE, R1=FAKE, R2=FAKE, out=FAKE, ldo=64):
+        gi_a, gj_a, gt_a = np.asarray(gi, np.int32), np.asarray(gj, np.int32), np.asarray(gt, np.float32)
+        return lib.sq_rotate_fp16(X, T, K, ldx, gi_a.ctypes.data, gj_a.ctypes.data, gt_a.ctypes.data, len(gi_a),
+                                  R1, n1, R2, n2, out, ldo, None)
+    lib.sq_rotate_fp16.restype = C.c_int
+    lib.sq_rotate_fp16.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                   C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.c_int64,
+                                   C.c_void_p]
+    assert rot(K=63) == 2 and rot(ldo=32) == 2 and rot(ldo=0) == 2 and rot(T=-1) == 2 and rot(ldx=8) == 2
+    assert rot(gi=(64,)) == 3 and rot(gi=(2,)) == 3
+    assert rot(out=None) == 1 and rot(X=None) == 1 and rot(R1=None) == 1
+    assert rot(out=FAKE + 2) == 4 and rot(ldo=68) == 4 and rot(X=FAKE + 8) == 4
+    assert rot(T=0) == 0
+
+    def mm(T=4, K=64, ldx=64, N=8, ldy=8, X=FAKE, Qw=FAKE, sw=FAKE, Y=FAKE):
+        return lib.sq_w4a16_gemm(X, T, K, ldx, Qw, sw, N, Y, ldy, None)
+    lib.sq_w4a16_gemm.restype = C.c_int
+    lib.sq_w4a16_gemm.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_int32,
+                                  C.c_void_p, C.c_int64, C.c_void_p]
+    assert mm(K=96) == 2 and mm(K=0) == 2 and mm(T=-1) == 2 and mm(ldy=6) == 2 and mm(ldx=32) == 2 and mm(K=262144, ldx=262144) == 2
+    assert mm(X=None) == 1 and mm(Qw=None) == 1 and mm(Y=None) == 1 and mm(sw=None) == 1
+    assert mm(X=FAKE + 4) == 4 and mm(ldx=68) == 4 and mm(Qw=FAKE + 8) == 4 and mm(Y=FAKE + 1) == 4
+    assert mm(T=0) == 0 and mm(N=0, ldy=0) == 0
+
+
 def _gemm(lib, T=4, K=64, N=8, ldy=8, Qx=FAKE, sx=FAKE, Qw=FAKE, sw=FAKE, Y=FAKE):
     return lib.sq_w4a4_gemm(Qx, sx, T, K, Qw, sw, N, Y, ldy, None, None)
 

@@ -1,0 +1,209 @@
+"""GPU parity of the weight-only setting (W4A16, the paper's appendix on weight-only
+quantization): sq_rotate_fp16 and sq_w4a16_gemm through the C ABI against the CPU oracle.
+
+Bars.  Rotated rows: the fp32 result is within 1e-5 of the row maximum (the bar of the W4A4 path)
+and is then rounded once to fp16, so |gpu - oracle| <= 1e-5 max_k|row| + one fp16 spacing at the
+oracle's value.  GEMM: products of fp16 values and codes are exact, the sums run in fp32 in the
+matrix cores' own order, the step and the final rounding follow: |gpu - oracle| <= 2^-11 |oracle|
+(final rounding) + (K + 2) 2^-24 sw sum_k|x q| (summation in any order, the step) + one fp16
+subnormal spacing.  Whole layer: per token row ||dY|| / ||Y|| <= 1e-2."""
+import numpy as np
+import pytest
+
+from paper_2511_22316_amd import synth
+from parity_util import Y_ROW_TOL, dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+def run_rotate_fp16(L, X=None, ldo=None):
+    import torch
+    import paper_2511_22316_amd as sq
+    X = L.X if X is None else X
+    T, K = X.shape
+    out = torch.full((T, ldo or K), 7.0, dtype=torch.float16, device="cuda")
+    sq.sq_rotate_fp16(dev(X), L.giv_i, L.giv_j, L.giv_theta, dev(L.R1), dev(L.R2), out[:, :K])
+    torch.cuda.synchronize()
+    return host(out)
+
+
+def check_rotated_f16(got, want, xr):
+    """got, want fp16 [T, K]; xr the oracle's fp64 rotated rows."""
+    g, o = got.astype(np.float64), want.astype(np.float64)
+    assert np.all(np.isfinite(g) == np.isfinite(o))
+    fin = np.isfinite(o)
+    spacing = np.maximum(np.abs(np.nextafter(want, np.float16(np.inf)).astype(np.float64) - o),
+                         np.abs(o - np.nextafter(want, np.float16(-np.inf)).astype(np.float64)))
+    bound = 1e-5 * np.max(np.abs(xr), axis=1, keepdims=True) + np.where(fin, spacing, 0.0)
+    excess = np.where(fin, np.abs(g - o) - bound, 0.0)
+    assert excess.max() <= 0, f"rotated fp16 rows: worst excess {excess.max():.3e}"
+    return float(np.mean(got == want))
+
+
+@pytest.mark.parametrize("name,T", [("tiny", 16), ("attn_proj", 70), ("mlp_down", 37), ("decode", 8),
+                                    ("large_prefill", 33)])
+def test_rotate_fp16_matches_oracle(oracle, name, T):
+    print(f"case rotate_fp16 {name} T={T}", flush=True)
+    L = synth.layer(synth.CONFIGS[name], T)
+    got = run_rotate_fp16(L)
+    xr = oracle.rotate(L.X, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)
+    want = oracle.rotate_f16(L.X, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)
+    same = check_rotated_f16(got, want, xr)
+    print(f"  {same:.4f} of the entries are the oracle's fp16 value exactly", flush=True)
+    assert same > 0.8
+
+
+def test_rotate_fp16_other_shapes_and_edges(oracle):
+    print("case rotate_fp16 plain-kernel shape, strided output, no tokens", flush=True)
+    import torch
+    import paper_2511_22316_amd as sq
+    # a shape only the plain-FMA kernel takes
+    cfg = synth.LayerConfig("w16_12x8", 9, 12, 8, 16, 3, "normal", 1, 50.0, 0.02, 20.0, 0.02, 77)
+    L = synth.layer(cfg)
+    xr = oracle.rotate(L.X, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)
+    check_rotated_f16(run_rotate_fp16(L), oracle.rotate_f16(L.X, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2), xr)
+    # strided output: the padding is not written
+    L = synth.layer(synth.CONFIGS["tiny"])
+    out = run_rotate_fp16(L, ldo=L.X.shape[1] + 40)
+    assert np.all(out[:, L.X.shape[1]:] == 7.0)
+    xr = oracle.rotate(L.X, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)
+    check_rotated_f16(out[:, : L.X.shape[1]], oracle.rotate_f16(L.X, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2), xr)
+    # identity rotation, no list: the input comes back bit for bit
+    n1, n2 = 16, 32
+    Li = synth.Layer(L.cfg, L.X, L.giv_i[:0], L.giv_j[:0], L.giv_theta[:0], np.eye(n1, dtype=np.float16),
+                     np.eye(n2, dtype=np.float16), None, None)
+    assert np.array_equal(run_rotate_fp16(Li), L.X)
+    # no tokens
+    e = torch.empty((0, 512), dtype=torch.float16, device="cuda")
+    sq.sq_rotate_fp16(e, L.giv_i, L.giv_j, L.giv_theta, dev(L.R1), dev(L.R2), torch.empty_like(e))
+
+
+def run_w4a16(X, Qw, sw, ldy=None):
+    import torch
+    import paper_2511_22316_amd as sq
+    T, N = X.shape[0], Qw.shape[0]
+    Y = torch.full((T, ldy or N), -9.0, dtype=torch.float16, device="cuda")
+    sq.sq_w4a16_gemm(dev(X), dev(Qw), dev(sw), Y[:, :N])
+    torch.cuda.synchronize()
+    return host(Y)
+
+
+def check_w4a16(Yg, Yo, m, K):
+    g, o = Yg.astype(np.float64), Yo.astype(np.float64)
+    bound = 2.0 ** -11 * np.abs(o) * 1.001 + (K + 2) * 2.0 ** -24 * m + 2.0 ** -24
+    excess = np.abs(g - o) - bound
+    assert excess.max() <= 0, f"w4a16 Y: worst excess {excess.max():.3e}"
+
+
+@pytest.mark.parametrize("T,K,N", [(1, 64, 1), (16, 512, 512), (77, 128, 300), (130, 320, 257), (300, 2048, 130),
+                                   (256, 4096, 384), (129, 64, 129)])
+def test_w4a16_gemm_random_operands(oracle, T, K, N):
+    print(f"case w4a16 gemm random T={T} K={K} N={N}", flush=True)
+    g = np.random.default_rng(T + 3 * K + 5 * N)
+    X = (g.standard_normal((T, K)) * g.choice([0.1, 1.0, 30.0], size=(T, 1))).astype(np.float16)
+    Qw = synth.random_codes(N, K, 300 + N)           # all 16 codes, -8 included
+    sw = g.uniform(1e-4, 5e-3, N).astype(np.float32)
+    Yo, m = oracle.gemm_w4a16(X, Qw, sw, want_abs_sum=True)
+    Yg = run_w4a16(X, Qw, sw)
+    check_w4a16(Yg, Yo, m, K)
+    # exactly representable case: small integers, step 1/4 -> no rounding anywhere, equal bits
+    Xi = g.integers(-3, 4, size=(T, K)).astype(np.float16)
+    s4 = np.full(N, 0.25, np.float32)
+    Yi = oracle.gemm_w4a16(Xi, Qw, s4)
+    if np.max(np.abs(Yi.astype(np.float64))) < 2048:
+        assert np.array_equal(run_w4a16(Xi, Qw, s4), Yi)
+
+
+def test_w4a16_gemm_strided_and_empty(oracle):
+    print("case w4a16 gemm strided output / input, empty", flush=True)
+    import torch
+    import paper_2511_22316_amd as sq
+    g = np.random.default_rng(4)
+    T, K, N = 40, 192, 72
+    X = g.standard_normal((T, K)).astype(np.float16)
+    Qw, sw = synth.random_codes(N, K, 2), np.full(N, 0.01, np.float32)
+    Yo, m = oracle.gemm_w4a16(X, Qw, sw, want_abs_sum=True)
+    got = run_w4a16(X, Qw, sw, ldy=N + 10)
+    check_w4a16(got[:, :N], Yo, m, K)
+    assert np.all(got[:, N:] == -9.0)
+    wide = torch.zeros((T, K + 64), dtype=torch.float16, device="cuda")
+    wide[:, :K] = dev(X)
+    Y = torch.empty((T, N), dtype=torch.float16, device="cuda")
+    sq.sq_w4a16_gemm(wide[:, :K], dev(Qw), dev(sw), Y)
+    torch.cuda.synchronize()
+    check_w4a16(host(Y), Yo, m, K)
+    sq.sq_w4a16_gemm(wide[:0, :K], dev(Qw), dev(sw), Y[:0])
+
+
+@pytest.mark.parametrize("name,T,N", [("tiny", 16, 512), ("attn_proj", 96, 300), ("mlp_down", 40, 130)])
+def test_weight_only_layer_end_to_end(oracle, name, T, N):
+    """GPU pipeline (rotation to fp16, offline weight path, W4A16 GEMM: its own values on both
+    operands) against the oracle pipeline."""
+    print(f"case weight-only layer {name} T={T} N={N}", flush=True)
+    import torch
+    import paper_2511_22316_amd as sq
+    cfg = synth.CONFIGS[name]
+    L = synth.layer(cfg, T)
+    Wt = synth.weights_t(cfg, N)
+    xo = oracle.rotate_f16(L.X, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)
+    Qwo, swo = oracle.prepare_weights(Wt, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)
+    Yo = oracle.gemm_w4a16(xo, Qwo, swo).astype(np.float64)
+    dR1, dR2 = dev(L.R1), dev(L.R2)
+    Qw = torch.empty((N, cfg.K // 2), dtype=torch.uint8, device="cuda")
+    sw = torch.empty((N,), dtype=torch.float32, device="cuda")
+    sq.sq_rotate_quantize(dev(Wt), L.giv_i, L.giv_j, L.giv_theta, dR1, dR2, Qw, sw)
+    Xr = torch.empty((T, cfg.K), dtype=torch.float16, device="cuda")
+    sq.sq_rotate_fp16(dev(L.X), L.giv_i, L.giv_j, L.giv_theta, dR1, dR2, Xr)
+    Y = torch.empty((T, N), dtype=torch.float16, device="cuda")
+    sq.sq_w4a16_gemm(Xr, Qw, sw, Y)
+    torch.cuda.synchronize()
+    d = host(Y).astype(np.float64) - Yo
+    rel = np.linalg.norm(d, axis=1) / np.linalg.norm(Yo, axis=1)
+    print(f"  worst row error {rel.max():.3e}", flush=True)
+    assert rel.max() <= Y_ROW_TOL
+    # and the point of the variant: with 16-bit activations the layer is closer to X W than W4A4
+    ref = L.X.astype(np.float64) @ Wt.astype(np.float64).T
+    e16 = np.linalg.norm(host(Y).astype(np.float64) - ref) / np.linalg.norm(ref)
+    Qx = torch.empty((T, cfg.K // 2), dtype=torch.uint8, device="cuda")
+    sx = torch.empty((T,), dtype=torch.float32, device="cuda")
+    sq.sq_rotate_quantize(dev(L.X), L.giv_i, L.giv_j, L.giv_theta, dR1, dR2, Qx, sx)
+    Y4 = torch.empty((T, N), dtype=torch.float16, device="cuda")
+    sq.sq_w4a4_gemm(Qx, sx, Qw, sw, Y4)
+    torch.cuda.synchronize()
+    e4 = np.linalg.norm(host(Y4).astype(np.float64) - ref) / np.linalg.norm(ref)
+    print(f"  error against X W: W4A16 {e16:.3f}, W4A4 {e4:.3f}", flush=True)
+    assert e16 < e4
+
+
+def test_weight_only_full_size_attn_proj_sampled_rows(oracle):
+    """Full attn_proj layer in the configuration the benchmark times; sampled token rows x all N
+    against the oracle pipeline."""
+    print("case weight-only attn_proj full size", flush=True)
+    import torch
+    import paper_2511_22316_amd as sq
+    cfg = synth.CONFIGS["attn_proj"]
+    L = synth.layer(cfg)
+    T, K, N = cfg.T, cfg.K, cfg.N
+    Wt = synth.weights_t(cfg)
+    dR1, dR2 = dev(L.R1), dev(L.R2)
+    Qw = torch.empty((N, K // 2), dtype=torch.uint8, device="cuda")
+    sw = torch.empty((N,), dtype=torch.float32, device="cuda")
+    sq.sq_rotate_quantize(dev(Wt), L.giv_i, L.giv_j, L.giv_theta, dR1, dR2, Qw, sw)
+    Xr = torch.empty((T, K), dtype=torch.float16, device="cuda")
+    sq.sq_rotate_fp16(dev(L.X), L.giv_i, L.giv_j, L.giv_theta, dR1, dR2, Xr)
+    Y = torch.empty((T, N), dtype=torch.float16, device="cuda")
+    sq.sq_w4a16_gemm(Xr, Qw, sw, Y)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, T - 1], np.random.default_rng(23).integers(0, T, 48)]))
+    xr = oracle.rotate(L.X[rows], L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)
+    xo = oracle.rotate_f16(L.X[rows], L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)
+    check_rotated_f16(host(Xr)[rows], xo, xr)
+    Qwo, swo = oracle.prepare_weights(Wt, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)
+    Yo = oracle.gemm_w4a16(xo, Qwo, swo).astype(np.float64)
+    d = host(Y)[rows].astype(np.float64) - Yo
+    rel = np.linalg.norm(d, axis=1) / np.linalg.norm(Yo, axis=1)
+    print(f"  worst row error {rel.max():.3e} over {len(rows)} rows", flush=True)
+    assert rel.max() <= Y_ROW_TOL
+    # the GEMM alone on the GPU's own operands: element-wise bound
+    Yo2, m = oracle.gemm_w4a16(host(Xr)[rows], host(Qw), host(sw), want_abs_sum=True)
+    check_w4a16(host(Y)[rows], Yo2, m, K)
