@@ -47,7 +47,7 @@ __global__ __launch_bounds__(256, 2) void decode_layer_kernel(
     const __half *__restrict__ X, int64_t ldx, int T, RotqPlan plan, const __half *__restrict__ F1,
     const __half *__restrict__ F2, uint8_t *Qx, float *sx, int *__restrict__ ctr,
     const uint8_t *__restrict__ Qw, const float *__restrict__ sw, int N, __half *__restrict__ Y, int64_t ldy,
-    int lds_main, int spin_limit)
+    int lds_main, int spin_limit, int sides)
 {
     using S = RotqShape<N1, N2, 3, false>;
     constexpr int Kb = N1 * N2 / 2, NW = 4, BN = 32 * FN, SLICE = 128;
@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256, 2) void decode_layer_kernel(
 
     if (block < groups) {
         rotate_quantize_mfma_body<N1, N2, QS_MAX, 3, false, true>(X, ldx, T, plan, F1, F2, Qx, sx, nullptr, block,
-                                                                  groups, smem_u4);
+                                                                  groups, smem_u4, sides);
         // Every wave has waited for its own stores (the body ends on vmcnt(0)); behind the barrier one
         // release writes this XCD's L2 back before the count can be seen.
         __syncthreads();
@@ -209,7 +209,8 @@ sq_status launch_decode_layer(const __half *X, int64_t ldx, int T, const RotqPla
     using S = RotqShape<N1, N2, 3, false>;
     constexpr int BN = 32 * FN;
     // the rotation's tiles, then the partial sums
-    const int rot_lds = S::lds_bytes((plan.n_qslots + 15) / 16), red_lds = 4 * FN * 16 * kWave * 4;
+    const int qsteps = (plan.n_qslots + 15) / 16, sides = S::side_tiles(qsteps, 2);
+    const int rot_lds = S::lds_bytes(qsteps, sides), red_lds = 4 * FN * 16 * kWave * 4;
     const int lds_main = ((rot_lds > red_lds ? rot_lds : red_lds) + 15) / 16 * 16;
     const int lds = lds_main + 16;
     if (lds > kMaxDynamicLds) return SQ_ERR_SHAPE;
@@ -224,7 +225,7 @@ sq_status launch_decode_layer(const __half *X, int64_t ldx, int T, const RotqPla
     const int option = debug_option(SQ_DEBUG_DECODE_SPIN_LIMIT);
     const int spin_limit = option > 0 ? option : (1 << 20);
     hipLaunchKernelGGL(kernel, dim3((unsigned)tiles), dim3(256), lds, st, X, ldx, T, plan, F1, F2, Qx, sx, ctr, Qw, sw,
-                       N, Y, ldy, lds_main, spin_limit);
+                       N, Y, ldy, lds_main, spin_limit, sides);
     return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 

@@ -74,15 +74,27 @@ struct RotqShape {
     static constexpr int NSX = NSX_;              // ring of token tiles
     static constexpr int TILE_BYTES = N1P * N2 * 2;
     static constexpr int LO_STEP_BYTES = N1P * 32;        // side tile: [step][row p][16 fp16]
-    static constexpr int OUT_UNITS = N2 / 4;      // 2-byte units (4 codes) per output row p'
-    static constexpr int OUT_BYTES = OUT_UNITS * N1P * 2;             // staged as [unit][p']
     static constexpr int OFF_X = 0;                                   // [TPP][NSX][TILE]
     static constexpr int OFF_R1F = TPP * NSX * TILE_BYTES;            // [MB][KSB][64 lanes][16 bytes]
     static constexpr int R1F_BYTES = R1LDS_ ? MB * KSB * 1024 : 0;
-    static constexpr int OFF_LO = OFF_R1F + R1F_BYTES;                // [TPP][qsteps][LO_STEP]
-    // after the side tiles (runtime size): [TPP][128] float, [TPP][4] float, [TPP][OUT]
-    static constexpr int TAIL_BYTES = TPP * (kRotqMaxSlots * 4 + 16 + OUT_BYTES);
-    static constexpr int lds_bytes(int qsteps) { return OFF_LO + TPP * qsteps * LO_STEP_BYTES + TAIL_BYTES; }
+    static constexpr int OFF_LO = OFF_R1F + R1F_BYTES;                // [TPP][side tiles][qsteps][LO_STEP]
+    // after the side tiles (runtime size): [TPP][128] float, [2][TPP][4] float
+    static constexpr int TAIL_BYTES = TPP * (kRotqMaxSlots * 4 + 32);
+    // sides: side tiles per token slot, 2 (they alternate from token to token, one barrier per
+    // token) or 1 (less LDS, a second barrier per token)
+    static constexpr int lds_bytes(int qsteps, int sides)
+    {
+        return OFF_LO + TPP * sides * qsteps * LO_STEP_BYTES + TAIL_BYTES;
+    }
+    // two side tiles per token slot unless they would cost a workgroup its place on the CU (occ:
+    // workgroups per CU that the registers allow) or do not fit at all
+    static constexpr int side_tiles(int qsteps, int occ)
+    {
+        const int l1 = lds_bytes(qsteps, 1), l2 = lds_bytes(qsteps, 2);
+        const int per_cu_1 = (160 * 1024) / l1 < occ ? (160 * 1024) / l1 : occ;
+        const int per_cu_2 = (160 * 1024) / l2 < occ ? (160 * 1024) / l2 : occ;
+        return (l2 <= kMaxDynamicLds && per_cu_2 >= per_cu_1) ? 2 : 1;
+    }
     static_assert(N2 == 32 || N2 == 64 || N2 == 128, "one to four waves per token");
     static_assert(NSX == 2 || NSX == 3, "ring of two or three tiles");
     static_assert(N1P <= 128, "at most four row blocks");
@@ -96,13 +108,14 @@ struct RotqShape {
 // F16OUT: no quantizer; the rotated row leaves as fp16 (round to nearest even) in xout [T, ldo]
 // (the 16-bit activations of the weight-only setting), and Q, scales, xrot are not touched.
 // g0, stride: the workgroup takes token groups g0, g0 + stride, ... (a kernel of its own passes its
-// block index and grid size); smem_u4: the workgroup's dynamic LDS, RotqShape::lds_bytes() of it.
+// block index and grid size); smem_u4: the workgroup's dynamic LDS, RotqShape::lds_bytes() of it;
+// sides: side tiles per token slot (RotqShape::side_tiles).
 template <int N1, int N2, int QS_MAX, int NSX_, bool R1LDS, bool PREPARED, bool F16OUT = false>
 __device__ __forceinline__ void rotate_quantize_mfma_body(
     const __half *__restrict__ X, int64_t ldx, int T, const RotqPlan &plan,
     const __half *__restrict__ R1, const __half *__restrict__ R2, uint8_t *__restrict__ Q,
     float *__restrict__ scales, float *__restrict__ xrot, const int g0, const int stride, uint4 *smem_u4,
-    __half *__restrict__ xout = nullptr, int64_t ldo = 0)
+    const int sides, __half *__restrict__ xout = nullptr, int64_t ldo = 0)
 {
     using S = RotqShape<N1, N2, NSX_, R1LDS>;
     constexpr bool prepared = PREPARED;
@@ -125,10 +138,10 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
                  "s"(Q), "s"(scales), "s"(xrot), "s"(stride));
 
     const int qsteps = (n_qslots + 15) / 16;                 // extra MFMA steps that repair the Givens rounding
-    const int lo_bytes = qsteps * S::LO_STEP_BYTES;          // one side tile
-    const int off_gv = S::OFF_LO + TPP * lo_bytes;
-    const int off_red = off_gv + TPP * kRotqMaxSlots * 4;
-    const int off_out = off_red + TPP * 16;
+    const int lo_bytes = qsteps * S::LO_STEP_BYTES;          // one side tile; every token slot has two
+    const int off_gv = S::OFF_LO + TPP * sides * lo_bytes;
+    const int side_mask = sides - 1;                         // 1: the two tiles alternate, 0: one tile
+    const int off_red = off_gv + TPP * kRotqMaxSlots * 4;    // [2][TPP][4] floats
 
     const int groups = (T + TPP - 1) / TPP;
     // does this wave's token exist in group grp (the last group may be partial)?
@@ -188,11 +201,13 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
     // declared here, filled in once the plan entries have arrived
     int my_level = -1, gs_tile[2] = {-1, -1}, gs_lo[2] = {0, 0};
 
-    // lead wave: Givens list on the tile in ring slot `slot`; fills the token's side tile
-    auto givens = [&](int slot) {
+    // lead wave: Givens list on the tile in ring slot `slot`; fills side tile `side` (0 / 1: the two
+    // alternate from token to token, so that the list of the token after next can be applied while
+    // stage A of the next one may still be reading its side tile)
+    auto givens = [&](int slot, int side) {
         if (n_slots == 0) return;
         char *xt = lds + S::OFF_X + (tok_slot * NSX + slot) * S::TILE_BYTES;
-        char *lo_t = lds + S::OFF_LO + tok_slot * lo_bytes;
+        char *lo_t = lds + S::OFF_LO + (tok_slot * sides + (side & side_mask)) * lo_bytes;
         float *gv = reinterpret_cast<float *>(lds + off_gv) + tok_slot * kRotqMaxSlots;
 #pragma unroll
         for (int u = 0; u < 2; ++u)
@@ -353,7 +368,7 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
                 *reinterpret_cast<uint4 *>(lds + S::OFF_X + tile * S::TILE_BYTES + (N1 * CPRX + r) * 16) = uint4{0, 0, 0, 0};
             }
         }
-        for (int c = tid; c < TPP * lo_bytes / 16; c += 256)
+        for (int c = tid; c < TPP * sides * lo_bytes / 16; c += 256)
             *reinterpret_cast<uint4 *>(lds + S::OFF_LO + c * 16) = uint4{0, 0, 0, 0};
 
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -364,7 +379,7 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
             gs_tile[u] = (lane + 64 * u < n_slots) ? (p * CPRX + ((q >> 3) ^ swz<CPRX>(p))) * 16 + (q & 7) * 2 : -1;
             gs_lo[u] = (qs >> 4) * S::LO_STEP_BYTES + p * 32 + (qs & 15) * 2;
         }
-        if (lead) givens(0);
+        if (lead) givens(0, 0);
         if constexpr (!prepared) {
 #pragma unroll
             for (int blk = 0; blk < N2 / 32; ++blk) {
@@ -450,7 +465,7 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
     // issued (quantization units of the previous token, or nothing)
     v16f accz[MB], accy[MB];
     constexpr int NMA = MB * KSA;
-    auto stage_a = [&](int slot, auto between) {
+    auto stage_a = [&](int slot, int side, auto between) {
         const char *xt = lds + S::OFF_X + (tok_slot * NSX + slot) * S::TILE_BYTES;
         auto a_at = [&](int m) {
             const int mb = m / KSA, ks = m % KSA;
@@ -463,14 +478,15 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
         v8h a0 = a_at(0), a1 = a_at(NMA > 1 ? 1 : 0);
 #pragma unroll
         for (int m = 0; m < NMA; ++m) {
-            const v8h a2 = a_at(m + 2 < NMA ? m + 2 : NMA - 1);     // operand reads run two MFMAs ahead
+            // operand reads run two MFMAs ahead (four ahead measured 2-4 % slower on every shape)
+            const v8h a2 = a_at(m + 2 < NMA ? m + 2 : NMA - 1);
             accz[m / KSA] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, r2f[m % KSA], accz[m / KSA], 0, 0, 0);
             between(m);
             __builtin_amdgcn_sched_barrier(0);
             a0 = a1;
             a1 = a2;
         }
-        const char *lo_t = lds + S::OFF_LO + tok_slot * lo_bytes;
+        const char *lo_t = lds + S::OFF_LO + (tok_slot * sides + (side & side_mask)) * lo_bytes;
 #pragma unroll
         for (int x = 0; x < QS_MAX; ++x) {
             if (x < qsteps) {
@@ -485,13 +501,18 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
 
     // ---- pipeline prologue: first row rotated, its stage A done -------------------------------
     __syncthreads();                       // first row rotated
-    stage_a(0, [](int) {});
-    // One side tile per token serves every row: stage A of a row has read it before the barrier
-    // that ends an iteration, and the list of the next row writes it after that barrier.  Here,
-    // ahead of the first iteration, the same order needs a barrier of its own.
-    __syncthreads();
+    stage_a(0, 0, [](int) {});
+    if (sides == 1) __syncthreads();       // the one side tile is rewritten in the first iteration
 
-    int slot = 0;
+    // Barriers per token: one (B2), behind which the token maximum, the rotated next tile and its
+    // side tile are visible.  Nothing else is shared between waves: codes leave from registers, and
+    // what a wave writes ahead of B2 of one iteration (its maximum, the lead wave's side tile) goes
+    // into the copy that nobody can still be reading, because the two copies alternate from token
+    // to token and every wave has passed the previous B2 since the last use.  With a ring of two
+    // tiles a second barrier per token (B3) protects the tile that is refilled right behind it,
+    // and with a single side tile per token slot (very long lists on the largest shapes) the
+    // side tile that the next list overwrites.
+    int slot = 0, par = 0;                 // ring slot and parity (side tile, maxima) of the current token
     for (int grp = g0; grp < groups; grp += stride) {
         const int t = grp * TPP + tok_slot;
         const bool live = t < T;
@@ -579,7 +600,7 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
 
         // ---- per-token step: wave maximum now, token maximum after the barrier --------------
         float amax = 0.f;
-        float *red = reinterpret_cast<float *>(lds + off_red) + tok_slot * 4;
+        float *red = reinterpret_cast<float *>(lds + off_red) + (par * TPP + tok_slot) * 4;
         if constexpr (!F16OUT) {
 #pragma unroll
             for (int nb = 0; nb < MB; ++nb) amax = max_abs16(accy[nb], amax);
@@ -592,9 +613,9 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
         if (lead) {
             if (has_row(grp + 2 * stride)) wait_loads_le<LPT>();
             else wait_loads_le<0>();
-            if (has_row(grp + stride)) givens(slot1);
+            if (has_row(grp + stride)) givens(slot1, par ^ 1);
         }
-        __syncthreads();     // B2: maxima visible; next tile rotated; copy-out of the last token done
+        __syncthreads();     // B2: maxima visible; next tile and its side tile rotated
         // stage A of this token ran an iteration ago, so its ring slot is free for the row after next
         if (NSX == 3 && lead) issue_row(grp + 3 * stride, slot);
 
@@ -622,10 +643,13 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
 
         // ---- codes of this token, issued between the stage-A MFMAs of the next one ------------
         // A lane holds column p' = 32nb + l32 of Y^T and, per register group rg, four consecutive
-        // q' = 32cb + 8rg + 4g + (0..3): one 2-byte unit of the code row.  Staged as [unit][p'] so
-        // that the 32 lanes of a store hit 32 consecutive halfwords.
-        uint16_t *outq = reinterpret_cast<uint16_t *>(lds + off_out + tok_slot * S::OUT_BYTES);
+        // q' = 32cb + 8rg + 4g + (0..3): one 2-byte unit of the code row; the eight units (rg, g) of
+        // a row p' are 16 contiguous bytes of Q.  The two half-waves trade units (one cross-half
+        // swap per pair) so that lanes g = 0 end up with the eight bytes of rg = 0, 1 and lanes
+        // g = 1 with those of rg = 2, 3, and the wave stores 32 row pieces of 16 bytes with one
+        // 8-byte store per lane, straight from registers.
         constexpr int NU = 4 * MB;               // quantization units of 4 codes
+        uint32_t unit[4];                        // the four units of the row block being quantized
         auto quant_unit = [&](int u) {
             const int nb = u / 4, rg = u % 4;
             if constexpr (F16OUT) {
@@ -645,32 +669,30 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
                 const uint32_t c = (uint32_t)fmaf(accy[nb][4 * rg + k], inv, 8.5f);
                 w |= c << (4 * k);
             }
-            outq[(8 * cb + 2 * rg + g) * N1P + 32 * nb + l32] = (uint16_t)(w ^ 0x8888u);
+            unit[rg] = w;
+            if (rg == 3) {
+                // swap(a, b): result 0 = (a of lanes 0..31, b of lanes 0..31), result 1 = (a of lanes
+                // 32..63, b of lanes 32..63).  With a = unit rg, b = unit rg + 2: lanes g = 0 get both
+                // halves (g = 0 low, g = 1 high) of unit rg, lanes g = 1 those of unit rg + 2.
+                typedef uint32_t v2u __attribute__((ext_vector_type(2)));
+                const v2u s02 = __builtin_amdgcn_permlane32_swap(unit[0], unit[2], false, false);
+                const v2u s13 = __builtin_amdgcn_permlane32_swap(unit[1], unit[3], false, false);
+                const uint32_t d0 = (s02[0] | (s02[1] << 16)) ^ 0x88888888u;     // rg = 0 (g = 0) or 2 (g = 1)
+                const uint32_t d1 = (s13[0] | (s13[1] << 16)) ^ 0x88888888u;     // rg = 1 (g = 0) or 3 (g = 1)
+                const int po = 32 * nb + l32;
+                if (live && po < N1)
+                    *reinterpret_cast<uint2 *>(Q + (int64_t)t * (K / 2) + po * (N2 / 2) + 16 * cb + 8 * g) = uint2{d0, d1};
+            }
         };
-        stage_a(slot1, [&](int m) {
+        stage_a(slot1, par ^ 1, [&](int m) {
             // NU units spread over the NMA MFMAs
 #pragma unroll
             for (int u = 0; u < NU; ++u)
                 if (u * NMA / NU == m) quant_unit(u);
         });
-        __syncthreads();     // B3: staged codes complete
-
-        // ---- copy-out: 16 bytes (8 units of one row p') per lane, coalesced along the row -----
-        constexpr int ROW_OUT_CHUNKS = K / 32;      // 16-byte chunks of one code row
-        constexpr int CH_PER_P = S::OUT_UNITS / 8;  // chunks per row p'
-        for (int c = tid; !F16OUT && c < TPP * ROW_OUT_CHUNKS; c += 256) {
-            const int ts = c / ROW_OUT_CHUNKS, cc = c % ROW_OUT_CHUNKS;
-            const int tt = grp * TPP + ts;
-            const int po = cc / CH_PER_P, u0 = (cc % CH_PER_P) * 8;
-            const uint16_t *src = reinterpret_cast<const uint16_t *>(lds + off_out + ts * S::OUT_BYTES) + u0 * N1P + po;
-            uint4 v;
-            v.x = src[0] | ((uint32_t)src[N1P] << 16);
-            v.y = src[2 * N1P] | ((uint32_t)src[3 * N1P] << 16);
-            v.z = src[4 * N1P] | ((uint32_t)src[5 * N1P] << 16);
-            v.w = src[6 * N1P] | ((uint32_t)src[7 * N1P] << 16);
-            if (tt < T) reinterpret_cast<uint4 *>(Q + (int64_t)tt * (K / 2))[cc] = v;
-        }
+        if (NSX == 2 || sides == 1) __syncthreads();     // B3: every wave is done with the tile / side tile rewritten next
         slot = slot1;
+        par ^= 1;
     }
     wait_loads_le<0>();
 }

@@ -39,11 +39,11 @@ template <int N1, int N2, int OCC, int QS_MAX, int NSX_, bool R1LDS, bool PREPAR
 __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
     const __half *__restrict__ X, int64_t ldx, int T, RotqPlan plan,
     const __half *__restrict__ R1, const __half *__restrict__ R2, uint8_t *__restrict__ Q,
-    float *__restrict__ scales, float *__restrict__ xrot)
+    float *__restrict__ scales, float *__restrict__ xrot, int sides)
 {
     extern __shared__ uint4 smem_u4[];
     rotate_quantize_mfma_body<N1, N2, QS_MAX, NSX_, R1LDS, PREPARED>(X, ldx, T, plan, R1, R2, Q, scales, xrot,
-                                                                    (int)blockIdx.x, (int)gridDim.x, smem_u4);
+                                                                    (int)blockIdx.x, (int)gridDim.x, smem_u4, sides);
 }
 
 // The same rotation without the quantizer: the rotated rows leave as fp16 (the 16-bit activations
@@ -51,11 +51,12 @@ __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
 template <int N1, int N2, int OCC, int QS_MAX, int NSX_, bool R1LDS>
 __global__ __launch_bounds__(256, OCC) void rotate_fp16_mfma_kernel(
     const __half *__restrict__ X, int64_t ldx, int T, RotqPlan plan, const __half *__restrict__ R1,
-    const __half *__restrict__ R2, __half *__restrict__ xout, int64_t ldo)
+    const __half *__restrict__ R2, __half *__restrict__ xout, int64_t ldo, int sides)
 {
     extern __shared__ uint4 smem_u4[];
-    rotate_quantize_mfma_body<N1, N2, QS_MAX, NSX_, R1LDS, false, true>(
-        X, ldx, T, plan, R1, R2, nullptr, nullptr, nullptr, (int)blockIdx.x, (int)gridDim.x, smem_u4, xout, ldo);
+    rotate_quantize_mfma_body<N1, N2, QS_MAX, NSX_, R1LDS, false, true>(X, ldx, T, plan, R1, R2, nullptr, nullptr,
+                                                                        nullptr, (int)blockIdx.x, (int)gridDim.x,
+                                                                        smem_u4, sides, xout, ldo);
 }
 
 // OCC: workgroups per CU the registers allow (512 per lane and SIMD, one wave of each workgroup
@@ -67,7 +68,8 @@ static sq_status launch_rotq_mfma_ring(const __half *X, int64_t ldx, int T, cons
 {
     using S = RotqShape<N1, N2, NSX, R1LDS>;
     const int qsteps = (plan.n_qslots + 15) / 16;
-    const int lds = S::lds_bytes(qsteps);
+    const int sides = S::side_tiles(qsteps, OCC);
+    const int lds = S::lds_bytes(qsteps, sides);
     if (lds > kMaxDynamicLds) return SQ_ERR_SHAPE;
     const int groups = (T + S::TPP - 1) / S::TPP;
     const int by_lds = (160 * 1024) / lds;
@@ -77,13 +79,13 @@ static sq_status launch_rotq_mfma_ring(const __half *X, int64_t ldx, int T, cons
     if (prepared == kRotqFp16Out) {
         auto kernel = rotate_fp16_mfma_kernel<N1, N2, OCC, QS_MAX, NSX, R1LDS>;
         if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return SQ_ERR_LAUNCH;
-        hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), lds, st, X, ldx, T, plan, R1, R2, xout, ldo);
+        hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), lds, st, X, ldx, T, plan, R1, R2, xout, ldo, sides);
         return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
     }
     auto kernel = prepared ? rotate_quantize_mfma_kernel<N1, N2, OCC, QS_MAX, NSX, R1LDS, true>
                            : rotate_quantize_mfma_kernel<N1, N2, OCC, QS_MAX, NSX, R1LDS, false>;
     if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return SQ_ERR_LAUNCH;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), lds, st, X, ldx, T, plan, R1, R2, Q, scales, xrot);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), lds, st, X, ldx, T, plan, R1, R2, Q, scales, xrot, sides);
     return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
@@ -110,7 +112,7 @@ static sq_status launch_rotq_mfma_qs(const __half *X, int64_t ldx, int T, const 
         // small enough.  The debug option SQ_DEBUG_ROTQ_R1_IN_REGISTERS forces the register variant.
         using S2 = RotqShape<N1, N2, 2, true>;
         const bool force_reg = debug_option(SQ_DEBUG_ROTQ_R1_IN_REGISTERS) != 0;
-        if (!force_reg && 2 * S2::lds_bytes((plan.n_qslots + 15) / 16) <= 160 * 1024)
+        if (!force_reg && 2 * S2::lds_bytes((plan.n_qslots + 15) / 16, 1) <= 160 * 1024)
             return launch_rotq_mfma_ring<N1, N2, QS_MAX, 2, 2, true>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st, prepared, xout, ldo);
     }
     return launch_rotq_mfma_ring<N1, N2, QS_MAX, 3, (MB <= 2) ? 2 : 1>(X, ldx, T, plan, R1, R2, Q, scales, xrot, st, prepared, xout, ldo);
