@@ -414,6 +414,8 @@ def main() -> int:
     ap.add_argument("--only-kernels", action="store_true",
                     help="run only the two kernels of --workload, each in queued batches (what the rocprofv3 "
                          "summaries under profiles/ are taken from)")
+    ap.add_argument("--only-weight-only", action="store_true",
+                    help="time only the weight-only setting (sq_rotate_fp16, sq_w4a16_gemm) on --workload")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run three plain 256 MiB device copies (known traffic: the scale for "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -451,6 +453,9 @@ def main() -> int:
         us = kernel_time(torch, B.single_launch, B.sets, args.steps, args.warmup)["mean_us"]
         print(json.dumps({"workload": cfg.name, "layer_us_single_launch": us, "ring_sets": B.sets,
                           "weight_stream_GBps": cfg.N * cfg.K / 2 / (us * 1e-6) / 1e9}))
+        return 0
+    if args.only_weight_only:
+        print(json.dumps({"weight_only_w4a16": measure_weight_only(cfg, torch, sq, synth, args.steps, args.warmup)}))
         return 0
     if args.only_kernels:
         B = LayerBuffers(cfg, torch, sq, synth)

@@ -9,7 +9,9 @@
 // "(x >> 4j) & 0x000F000F | 0x64006400" is the pair of halves (1024 + code_j + 8, 1024 + code_{j+4} + 8),
 // and one packed subtraction of 1032 leaves the codes themselves, exactly.  A dword therefore
 // yields its eight codes in the order 0 4 1 5 2 6 3 7; the activations of a 16-byte chunk are put
-// into the same order once, on their way into LDS, which a dot product does not see.
+// into the same order, which a dot product does not see.  Both happen once per element, on the way
+// into LDS (every tile row is read by two waves afterwards): the loop over a tile is then LDS reads
+// and MFMAs only.
 #include "sq_common.h"
 
 namespace sq {
@@ -17,7 +19,7 @@ namespace sq {
 namespace {
 
 constexpr int kBM = 128, kBN = 128, kBK = 64;      // block tile and codes per K tile
-constexpr int kXRow = kBK * 2, kWRow = kBK / 2;    // bytes of a tile row: activations, weight codes
+constexpr int kXRow = kBK * 2, kWRow = kBK / 2;    // bytes of a tile row in memory: activations, weight codes
 
 // halves 0..7 of a chunk -> order 0 4 1 5 2 6 3 7 (dword d holds halves 2d, 2d+1)
 __device__ __forceinline__ uint4 interleave_halves(const uint4 v)
@@ -43,17 +45,17 @@ __device__ __forceinline__ v8h widen_codes_f16(uint32_t w)
 }
 
 // Block tile 128 x 128, four waves of 64 x 64 (2 x 2 fragments of 32 x 32), K walked in tiles of 64
-// codes.  Tiles travel global -> registers -> LDS (the activations are reordered on the way), the
-// next tile's loads in flight while this one is multiplied; two LDS buffers, one barrier per tile.
-// Within a K tile lane half g takes codes 32g .. 32g + 31 and step s the eight codes 32g + 8s ..:
-// a lane then reads one 16-byte chunk of its weight row per tile and one chunk of its token row
-// per step.
+// codes.  Tiles travel global -> registers -> LDS (activations reordered, codes widened to fp16 on
+// the way), the next tile's loads in flight while this one is multiplied; two LDS buffers, one
+// barrier per tile.  Both operands sit in LDS as rows of eight 16-byte chunks (eight fp16 values
+// each), chunk c of row r at slot r * 8 + (c ^ (r & 7)).  Within a K tile lane half g takes codes
+// 32g .. 32g + 31 and step s the eight codes 32g + 8s ..: chunk 4g + s of its row, for both operands.
 __global__ __launch_bounds__(256, 2) void w4a16_gemm_kernel(
     const __half *__restrict__ X, int64_t ldx, int T, int K, const uint8_t *__restrict__ Qw,
     const float *__restrict__ sw, int N, __half *__restrict__ Y, int64_t ldy, int tiles_m, int tiles_n)
 {
-    __shared__ uint4 xs[2][kBM * kXRow / 16];      // chunk c of row r at slot r * 8 + (c ^ (r & 7))
-    __shared__ uint4 ws[2][kBN * kWRow / 16];      // chunk c of row r at slot r * 2 + c
+    __shared__ uint4 xs[2][kBM * 8];               // activations
+    __shared__ uint4 ws[2][kBN * 8];               // weight codes as fp16
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int l32 = lane & 31, g = lane >> 5, wm = wave >> 1, wn = wave & 1;
@@ -81,6 +83,10 @@ __global__ __launch_bounds__(256, 2) void w4a16_gemm_kernel(
         x_slot[u] = r * 8 + (ch ^ (r & 7));
     }
     const uint8_t *w_src = Qw + (int64_t)min(col0 + (tid >> 1), N - 1) * Kb + (tid & 1) * 16;
+    // the 32 codes of this thread's weight chunk become chunks 4 (tid & 1) .. + 3 of row tid >> 1
+    int w_slot[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) w_slot[u] = (tid >> 1) * 8 + ((4 * (tid & 1) + u) ^ ((tid >> 1) & 7));
 
     v16f acc[2][2];
 #pragma unroll
@@ -99,7 +105,9 @@ __global__ __launch_bounds__(256, 2) void w4a16_gemm_kernel(
     auto park = [&](int buf) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) xs[buf][x_slot[u]] = interleave_halves(xr[u]);
-        ws[buf][tid] = wr;
+        const uint32_t wd[4] = {wr.x, wr.y, wr.z, wr.w};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) ws[buf][w_slot[u]] = __builtin_bit_cast(uint4, widen_codes_f16(wd[u]));
     };
 
     const int ktiles = K / kBK;
@@ -109,9 +117,6 @@ __global__ __launch_bounds__(256, 2) void w4a16_gemm_kernel(
     for (int kt = 0; kt < ktiles; ++kt) {
         const int buf = kt & 1;
         if (kt + 1 < ktiles) fetch(kt + 1);
-        uint4 wq[2];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) wq[j] = ws[buf][(wn * 64 + 32 * j + l32) * 2 + g];
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             v8h a[2], b[2];
@@ -121,8 +126,10 @@ __global__ __launch_bounds__(256, 2) void w4a16_gemm_kernel(
                 a[i] = __builtin_bit_cast(v8h, xs[buf][r * 8 + ((4 * g + s) ^ (r & 7))]);
             }
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-                b[j] = widen_codes_f16(s == 0 ? wq[j].x : s == 1 ? wq[j].y : s == 2 ? wq[j].z : wq[j].w);
+            for (int j = 0; j < 2; ++j) {
+                const int r = wn * 64 + 32 * j + l32;
+                b[j] = __builtin_bit_cast(v8h, ws[buf][r * 8 + ((4 * g + s) ^ (r & 7))]);
+            }
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
