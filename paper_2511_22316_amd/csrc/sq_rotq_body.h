@@ -128,7 +128,14 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int tok_slot = wave / NCB, cb = wave % NCB;        // which token of the pass, which columns
     const int l32 = lane & 31, g = lane >> 5;
-    const bool lead = (cb == 0);                             // this wave loads and Givens-rotates its token
+    // The waves of a token take turns as the owner of its rows: the owner of row r (the r-th row this
+    // workgroup handles for the token slot) requests it from memory and later applies the Givens
+    // list to it.  A fixed owner would have about twice the work of the others -- the row requests
+    // cost a wave some tens of ns each to issue, the list several LDS round trips -- and, being
+    // wave 0 of every workgroup, would share one SIMD with the owners of the CU's other workgroups
+    // while the other three SIMDs wait at the barrier.
+    auto owns = [&](int r) { return cb == r % NCB; };
+    const bool lead = owns(0);                               // owner of the first row: the prologue's extra work
 
     // Every scalar argument the kernel will need is fetched here, in one batch.  Left to the
     // compiler, each is loaded in front of its first use, and the prologue waits for five scalar
@@ -146,7 +153,7 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
     const int groups = (T + TPP - 1) / TPP;
     // does this wave's token exist in group grp (the last group may be partial)?
     auto has_row = [&](int grp) { return (int64_t)grp * TPP + tok_slot < T; };
-    // lead wave: all loads of its token row of group `grp` into ring slot `slot`
+    // a row's owner: all loads of its token row of group `grp` into ring slot `slot`
     auto issue_row = [&](int grp, int slot) {
         if (has_row(grp)) {
             const __half *row = X + ((int64_t)grp * TPP + tok_slot) * ldx;
@@ -201,7 +208,7 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
     // declared here, filled in once the plan entries have arrived
     int my_level = -1, gs_tile[2] = {-1, -1}, gs_lo[2] = {0, 0};
 
-    // lead wave: Givens list on the tile in ring slot `slot`; fills side tile `side` (0 / 1: the two
+    // a row's owner: Givens list on the tile in ring slot `slot`; fills side tile `side` (0 / 1: the two
     // alternate from token to token, so that the list of the token after next can be applied while
     // stage A of the next one may still be reading its side tile)
     auto givens = [&](int slot, int side) {
@@ -448,10 +455,8 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
         }
     }
 
-    if (lead) {
-        issue_row(g0 + stride, 1);
-        if (NSX == 3) issue_row(g0 + 2 * stride, 2);
-    }
+    if (owns(1)) issue_row(g0 + stride, 1);
+    if (NSX == 3 && owns(2)) issue_row(g0 + 2 * stride, 2);
 
     // LDS byte offsets of this lane's operand chunks inside a tile (row block 0): the swizzle
     // only touches the low bits of the chunk index, so four offsets cover every step
@@ -506,20 +511,21 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
 
     // Barriers per token: one (B2), behind which the token maximum, the rotated next tile and its
     // side tile are visible.  Nothing else is shared between waves: codes leave from registers, and
-    // what a wave writes ahead of B2 of one iteration (its maximum, the lead wave's side tile) goes
+    // what a wave writes ahead of B2 of one iteration (its maximum, the owner's side tile) goes
     // into the copy that nobody can still be reading, because the two copies alternate from token
     // to token and every wave has passed the previous B2 since the last use.  With a ring of two
     // tiles a second barrier per token (B3) protects the tile that is refilled right behind it,
     // and with a single side tile per token slot (very long lists on the largest shapes) the
     // side tile that the next list overwrites.
     int slot = 0, par = 0;                 // ring slot and parity (side tile, maxima) of the current token
-    for (int grp = g0; grp < groups; grp += stride) {
+    int it = 0;                            // rows of this token slot done so far: the current row's number
+    for (int grp = g0; grp < groups; grp += stride, ++it) {
         const int t = grp * TPP + tok_slot;
         const bool live = t < T;
         const int slot1 = (slot + 1 == NSX) ? 0 : slot + 1;
         // ring of two: the tile of this token went through stage A an iteration ago (every wave
         // has passed the barrier that ended it), so the row after next can start now
-        if (NSX == 2 && lead) issue_row(grp + 2 * stride, slot);
+        if (NSX == 2 && owns(it + 2)) issue_row(grp + 2 * stride, slot);
 
         // ---- power-of-two prescale of this wave's columns so that hi/lo fit fp16 -------------
         // Stage B contracts over rows p within a column, so a per-wave factor commutes with it.
@@ -608,16 +614,17 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
             if (lane == 0) red[cb] = amax;
         }
 
-        // ---- lead wave: the next row has landed (rows complete in order; only the row after it
-        // may still be in flight) -> rotate its touched channels
-        if (lead) {
-            if (has_row(grp + 2 * stride)) wait_loads_le<LPT>();
+        // ---- owner of the next row: the row has landed -> rotate its touched channels.  With one
+        // wave per token the owner also requested the row after it, which may still be in flight
+        // (rows complete in order); with turns, every other request of this wave is older.
+        if (owns(it + 1)) {
+            if (NCB == 1 && has_row(grp + 2 * stride)) wait_loads_le<LPT>();
             else wait_loads_le<0>();
             if (has_row(grp + stride)) givens(slot1, par ^ 1);
         }
         __syncthreads();     // B2: maxima visible; next tile and its side tile rotated
         // stage A of this token ran an iteration ago, so its ring slot is free for the row after next
-        if (NSX == 3 && lead) issue_row(grp + 3 * stride, slot);
+        if (NSX == 3 && owns(it + 3)) issue_row(grp + 3 * stride, slot);
 
         float inv = fz_inv;                    // F16OUT: Y = accy * fz_inv
         if constexpr (!F16OUT) {
@@ -626,7 +633,7 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
             for (int w = 1; w < NCB; ++w) amax = fmaxf(amax, red[w]);
             const float step = (amax == 0.f) ? 1.0f : amax / 7.0f;
             inv = fz_inv / step;               // codes = Y / step with Y = accy * fz_inv
-            if (live && lead && lane == 0) scales[t] = step;
+            if (live && cb == 0 && lane == 0) scales[t] = step;
         }
         if (!F16OUT && xrot != nullptr && live) {
 #pragma unroll
