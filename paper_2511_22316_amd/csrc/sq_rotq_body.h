@@ -47,11 +47,17 @@ __device__ __forceinline__ void split_pair(float z0, float z1, uint32_t &hi, uin
     lo = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(r0, r1));
 }
 
+// max(m, |a[0]|, ..., |a[15]|), as four independent chains of two steps each (one long chain of
+// dependent maxima costs a wave its issue latency sixteen times over)
 __device__ __forceinline__ float max_abs16(const v16f &a, float m)
 {
+    float c[4];
 #pragma unroll
-    for (int e = 0; e < 16; e += 2) m = fmaxf(m, fmaxf(fabsf(a[e]), fabsf(a[e + 1])));
-    return m;
+    for (int k = 0; k < 4; ++k) {
+        c[k] = fmaxf(fabsf(a[4 * k]), fmaxf(fabsf(a[4 * k + 1]), fabsf(a[4 * k + 2])));
+        c[k] = fmaxf(c[k], fabsf(a[4 * k + 3]));
+    }
+    return fmaxf(fmaxf(m, c[0]), fmaxf(fmaxf(c[1], c[2]), c[3]));
 }
 
 }  // namespace
