@@ -33,16 +33,15 @@ the rank order of the URT over the reals.
 Close calls.  Multi-step ART produces them by itself: a massive entry a rotated against a tiny
 entry b leaves a (1 + b^2 / 2a^2) / sqrt(2) in both channels, so the halves of two outliers, or
 of one outlier met twice, differ only in their 13th to 16th digit, and which of them is "the
-largest" next is then not a property of the method but of the last bits.  ``art_select``
-(With a = 19712 and b = 1e-4 the difference is below fp64 resolution altogether: two such halves
-come out "equal" or not depending on how the square root was evaluated.)  ``art_select``
-therefore reports its closest call (``margin``: the smallest relative distance between a winner
+largest" next is then not a property of the method but of the last bits.  (With a = 19712 and
+b = 1e-4 the difference is below fp64 resolution altogether: two such halves come out "equal" or
+not depending on how the square root was evaluated.)  ``art_select`` therefore reports its closest call (``margin``: the smallest relative distance between a winner
 and the best candidate that is not tied with it by construction -- equal inputs, or the two
 outputs of one step, which the index rule decides in any arithmetic), and it can be told to
 ``follow`` another implementation's choices: a followed choice is accepted if it is the oracle's
 own or if its magnitude lies within the relative ``band`` of the oracle's winner and is not a
-tie by construction, and is counted as a departure; any other choice raises.  The rank order of the URT has a margin of its own
-(``rank_margin``).
+tie by construction, and is counted as a departure; any other choice raises.  The rank order
+of the URT has a margin of its own (``rank_margin``).
 """
 from __future__ import annotations
 
