@@ -203,9 +203,15 @@ sq_status sq_w4a16_gemm(const void *X, int64_t T, int32_t K, int64_t ldx,
  *              workgroups with the lowest indices rotate the tokens and the
  *              others wait for them; the bound is what a dispatch order other
  *              than lowest-index-first would run into.)
- * On one MI355X the call takes as long as the two calls it replaces (33.9 us
- * against 33.8 us at T = 8, K = 8192, N = 28672): what it saves is one host
- * call per layer.
+ * The only benefit of this entry point is one host call per layer instead of
+ * two.  It saves no GPU time: on one MI355X the single launch takes slightly
+ * longer than the two launches it replaces (35.6 us against 33.8 us at T = 8,
+ * K = 8192, N = 28672), because the multiplying workgroups wait for the
+ * rotating ones across the chip and then read the codes with agent-coherent
+ * loads (the writers release their stores at agent scope; the readers' loads
+ * bypass their own caches, so that no stale line can be returned and nothing
+ * has to be invalidated).  Use it where the host's launch path is the bound
+ * (a handful of tokens on small layers), otherwise use the two calls.
  * Needs at least as many blocks of 32 (N < 16384) or 64 output channels as there
  * are token groups (N >= 32 T is always enough), else SQ_ERR_SHAPE.
  */

@@ -29,6 +29,12 @@ def test_library_exports_every_declared_symbol(lib):
     assert {"sq_rotate_quantize", "sq_w4a4_gemm", "sq_prepare_weights", "sq_status_string"} <= declared
     for name in declared:
         assert hasattr(lib, name), f"{name} is declared in singlequant.h but not exported"
+    # and the other way round: no C symbol of the library's own prefix without a declaration
+    import subprocess
+    table = subprocess.run(["nm", "-D", "--defined-only", sq.library_path()], capture_output=True, text=True,
+                           check=True).stdout
+    exported = {line.split()[-1] for line in table.splitlines() if line.split()[-1].startswith("sq_")}
+    assert exported and exported <= declared, f"exported but not declared: {sorted(exported - declared)}"
 
 
 def test_status_strings(lib):
