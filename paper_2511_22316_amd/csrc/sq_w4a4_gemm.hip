@@ -452,20 +452,32 @@ __global__ __launch_bounds__(KG *WM *WN *kWave, OCC) void w4a4_gemm_kernel(
 // Skinny kernel (T <= 32*FM <= 64, K % 256 == 0): the decode-shaped product, bound by the one
 // pass over the weights.  A workgroup owns 32*FN output channels and all tokens; its NW waves
 // split K between them (256-code slices dealt round-robin) and add their partial accumulators
-// through LDS at the end.  Operands go straight from global memory to registers: a lane reads 64
-// contiguous bytes of its row per slice as four 16-byte loads, so each wave-wide group of four
+// through LDS at the end.  The weights go straight from global memory to registers: a lane reads
+// 64 contiguous bytes of its row per slice as four 16-byte loads, so each wave-wide group of four
 // loads consumes whole 128-byte lines, and the loads of the next slice are in flight while this
 // one is multiplied.
+// The tokens' codes are the same for every workgroup and come out of L2, but loaded like the
+// weights they are a third of all vector-memory instructions (2.2 of 27.5 us at T = 8, K = 8192,
+// N = 28672).  ALDS: when all T rows fit, each workgroup copies them into LDS once (global -> LDS,
+// behind the request for its first weight slice) and the waves read their operand chunks from
+// there; rows are padded by 16 bytes so that the rows a wave reads together fall into different
+// banks.
 // ------------------------------------------------------------------------------------------
-template <int FM, int FN, int NW>
+constexpr int kSkinnyRowPad = 16;      // bytes between the token rows in LDS beyond their length
+
+template <int FM, int FN, int NW, bool ALDS>
 __global__ __launch_bounds__(NW *kWave) void w4a4_gemm_skinny_kernel(
     const uint8_t *__restrict__ Qx, const float *__restrict__ sx, int T, int Kb,
     const uint8_t *__restrict__ Qw, const float *__restrict__ sw, int N, __half *__restrict__ Y,
     int64_t ldy, int32_t *__restrict__ acc_dbg)
 {
     constexpr int BN = 32 * FN, SLICE = 128;        // bytes of a row per slice (256 codes)
-    static_assert(NW * FM * FN * 16 * kWave * 4 <= 64 * 1024, "partial sums must fit in static LDS");
-    __shared__ int red[NW][FM][FN][16][kWave];
+    static_assert(NW * FM * FN * 16 * kWave * 4 <= 64 * 1024, "partial sums must fit in LDS");
+    static_assert(!ALDS || FM == 1, "token rows in LDS: one token block");
+    // ALDS: the dynamic LDS holds the token rows during the loop and the partial sums after it
+    __shared__ int red_static[ALDS ? 1 : NW][FM][FN][16][kWave];
+    extern __shared__ uint4 dyn[];
+    int(*red)[FM][FN][16][kWave] = ALDS ? reinterpret_cast<int(*)[FM][FN][16][kWave]>(dyn) : red_static;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const int l32 = lane & 31, g = lane >> 5;
     const int col0 = blockIdx.x * BN;
@@ -486,26 +498,34 @@ __global__ __launch_bounds__(NW *kWave) void w4a4_gemm_skinny_kernel(
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
 
-    uint4 ra[2][FM][4], rb[2][FN][4];
+    uint4 ra[ALDS ? 1 : 2][FM][4], rb[2][FN][4];
     const int slices = Kb / SLICE;
+    const int a_stride = Kb + kSkinnyRowPad;
+    const char *a_lds = reinterpret_cast<const char *>(dyn) + min(l32, T - 1) * a_stride + g * 64;
 #define SQ_SKINNY_FETCH(BUF, S)                                                                      \
     do {                                                                                             \
         const int off_ = (S) * SLICE;                                                                \
         _Pragma("unroll") for (int j = 0; j < FN; ++j)                                               \
             _Pragma("unroll") for (int c = 0; c < 4; ++c)                                            \
                 rb[BUF][j][c] = *reinterpret_cast<const uint4 *>(b_ptr[j] + off_ + 16 * c);          \
-        _Pragma("unroll") for (int i = 0; i < FM; ++i)                                               \
-            _Pragma("unroll") for (int c = 0; c < 4; ++c)                                            \
-                ra[BUF][i][c] = *reinterpret_cast<const uint4 *>(a_ptr[i] + off_ + 16 * c);          \
+        if constexpr (!ALDS) {                                                                       \
+            _Pragma("unroll") for (int i = 0; i < FM; ++i)                                           \
+                _Pragma("unroll") for (int c = 0; c < 4; ++c)                                        \
+                    ra[BUF][i][c] = *reinterpret_cast<const uint4 *>(a_ptr[i] + off_ + 16 * c);      \
+        }                                                                                            \
     } while (0)
-#define SQ_SKINNY_MULTIPLY(BUF)                                                                      \
+#define SQ_SKINNY_MULTIPLY(BUF, S)                                                                   \
     do {                                                                                             \
+        if constexpr (ALDS) {                                                                        \
+            _Pragma("unroll") for (int c = 0; c < 4; ++c)                                            \
+                ra[0][0][c] = *reinterpret_cast<const uint4 *>(a_lds + (S) * SLICE + 16 * c);        \
+        }                                                                                            \
         _Pragma("unroll") for (int c = 0; c < 4; ++c) {                                              \
             v4i b0[FN], b1[FN];                                                                      \
             _Pragma("unroll") for (int j = 0; j < FN; ++j) widen_chunk(rb[BUF][j][c], b0[j], b1[j]); \
             _Pragma("unroll") for (int i = 0; i < FM; ++i) {                                         \
                 v4i a0, a1;                                                                          \
-                widen_chunk(ra[BUF][i][c], a0, a1);                                                  \
+                widen_chunk(ra[ALDS ? 0 : BUF][i][c], a0, a1);                                       \
                 _Pragma("unroll") for (int j = 0; j < FN; ++j) {                                     \
                     acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, b0[j], acc[i][j], 0, 0, 0); \
                     acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, b1[j], acc[i][j], 0, 0, 0); \
@@ -517,18 +537,33 @@ __global__ __launch_bounds__(NW *kWave) void w4a4_gemm_skinny_kernel(
     // wave w takes slices w, w+NW, w+2NW, ...; two register sets alternate
     int S = wave;
     if (S < slices) SQ_SKINNY_FETCH(0, S);
+    if constexpr (ALDS) {
+        // token rows -> LDS, 1 KB per wave-wide load, behind the first weight request (which has
+        // the longer way to go); visible to every wave after the barrier
+        const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)dyn;
+        const int parts = (Kb + 1023) / 1024;
+        for (int idx = wave; idx < T * parts; idx += NW) {
+            const int row = idx / parts, part = idx - row * parts;
+            if (part * 1024 + lane * 16 < Kb)
+                load_to_lds_16(Qx + (int64_t)row * Kb + part * 1024 + lane * 16,
+                               __builtin_amdgcn_readfirstlane(lds_base + row * a_stride + part * 1024));
+        }
+        wait_vmcnt<0>();
+        __syncthreads();
+    }
     while (S < slices) {
         if (S + NW < slices) SQ_SKINNY_FETCH(1, S + NW);
-        SQ_SKINNY_MULTIPLY(0);
+        SQ_SKINNY_MULTIPLY(0, S);
         S += NW;
         if (S >= slices) break;
         if (S + NW < slices) SQ_SKINNY_FETCH(0, S + NW);
-        SQ_SKINNY_MULTIPLY(1);
+        SQ_SKINNY_MULTIPLY(1, S);
         S += NW;
     }
 #undef SQ_SKINNY_FETCH
 #undef SQ_SKINNY_MULTIPLY
 
+    if constexpr (ALDS) __syncthreads();        // every wave is done with the token rows: the sums take their place
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -674,8 +709,20 @@ static sq_status launch_skinny(const uint8_t *Qx, const float *sx, int T, int K,
                                const float *sw, int N, __half *Y, int64_t ldy, int32_t *acc_dbg,
                                hipStream_t st)
 {
-    hipLaunchKernelGGL((w4a4_gemm_skinny_kernel<FM, FN, NW>), dim3((unsigned)((N + 32 * FN - 1) / (32 * FN))),
-                       dim3(NW * kWave), 0, st, Qx, sx, T, K / 2, Qw, sw, N, Y, ldy, acc_dbg);
+    const dim3 grid((unsigned)((N + 32 * FN - 1) / (32 * FN))), block(NW * kWave);
+    // token rows in LDS where they fit 64 KB (and two workgroups a CU)
+    const size_t rows_bytes = (size_t)T * (K / 2 + kSkinnyRowPad), sums_bytes = (size_t)NW * FM * FN * 16 * kWave * 4;
+    // (sixteen waves have two slices each at K = 8192: the wait for the rows costs them more than it saves)
+    if constexpr (FM == 1 && NW <= 8) {
+        if (rows_bytes <= 64 * 1024) {
+            hipLaunchKernelGGL((w4a4_gemm_skinny_kernel<FM, FN, NW, true>), grid, block,
+                               rows_bytes > sums_bytes ? rows_bytes : sums_bytes, st, Qx, sx, T, K / 2, Qw, sw, N, Y,
+                               ldy, acc_dbg);
+            return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+        }
+    }
+    hipLaunchKernelGGL((w4a4_gemm_skinny_kernel<FM, FN, NW, false>), grid, block, 0, st, Qx, sx, T, K / 2, Qw, sw, N,
+                       Y, ldy, acc_dbg);
     return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
@@ -727,7 +774,10 @@ extern "C" sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T,
         choice = (N >= 64 * 384 && Ti > 32) ? 11 : 10;
         if (choice == 11 && N <= 128 * 256 && two_k_groups) choice = 15;
     }
-    if (choice < 0 && Ti <= 32) choice = (N >= 64 * 384) ? 8 : (N >= 10240 ? 9 : 7);
+    // (with the token rows in LDS -- they fit up to 64 KB -- eight waves on 32 channels beat four waves on 64:
+    // T = 8, K = 8192, N = 28672 27.1 against 27.4 us, and 27.6 us for the latter without the rows in LDS)
+    const bool rows_fit_lds = (int64_t)Ti * (K / 2 + sq::kSkinnyRowPad) <= 64 * 1024;
+    if (choice < 0 && Ti <= 32) choice = (N >= 64 * 384 && !rows_fit_lds) ? 8 : (N >= 10240 ? 9 : 7);
     if (choice < 0 && Ti <= 64) choice = 13;
     // Few tokens times few output channels: even 128x128 tiles would be too few for 256 CUs, and the
     // time is one workgroup's walk over K.  64x64 tiles (four times as many workgroups) up to 64

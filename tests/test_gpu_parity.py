@@ -307,6 +307,10 @@ def test_rounding_ties_go_up(oracle, n1, n2, delta):
                                    # at most 32 tokens: the decode-shaped kernel in its three launch
                                    # shapes, one K slice only / ragged channel tails / T = 32
                                    (1, 256, 33), (32, 768, 8200), (16, 512, 10300), (31, 512, 24600), (33, 512, 300),
+                                   # ... with the token rows held in LDS over several 1 KB pieces
+                                   # (15 rows of 4 KB are the most that fit) and without (too many rows)
+                                   (8, 8192, 25000), (15, 8192, 700), (5, 2304, 12000), (16, 8192, 700), (32, 8192, 300),
+                                   (20, 4096, 10300),
                                    # 33..64 tokens: the same kernel with two token blocks (few
                                    # channels) or 64x64 tiles (many); 65..128 tokens: 64x64 tiles
                                    (64, 768, 16500), (48, 512, 300), (40, 512, 30000), (20, 256, 25000),
