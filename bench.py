@@ -319,6 +319,9 @@ def measure_weight_only(cfg, torch, sq, synth, steps, warmup):
            "gemm_us": g["mean_us"], "gemm_TFLOPS": flops / (g["mean_us"] * 1e-6) / 1e12,
            "gemm_frac_of_fp16_peak": flops / (g["mean_us"] * 1e-6) / 1e12 / FP16_MFMA_PEAK_TFLOPS,
            "ring_sets": B.sets}
+    if T <= 32:      # decode-shaped: one pass over the weight codes, HBM-bound
+        out["gemm_weight_stream_GBps"] = N * K / 2.0 / (g["mean_us"] * 1e-6) / 1e9
+        out["gemm_frac_of_hbm_peak"] = out["gemm_weight_stream_GBps"] / HBM_PEAK_GBPS
     del B, Xr
     torch.cuda.empty_cache()
     return out

@@ -156,6 +156,102 @@ __global__ __launch_bounds__(256, 2) void w4a16_gemm_kernel(
     }
 }
 
+// Decode-shaped kernel (T <= 32, K % 256 == 0): the product is one pass over the weight codes,
+// 117 MB for 8 tokens at K = 8192, N = 28672, and the tile kernel above would walk K in 224
+// workgroups one tile at a time.  Here a workgroup owns 16 NS output channels and one block of 16
+// tokens (v_mfma_f32_16x16x32_f16: lane = token or channel l % 16, its quarter q = l / 16 of the
+// 32 contraction indices of a step); its NW waves split K in slices of 256 codes dealt round-robin
+// and add their partial sums through LDS at the end.  Both operands go global -> registers, the
+// next slice in flight while this one is multiplied.  Per slice a lane reads the 64 codes
+// [64 q, 64 q + 64) of its channel rows (two 16-byte loads each, so that the four quarters of a
+// wave consume whole 128-byte lines) and the same 64 activations of its token (128 contiguous
+// bytes); dword d of chunk c, widened, is the operand of step (c, d), against the activations
+// 32 c + 8 d .. + 7 of the lane's 64, put into the order 0 4 1 5 2 6 3 7 the widening produces.
+template <int NS, int NW>
+__global__ __launch_bounds__(NW *kWave) void w4a16_gemm_skinny_kernel(
+    const __half *__restrict__ X, int64_t ldx, int T, int K, const uint8_t *__restrict__ Qw,
+    const float *__restrict__ sw, int N, __half *__restrict__ Y, int64_t ldy)
+{
+    constexpr int BN = 16 * NS;
+    static_assert(NW * NS * 4 * kWave * 4 <= 64 * 1024, "partial sums must fit in static LDS");
+    __shared__ float red[NW][NS][4][kWave];
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+    const int l16 = lane & 15, q = lane >> 4;
+    const int col0 = blockIdx.x * BN, t0 = blockIdx.y * 16, Kb = K / 2;
+
+    // rows past the ends are clamped: their products are never stored
+    const __half *a_ptr = X + (int64_t)min(t0 + l16, T - 1) * ldx + q * 64;
+    const uint8_t *b_ptr[NS];
+#pragma unroll
+    for (int j = 0; j < NS; ++j) b_ptr[j] = Qw + (int64_t)min(col0 + 16 * j + l16, N - 1) * Kb + q * 32;
+
+    v4f acc[NS];
+#pragma unroll
+    for (int j = 0; j < NS; ++j) acc[j] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    uint4 ra[2][8], rb[2][NS][2];
+    const int slices = K / 256;
+#define SQ_W16_FETCH(BUF, S)                                                                         \
+    do {                                                                                             \
+        _Pragma("unroll") for (int j = 0; j < NS; ++j)                                               \
+            _Pragma("unroll") for (int c = 0; c < 2; ++c)                                            \
+                rb[BUF][j][c] = *reinterpret_cast<const uint4 *>(b_ptr[j] + (S) * 128 + 16 * c);     \
+        _Pragma("unroll") for (int u = 0; u < 8; ++u)                                                \
+            ra[BUF][u] = *reinterpret_cast<const uint4 *>(a_ptr + (S) * 256 + 8 * u);                \
+    } while (0)
+#define SQ_W16_MULTIPLY(BUF)                                                                         \
+    do {                                                                                             \
+        _Pragma("unroll") for (int c = 0; c < 2; ++c)                                                \
+            _Pragma("unroll") for (int d = 0; d < 4; ++d) {                                          \
+                const v8h a = __builtin_bit_cast(v8h, interleave_halves(ra[BUF][4 * c + d]));        \
+                _Pragma("unroll") for (int j = 0; j < NS; ++j) {                                     \
+                    const uint4 w4 = rb[BUF][j][c];                                                  \
+                    const uint32_t w = d == 0 ? w4.x : d == 1 ? w4.y : d == 2 ? w4.z : w4.w;         \
+                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, widen_codes_f16(w), acc[j], 0, 0, 0); \
+                }                                                                                    \
+            }                                                                                        \
+    } while (0)
+
+    // wave w takes slices w, w + NW, w + 2 NW, ...; two register sets alternate
+    int S = wave;
+    if (S < slices) SQ_W16_FETCH(0, S);
+    while (S < slices) {
+        if (S + NW < slices) SQ_W16_FETCH(1, S + NW);
+        SQ_W16_MULTIPLY(0);
+        S += NW;
+        if (S >= slices) break;
+        if (S + NW < slices) SQ_W16_FETCH(0, S + NW);
+        SQ_W16_MULTIPLY(1);
+        S += NW;
+    }
+#undef SQ_W16_FETCH
+#undef SQ_W16_MULTIPLY
+
+#pragma unroll
+    for (int j = 0; j < NS; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) red[wave][j][r][lane] = acc[j][r];
+    __syncthreads();
+    // 16 x 16 accumulator layout: lane holds channel l % 16, register r holds token 4 (l / 16) + r
+    for (int idx = tid; idx < NS * 4 * kWave; idx += NW * kWave) {
+        const int ln = idx & (kWave - 1), r = (idx >> 6) & 3, j = idx >> 8;
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) sum += red[w][j][r][ln];
+        const int t = t0 + 4 * (ln >> 4) + r, n = col0 + 16 * j + (ln & 15);
+        if (t < T && n < N) Y[(int64_t)t * ldy + n] = __float2half_rn(sum * sw[n]);
+    }
+}
+
+template <int NS, int NW>
+sq_status launch_w4a16_skinny(const __half *X, int64_t ldx, int T, int K, const uint8_t *Qw, const float *sw, int N,
+                              __half *Y, int64_t ldy, hipStream_t st)
+{
+    hipLaunchKernelGGL((w4a16_gemm_skinny_kernel<NS, NW>), dim3((unsigned)((N + 16 * NS - 1) / (16 * NS)), (unsigned)((T + 15) / 16)),
+                       dim3(NW * kWave), 0, st, X, ldx, T, K, Qw, sw, N, Y, ldy);
+    return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+}
+
 }  // namespace
 
 }  // namespace sq
@@ -169,6 +265,16 @@ extern "C" sq_status sq_w4a16_gemm(const void *X, int64_t T, int32_t K, int64_t 
     if (!X || !Qw || !sw || !Y) return SQ_ERR_NULL;
     if (((uintptr_t)X & 15) || (ldx % 8) != 0 || ((uintptr_t)Qw & 15) || ((uintptr_t)Y & 1) || ((uintptr_t)sw & 3))
         return SQ_ERR_ALIGN;
+    // At most 32 tokens: one pass over the weights (two token blocks above 16 tokens read them twice,
+    // the second time mostly out of the caches; beyond that the tile kernel is the better choice).
+    // Launch shapes as in the W4A4 decode-shaped kernel: about eight waves on every CU.
+    if (T <= 32 && (K % 256) == 0) {
+        const hipStream_t st = static_cast<hipStream_t>(stream);
+        const __half *Xh = static_cast<const __half *>(X);
+        __half *Yh = static_cast<__half *>(Y);
+        if (N >= 64 * 384) return sq::launch_w4a16_skinny<4, 4>(Xh, ldx, (int)T, K, Qw, sw, N, Yh, ldy, st);
+        return sq::launch_w4a16_skinny<2, 8>(Xh, ldx, (int)T, K, Qw, sw, N, Yh, ldy, st);
+    }
     const int tiles_m = (int)((T + sq::kBM - 1) / sq::kBM), tiles_n = (N + sq::kBN - 1) / sq::kBN;
     hipLaunchKernelGGL(sq::w4a16_gemm_kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0,
                        static_cast<hipStream_t>(stream), static_cast<const __half *>(X), ldx, (int)T, K, Qw, sw, N,

@@ -96,7 +96,12 @@ def check_w4a16(Yg, Yo, m, K):
 
 
 @pytest.mark.parametrize("T,K,N", [(1, 64, 1), (16, 512, 512), (77, 128, 300), (130, 320, 257), (300, 2048, 130),
-                                   (256, 4096, 384), (129, 64, 129)])
+                                   (256, 4096, 384), (129, 64, 129),
+                                   # at most 32 tokens and K % 256 == 0: the decode-shaped kernel, both launch
+                                   # shapes, one and two token blocks, ragged channel tails, one slice only;
+                                   # K % 256 != 0: the tile kernel on few tokens
+                                   (8, 1024, 24700), (32, 768, 10300), (20, 256, 50), (16, 8192, 300), (17, 2048, 33),
+                                   (1, 4096, 4096), (16, 320, 100)])
 def test_w4a16_gemm_random_operands(oracle, T, K, N):
     print(f"case w4a16 gemm random T={T} K={K} N={N}", flush=True)
     g = np.random.default_rng(T + 3 * K + 5 * N)
