@@ -5,31 +5,52 @@
 
 namespace sq {
 
-// 64 x 64 tile through LDS: 8-byte reads along n, 8-byte writes along k.  The LDS row stride of
-// 66 halves keeps both the row-wise writes and the column-wise reads spread over the banks.
+// 64 x 64 tile through LDS.  Tiles that lie inside the matrix move in 8-byte accesses on both
+// sides (four halves along n in, four halves along k out) when the pointers and leading dimensions
+// allow it (vec); edge tiles and unaligned matrices go element by element with bounds checks.
+// The LDS row stride of 66 halves keeps both the row-wise writes and the column-wise reads spread
+// over the banks.
 __global__ __launch_bounds__(256) void transpose_fp16_kernel(const __half *__restrict__ W, int K, int N,
-                                                             int64_t ldw, __half *__restrict__ Wt)
+                                                             int64_t ldw, __half *__restrict__ Wt, int vec)
 {
     constexpr int TILE = 64, LD = TILE + 2;
     __shared__ __half tile[TILE * LD];
     const int k0 = blockIdx.y * TILE, n0 = blockIdx.x * TILE;
     const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;       // 16 x 16 threads, 4 elements each
+    const bool fast = vec && k0 + TILE <= K && n0 + TILE <= N;    // the same for the whole block
+    if (fast) {
 #pragma unroll
-    for (int pass = 0; pass < 4; ++pass) {
-        const int k = k0 + ty + 16 * pass, n = n0 + 4 * tx;
+        for (int pass = 0; pass < 4; ++pass) {
+            const int kl = ty + 16 * pass;
+            const uint2 v = *reinterpret_cast<const uint2 *>(W + (int64_t)(k0 + kl) * ldw + n0 + 4 * tx);
+            uint32_t *dst = reinterpret_cast<uint32_t *>(tile + kl * LD + 4 * tx);      // 4-byte aligned: LD, 4 tx even
+            dst[0] = v.x;
+            dst[1] = v.y;
+        }
+    } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-            tile[(ty + 16 * pass) * LD + 4 * tx + e] =
-                (k < K && n + e < N) ? W[(int64_t)k * ldw + n + e] : __float2half(0.f);
+        for (int pass = 0; pass < 4; ++pass) {
+            const int k = k0 + ty + 16 * pass, n = n0 + 4 * tx;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                tile[(ty + 16 * pass) * LD + 4 * tx + e] =
+                    (k < K && n + e < N) ? W[(int64_t)k * ldw + n + e] : __float2half(0.f);
+        }
     }
     __syncthreads();
+    const uint16_t *t16 = reinterpret_cast<const uint16_t *>(tile);
 #pragma unroll
     for (int pass = 0; pass < 4; ++pass) {
-        const int n = n0 + ty + 16 * pass, k = k0 + 4 * tx;
-        if (n >= N) continue;
+        const int nl = ty + 16 * pass, n = n0 + nl, k = k0 + 4 * tx;
+        if (fast) {
+            const uint32_t lo = t16[(4 * tx) * LD + nl] | ((uint32_t)t16[(4 * tx + 1) * LD + nl] << 16);
+            const uint32_t hi = t16[(4 * tx + 2) * LD + nl] | ((uint32_t)t16[(4 * tx + 3) * LD + nl] << 16);
+            *reinterpret_cast<uint2 *>(Wt + (int64_t)n * K + k) = uint2{lo, hi};
+        } else if (n < N) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if (k + e < K) Wt[(int64_t)n * K + k + e] = tile[(4 * tx + e) * LD + ty + 16 * pass];
+            for (int e = 0; e < 4; ++e)
+                if (k + e < K) Wt[(int64_t)n * K + k + e] = tile[(4 * tx + e) * LD + nl];
+        }
     }
 }
 
@@ -54,7 +75,8 @@ extern "C" sq_status sq_prepare_weights(const void *W, int32_t K, int32_t N, int
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipLaunchKernelGGL(sq::transpose_fp16_kernel, dim3((unsigned)((N + 63) / 64), (unsigned)((K + 63) / 64)),
                        dim3(256), 0, st, static_cast<const __half *>(W), K, N, ldw,
-                       static_cast<__half *>(workspace));
+                       static_cast<__half *>(workspace),
+                       (((uintptr_t)W & 7) == 0 && (ldw % 4) == 0 && (K % 4) == 0) ? 1 : 0);
     if (hipGetLastError() != hipSuccess) return SQ_ERR_LAUNCH;
     return sq_rotate_quantize(workspace, N, K, K, giv_i, giv_j, giv_theta, P, R1, n1, R2, n2, Qw, sw, nullptr,
                               stream);
