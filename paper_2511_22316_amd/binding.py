@@ -116,6 +116,7 @@ SQ_DEBUG_ROTQ_RING = 1
 SQ_DEBUG_ROTQ_R1_IN_REGISTERS = 2
 SQ_DEBUG_ROTQ_PLAIN_KERNEL = 3
 SQ_DEBUG_DECODE_SPIN_LIMIT = 4
+SQ_DEBUG_W4A16_LAUNCH_SHAPE = 5
 
 
 def sq_debug_set_option(option: int, value: int) -> None:

@@ -233,8 +233,8 @@ def test_prepare_weights_argument_errors(lib):
 def test_debug_options(lib):
     lib.sq_debug_set_option.restype = C.c_int
     lib.sq_debug_set_option.argtypes = [C.c_int, C.c_int32]
-    assert lib.sq_debug_set_option(5, 1) == 2 and lib.sq_debug_set_option(-1, 1) == 2     # unknown options
-    for option in range(5):
+    assert lib.sq_debug_set_option(6, 1) == 2 and lib.sq_debug_set_option(-1, 1) == 2     # unknown options
+    for option in range(6):
         assert lib.sq_debug_set_option(option, 0) == 0
     # a forced shape never changes what is checked before the launch
     assert lib.sq_debug_set_option(0, 5) == 0 and _gemm(lib, K=48) == 2 and _gemm(lib, T=0) == 0
