@@ -5,21 +5,14 @@
 //
 //   Y[t, n] = fp16( sw[n] * sum_k X[t, k] * Qw[n, k] )        fp32 accumulation
 //
-// Codes are widened to fp16 in registers: with x = dword ^ 0x88888888 every nibble holds code + 8,
-// "(x >> 4j) & 0x000F000F | 0x64006400" is the pair of halves (1024 + code_j + 8, 1024 + code_{j+4} + 8),
-// and one packed subtraction of 1032 leaves the codes themselves, exactly.  A dword therefore
-// yields its eight codes in the order 0 4 1 5 2 6 3 7; the activations of a 16-byte chunk are put
-// into the same order, which a dot product does not see.  Both happen once per element, on the way
-// into LDS (every tile row is read by two waves afterwards): the loop over a tile is then LDS reads
-// and MFMAs only.
+// Two kernels: a tile kernel for many tokens (w4a16_gemm_ring_kernel) and a decode-shaped one for
+// at most 32 (w4a16_gemm_skinny_kernel).  Both widen the codes to fp16 in registers, exactly, with
+// the magic-number form described at the two widening functions below.
 #include "sq_common.h"
 
 namespace sq {
 
 namespace {
-
-constexpr int kBM = 128, kBN = 128, kBK = 64;      // block tile and codes per K tile
-constexpr int kXRow = kBK * 2, kWRow = kBK / 2;    // bytes of a tile row in memory: activations, weight codes
 
 // halves 0..7 of a chunk -> order 0 4 1 5 2 6 3 7 (dword d holds halves 2d, 2d+1)
 __device__ __forceinline__ uint4 interleave_halves(const uint4 v)
@@ -32,7 +25,11 @@ __device__ __forceinline__ uint4 interleave_halves(const uint4 v)
     return r;
 }
 
-// eight codes of a dword as fp16, in the order 0 4 1 5 2 6 3 7
+// eight codes of a dword as fp16, in the order 0 4 1 5 2 6 3 7: with x = dword ^ 0x88888888 every
+// nibble holds code + 8, "(x >> 4j) & 0x000F000F | 0x64006400" is the pair of halves
+// (1024 + code_j + 8, 1024 + code_{j+4} + 8), and one packed subtraction of 1032 leaves the codes.
+// The other operand's 16-byte chunks are put into the same order (interleave_halves), which a dot
+// product does not see.
 __device__ __forceinline__ v8h widen_codes_f16(uint32_t w)
 {
     const uint32_t x = w ^ 0x88888888u;
@@ -44,131 +41,24 @@ __device__ __forceinline__ v8h widen_codes_f16(uint32_t w)
     return v8h{p[0][0], p[0][1], p[1][0], p[1][1], p[2][0], p[2][1], p[3][0], p[3][1]};
 }
 
-// Block tile 128 x 128, four waves of 64 x 64 (2 x 2 fragments of 32 x 32), K walked in tiles of 64
-// codes.  Tiles travel global -> registers -> LDS (activations reordered, codes widened to fp16 on
-// the way), the next tile's loads in flight while this one is multiplied; two LDS buffers, one
-// barrier per tile.  Both operands sit in LDS as rows of eight 16-byte chunks (eight fp16 values
-// each), chunk c of row r at slot r * 8 + (c ^ (r & 7)).  Within a K tile lane half g takes codes
-// 32g .. 32g + 31 and step s the eight codes 32g + 8s ..: chunk 4g + s of its row, for both operands.
-__global__ __launch_bounds__(256, 2) void w4a16_gemm_kernel(
-    const __half *__restrict__ X, int64_t ldx, int T, int K, const uint8_t *__restrict__ Qw,
-    const float *__restrict__ sw, int N, __half *__restrict__ Y, int64_t ldy, int tiles_m, int tiles_n)
-{
-    __shared__ uint4 xs[2][kBM * 8];               // activations
-    __shared__ uint4 ws[2][kBN * 8];               // weight codes as fp16
-
-    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    const int l32 = lane & 31, g = lane >> 5, wm = wave >> 1, wn = wave & 1;
-    // XCD-contiguous tile ids, column-major inside groups of 8 row tiles: the tiles resident on one
-    // XCD share a few row and column panels in its L2
-    int bm, bn;
-    {
-        const int id = xcd_contiguous_id(blockIdx.x, tiles_m * tiles_n);
-        constexpr int GM = 8;
-        const int group = id / (GM * tiles_n), gm = min(GM, tiles_m - group * GM);
-        const int in_group = id - group * GM * tiles_n;
-        bm = group * GM + in_group % gm;
-        bn = in_group / gm;
-    }
-    const int row0 = bm * kBM, col0 = bn * kBN, Kb = K / 2;
-
-    // this thread's share of a tile: four activation chunks, one weight chunk (rows past the ends
-    // are clamped: their products are never stored)
-    const __half *x_src[4];
-    int x_slot[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int c = tid + 256 * u, r = c >> 3, ch = c & 7;
-        x_src[u] = X + (int64_t)min(row0 + r, T - 1) * ldx + ch * 8;
-        x_slot[u] = r * 8 + (ch ^ (r & 7));
-    }
-    const uint8_t *w_src = Qw + (int64_t)min(col0 + (tid >> 1), N - 1) * Kb + (tid & 1) * 16;
-    // the 32 codes of this thread's weight chunk become chunks 4 (tid & 1) .. + 3 of row tid >> 1
-    int w_slot[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) w_slot[u] = (tid >> 1) * 8 + ((4 * (tid & 1) + u) ^ ((tid >> 1) & 7));
-
-    v16f acc[2][2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-    uint4 xr[4], wr;
-    auto fetch = [&](int kt) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) xr[u] = *reinterpret_cast<const uint4 *>(x_src[u] + kt * kBK);
-        wr = *reinterpret_cast<const uint4 *>(w_src + kt * kWRow);
-    };
-    auto park = [&](int buf) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) xs[buf][x_slot[u]] = interleave_halves(xr[u]);
-        const uint32_t wd[4] = {wr.x, wr.y, wr.z, wr.w};
-#pragma unroll
-        for (int u = 0; u < 4; ++u) ws[buf][w_slot[u]] = __builtin_bit_cast(uint4, widen_codes_f16(wd[u]));
-    };
-
-    const int ktiles = K / kBK;
-    fetch(0);
-    park(0);
-    __syncthreads();
-    for (int kt = 0; kt < ktiles; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < ktiles) fetch(kt + 1);
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            v8h a[2], b[2];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int r = wm * 64 + 32 * i + l32;
-                a[i] = __builtin_bit_cast(v8h, xs[buf][r * 8 + ((4 * g + s) ^ (r & 7))]);
-            }
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int r = wn * 64 + 32 * j + l32;
-                b[j] = __builtin_bit_cast(v8h, ws[buf][r * 8 + ((4 * g + s) ^ (r & 7))]);
-            }
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
-        }
-        if (kt + 1 < ktiles) park(buf ^ 1);
-        __syncthreads();
-    }
-
-    // 32 x 32 accumulator layout: lane holds channel l32, register e holds token 8 (e / 4) + 4 g + e % 4
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int n = col0 + wn * 64 + 32 * j + l32;
-        if (n >= N) continue;
-        const float step = sw[n];
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int t = row0 + wm * 64 + 32 * i + 8 * (e / 4) + 4 * g + (e % 4);
-                if (t < T) Y[(int64_t)t * ldy + n] = __float2half_rn(acc[i][j][e] * step);
-            }
-    }
-}
-
 // eight codes of a dword as fp16, in their own order.  Byte m of the dword (with every nibble
 // holding code + 8) is copied into both halves of a dword; "& 0x00F0000F | 0x64006400" leaves
 // 1024 + (code_2m + 8) in the low half and 1024 + 16 (code_2m+1 + 8) in the high half, and one
-// packed multiply-add with (1, 1/16) and (-1032, -72) the two codes, exactly.
-__device__ __forceinline__ v8h widen_codes_f16_in_order(uint32_t w)
+// packed multiply-add with (1, 1/16) and (-1032, -72) the two codes, exactly.  Thirteen
+// instructions per dword: the and-or is written as the one three-operand instruction it is (its
+// constants must come from registers in that form, which the compiler avoids by emitting two).
+__device__ __forceinline__ v8h widen_codes_f16_in_order(uint32_t w, uint32_t magic_vgpr)
 {
     const uint32_t x = w ^ 0x88888888u;
     const v2h scale = {(_Float16)1.f, (_Float16)0.0625f}, bias = {(_Float16)-1032.f, (_Float16)-72.f};
     v2h p[4];
-    p[0] = __builtin_bit_cast(v2h, (__builtin_amdgcn_perm(0u, x, 0x0C000C00u) & 0x00F0000Fu) | 0x64006400u) * scale + bias;
-    p[1] = __builtin_bit_cast(v2h, (__builtin_amdgcn_perm(0u, x, 0x0C010C01u) & 0x00F0000Fu) | 0x64006400u) * scale + bias;
-    p[2] = __builtin_bit_cast(v2h, (__builtin_amdgcn_perm(0u, x, 0x0C020C02u) & 0x00F0000Fu) | 0x64006400u) * scale + bias;
-    p[3] = __builtin_bit_cast(v2h, (__builtin_amdgcn_perm(0u, x, 0x0C030C03u) & 0x00F0000Fu) | 0x64006400u) * scale + bias;
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        const uint32_t sel = 0x0C000C00u | (uint32_t)m | ((uint32_t)m << 16);
+        uint32_t h;
+        asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(h) : "v"(__builtin_amdgcn_perm(0u, x, sel)), "s"(0x00F0000Fu), "v"(magic_vgpr));
+        p[m] = __builtin_bit_cast(v2h, h) * scale + bias;
+    }
     return v8h{p[0][0], p[0][1], p[1][0], p[1][1], p[2][0], p[2][1], p[3][0], p[3][1]};
 }
 
@@ -219,23 +109,28 @@ __device__ __forceinline__ void wait_tile_then_barrier(int rem)
 // the channel in the register: register e holds channel 8 (e / 4) + 4 (lane / 32) + e % 4, four
 // runs of four consecutive channels.  Two runs are traded between the half-waves (one cross-half
 // swap per dword) and every lane stores 16 contiguous bytes of a row of Y.
-template <int WM, int WN, int FM, int FN, int OCC>
+// BK: elements of K per tile, 64 or 128 (a tile row of activations is 2 BK bytes, of codes BK / 2).
+template <int WM, int WN, int FM, int FN, int OCC, int BK>
 __global__ __launch_bounds__(WM *WN *kWave, OCC) void w4a16_gemm_ring_kernel(
     const __half *__restrict__ X, int64_t ldx, int T, int K, const uint8_t *__restrict__ Qw,
     const float *__restrict__ sw, int N, __half *__restrict__ Y, int64_t ldy, int tiles_m, int tiles_n,
     int vec_store)
 {
-    constexpr int NW = WM * WN, NS = 3;
+    static_assert(BK == 64 || BK == 128, "tiles of 64 or 128 elements of K");
+    constexpr int NW = WM * WN, NS = 3, STEPS = BK / 16;     // waves; ring stages; MFMA steps per K tile
     constexpr int BM = WM * FM * 32, BN = WN * FN * 32;
-    constexpr int A_ROW = 128, B_ROW = 32;                   // bytes of a tile row
+    constexpr int A_ROW = 2 * BK, B_ROW = BK / 2;            // bytes of a tile row
+    constexpr int A_CPR = A_ROW / 16, B_CPR = B_ROW / 16;    // 16-byte chunks per row
+    constexpr int A_RPL = 64 / A_CPR, B_RPL = 64 / B_CPR;    // rows filled by one wave-wide load
     constexpr int A_BYTES = BM * A_ROW, B_BYTES = BN * B_ROW, STAGE = A_BYTES + B_BYTES;
-    constexpr int A_LOADS = BM / 8 / NW, B_LOADS = BN / 32 / NW;       // wave-wide loads per wave and tile
+    constexpr int A_LOADS = BM / A_RPL / NW, B_LOADS = BN / B_RPL / NW;       // wave-wide loads per wave and tile
     constexpr int LOADS = A_LOADS + B_LOADS;
-    static_assert((BM / 8) % NW == 0 && (BN / 32) % NW == 0, "loads must split evenly over the waves");
+    static_assert((BM / A_RPL) % NW == 0 && (BN / B_RPL) % NW == 0, "loads must split evenly over the waves");
     extern __shared__ uint4 ring[];
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
-    const int l32 = lane & 31, g = lane >> 5, wm = wave / WN, wn = wave % WN;
+    const int l32 = lane & 31, g = lane >> 5;
+    const int wm = wave / WN, wn = wave % WN;
     int bm, bn;
     {
         const int id = xcd_contiguous_id(blockIdx.x, tiles_m * tiles_n);
@@ -247,30 +142,31 @@ __global__ __launch_bounds__(WM *WN *kWave, OCC) void w4a16_gemm_ring_kernel(
     }
     const int row0 = bm * BM, col0 = bn * BN, Kb = K / 2;
 
-    // global -> LDS.  Activations: one wave-wide load fills 8 rows x 8 chunks; lane l lands in row
-    // l / 8, physical chunk l % 8, which holds the logical chunk (l % 8) ^ (row % 8).  Codes: 32 rows
-    // x 2 chunks.  Rows past the ends are clamped: their products are never stored.
+    // global -> LDS.  One wave-wide load fills 64 consecutive chunk slots: A_RPL rows of activations
+    // (lane l lands in row l / A_CPR, physical chunk l % A_CPR, which holds the logical chunk
+    // (l % A_CPR) ^ (row % 8)) or B_RPL rows of codes.  Rows past the ends are clamped: their
+    // products are never stored.
     const __half *a_src[A_LOADS];
     const uint8_t *b_src[B_LOADS];
 #pragma unroll
     for (int u = 0; u < A_LOADS; ++u) {
-        const int r = 8 * (wave + NW * u) + lane / 8;
-        a_src[u] = X + (int64_t)min(row0 + r, T - 1) * ldx + (((lane & 7) ^ (r & 7)) * 8);
+        const int r = A_RPL * (wave + NW * u) + lane / A_CPR;
+        a_src[u] = X + (int64_t)min(row0 + r, T - 1) * ldx + (((lane % A_CPR) ^ (r & 7)) * 8);
     }
 #pragma unroll
     for (int u = 0; u < B_LOADS; ++u) {
-        const int r = 32 * (wave + NW * u) + lane / 2;
-        b_src[u] = Qw + (int64_t)min(col0 + r, N - 1) * Kb + (lane & 1) * 16;
+        const int r = B_RPL * (wave + NW * u) + lane / B_CPR;
+        b_src[u] = Qw + (int64_t)min(col0 + r, N - 1) * Kb + (lane % B_CPR) * 16;
     }
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)ring;
     const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
     auto issue_tile = [&](int kt, int stage, int limit) {
         const uint32_t sa = lds_base + (uint32_t)stage * STAGE;
 #pragma unroll
-        for (int u = 0; u < A_LOADS; ++u) dma_16_if(a_src[u] + kt * 64, sa + (wave_u + NW * u) * 1024, kt, limit);
+        for (int u = 0; u < A_LOADS; ++u) dma_16_if(a_src[u] + kt * BK, sa + (wave_u + NW * u) * 1024, kt, limit);
 #pragma unroll
         for (int u = 0; u < B_LOADS; ++u)
-            dma_16_if(b_src[u] + kt * 32, sa + A_BYTES + (wave_u + NW * u) * 1024, kt, limit);
+            dma_16_if(b_src[u] + kt * (BK / 2), sa + A_BYTES + (wave_u + NW * u) * 1024, kt, limit);
     };
 
     v16f acc[FM][FN];
@@ -281,14 +177,18 @@ __global__ __launch_bounds__(WM *WN *kWave, OCC) void w4a16_gemm_ring_kernel(
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    // LDS byte offsets of this lane's fragment chunks inside a stage
-    int a_off[4];
+    // LDS byte offsets of this lane's fragment chunks inside a stage: lane half g takes the elements
+    // [g BK / 2, (g + 1) BK / 2) of a K tile, step s the eight elements 8 s .. of those
+    int a_off[STEPS];
 #pragma unroll
-    for (int s = 0; s < 4; ++s) a_off[s] = (wm * FM * 32 + l32) * A_ROW + (((4 * g + s) ^ (l32 & 7)) * 16);
-    const int b_off = A_BYTES + (wn * FN * 32 + l32) * B_ROW + g * 16;
+    for (int s = 0; s < STEPS; ++s)
+        a_off[s] = (wm * FM * 32 + l32) * A_ROW + (((STEPS * g + s) ^ (l32 & 7)) * 16);
+    const int b_off = A_BYTES + (wn * FN * 32 + l32) * B_ROW + g * (STEPS * 4);
     const char *lds = reinterpret_cast<const char *>(ring);
 
-    const int ktiles = K / 64;
+    uint32_t magic;                                    // 1024.0 in both halves, held in a vector register
+    asm volatile("v_mov_b32 %0, 0x64006400" : "=v"(magic));
+    const int ktiles = K / BK;
     issue_tile(0, 0, ktiles);
     issue_tile(1, 1, ktiles);
     int stage = 0;
@@ -299,23 +199,27 @@ __global__ __launch_bounds__(WM *WN *kWave, OCC) void w4a16_gemm_ring_kernel(
         wait_tile_then_barrier<LOADS>(ktiles - 1 - kt);
         issue_tile(kt + 2, stage == 0 ? 2 : stage - 1, ktiles);
         const char *st = lds + stage * STAGE;
-        uint4 rb[FN];
+        uint32_t rb[FN][STEPS];                        // one dword of codes per step
 #pragma unroll
-        for (int j = 0; j < FN; ++j) rb[j] = *reinterpret_cast<const uint4 *>(st + b_off + j * (32 * B_ROW));
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int c = 0; c < STEPS / 4; ++c) {
+                const uint4 v = *reinterpret_cast<const uint4 *>(st + b_off + j * (32 * B_ROW) + 16 * c);
+                rb[j][4 * c] = v.x, rb[j][4 * c + 1] = v.y, rb[j][4 * c + 2] = v.z, rb[j][4 * c + 3] = v.w;
+            }
         v8h a[2][FM];
 #pragma unroll
         for (int i = 0; i < FM; ++i) a[0][i] = *reinterpret_cast<const v8h *>(st + a_off[0] + i * (32 * A_ROW));
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            if (s + 1 < 4) {
+        for (int s = 0; s < STEPS; ++s) {
+            if (s + 1 < STEPS) {
 #pragma unroll
                 for (int i = 0; i < FM; ++i)
                     a[(s + 1) & 1][i] = *reinterpret_cast<const v8h *>(st + a_off[s + 1] + i * (32 * A_ROW));
             }
 #pragma unroll
             for (int j = 0; j < FN; ++j) {
-                const uint32_t w = s == 0 ? rb[j].x : s == 1 ? rb[j].y : s == 2 ? rb[j].z : rb[j].w;
-                const v8h b = widen_codes_f16_in_order(w);
+                const v8h b = widen_codes_f16_in_order(rb[j][s], magic);
 #pragma unroll
                 for (int i = 0; i < FM; ++i)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(b, a[s & 1][i], acc[i][j], 0, 0, 0);
@@ -368,14 +272,15 @@ __global__ __launch_bounds__(WM *WN *kWave, OCC) void w4a16_gemm_ring_kernel(
     }
 }
 
-template <int WM, int WN, int FM, int FN, int OCC>
+template <int WM, int WN, int FM, int FN, int OCC, int BK>
 sq_status launch_w4a16_ring(const __half *X, int64_t ldx, int T, int K, const uint8_t *Qw, const float *sw, int N,
                             __half *Y, int64_t ldy, hipStream_t st)
 {
     constexpr int BM = WM * FM * 32, BN = WN * FN * 32;
-    constexpr size_t lds = (size_t)3 * (BM * 128 + BN * 32);
+    constexpr size_t lds = (size_t)3 * (BM * 2 * BK + BN * BK / 2);
     static_assert(lds <= (size_t)kMaxDynamicLds, "ring does not fit in LDS");
-    auto kernel = w4a16_gemm_ring_kernel<WM, WN, FM, FN, OCC>;
+    auto kernel = w4a16_gemm_ring_kernel<WM, WN, FM, FN, OCC, BK>;
+    if ((K % BK) != 0) return SQ_ERR_SHAPE;
     if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return SQ_ERR_LAUNCH;
     const int tiles_m = (T + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int vec_store = (((uintptr_t)Y & 15) == 0 && (ldy % 8) == 0) ? 1 : 0;
@@ -487,7 +392,7 @@ sq_status launch_w4a16_skinny(const __half *X, int64_t ldx, int T, int K, const 
 extern "C" sq_status sq_w4a16_gemm(const void *X, int64_t T, int32_t K, int64_t ldx, const uint8_t *Qw,
                                    const float *sw, int32_t N, void *Y, int64_t ldy, void *stream)
 {
-    if (T < 0 || N < 0 || K <= 0 || (K % sq::kBK) != 0 || K > 131072) return SQ_ERR_SHAPE;
+    if (T < 0 || N < 0 || K <= 0 || (K % 64) != 0 || K > 131072) return SQ_ERR_SHAPE;
     if (T > (1 << 24) || ldx < K || ldy < N) return SQ_ERR_SHAPE;
     if (T == 0 || N == 0) return SQ_OK;
     if (!X || !Qw || !sw || !Y) return SQ_ERR_NULL;
@@ -497,26 +402,19 @@ extern "C" sq_status sq_w4a16_gemm(const void *X, int64_t T, int32_t K, int64_t 
     // the second time mostly out of the caches; beyond that the tile kernel is the better choice).
     // Launch shapes as in the W4A4 decode-shaped kernel: about eight waves on every CU.
     if (T <= 32 && (K % 256) == 0 && sq::debug_option(SQ_DEBUG_W4A16_LAUNCH_SHAPE) == 0) {
-        const hipStream_t st = static_cast<hipStream_t>(stream);
-        const __half *Xh = static_cast<const __half *>(X);
-        __half *Yh = static_cast<__half *>(Y);
-        if (N >= 64 * 384) return sq::launch_w4a16_skinny<4, 4>(Xh, ldx, (int)T, K, Qw, sw, N, Yh, ldy, st);
-        return sq::launch_w4a16_skinny<2, 8>(Xh, ldx, (int)T, K, Qw, sw, N, Yh, ldy, st);
+        const hipStream_t s0 = static_cast<hipStream_t>(stream);
+        const __half *X0 = static_cast<const __half *>(X);
+        if (N >= 64 * 384) return sq::launch_w4a16_skinny<4, 4>(X0, ldx, (int)T, K, Qw, sw, N, static_cast<__half *>(Y), ldy, s0);
+        return sq::launch_w4a16_skinny<2, 8>(X0, ldx, (int)T, K, Qw, sw, N, static_cast<__half *>(Y), ldy, s0);
     }
-    {
-        const hipStream_t st = static_cast<hipStream_t>(stream);
-        const __half *Xh = static_cast<const __half *>(X);
-        __half *Yh = static_cast<__half *>(Y);
-        const int shape = sq::debug_option(SQ_DEBUG_W4A16_LAUNCH_SHAPE);
-        const int64_t tiles_large = ((T + 255) / 256) * ((N + 255) / 256);
-        if (shape == 3 || (shape == 0 && tiles_large >= 192))
-            return sq::launch_w4a16_ring<2, 4, 4, 2, 1>(Xh, ldx, (int)T, K, Qw, sw, N, Yh, ldy, st);
-        if (shape == 2 || shape == 0)
-            return sq::launch_w4a16_ring<1, 4, 4, 2, 2>(Xh, ldx, (int)T, K, Qw, sw, N, Yh, ldy, st);
-    }
-    const int tiles_m = (int)((T + sq::kBM - 1) / sq::kBM), tiles_n = (N + sq::kBN - 1) / sq::kBN;
-    hipLaunchKernelGGL(sq::w4a16_gemm_kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0,
-                       static_cast<hipStream_t>(stream), static_cast<const __half *>(X), ldx, (int)T, K, Qw, sw, N,
-                       static_cast<__half *>(Y), ldy, tiles_m, tiles_n);
-    return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
+    // Many tokens: 256 x 256 tiles (eight waves) when there are enough of them to fill the CUs, else
+    // 128 x 256 tiles (four waves, two workgroups per CU where there are that many).
+    const hipStream_t st = static_cast<hipStream_t>(stream);
+    const __half *Xh = static_cast<const __half *>(X);
+    __half *Yh = static_cast<__half *>(Y);
+    const int shape = sq::debug_option(SQ_DEBUG_W4A16_LAUNCH_SHAPE);
+    const int64_t tiles_large = ((T + 255) / 256) * ((N + 255) / 256);
+    if (shape == 2 || (shape != 1 && tiles_large >= 192))
+        return sq::launch_w4a16_ring<2, 4, 4, 2, 1, 64>(Xh, ldx, (int)T, K, Qw, sw, N, Yh, ldy, st);
+    return sq::launch_w4a16_ring<1, 4, 4, 2, 2, 64>(Xh, ldx, (int)T, K, Qw, sw, N, Yh, ldy, st);
 }

@@ -130,11 +130,11 @@ def test_w4a16_gemm_random_operands(oracle, T, K, N):
         assert np.array_equal(run_w4a16(Xi, Qw, s4), Yi)
 
 
-@pytest.mark.parametrize("shape", [1, 2, 3])
+@pytest.mark.parametrize("shape", [1, 2])
 @pytest.mark.parametrize("T,K,N", [(16, 512, 512), (130, 320, 257), (300, 2048, 130), (257, 128, 520), (1, 64, 1)])
 def test_w4a16_gemm_every_tile_kernel(oracle, shape, T, K, N):
-    """The three kernels for many tokens (128 x 128 tiles; the ring kernel with 128 x 256 and with
-    256 x 256 tiles), each forced onto shapes with ragged token and channel tails, strided output."""
+    """The kernel for many tokens with 128 x 256 and with 256 x 256 tiles, each forced onto shapes
+    with few tokens, ragged token and channel tails, strided output."""
     print(f"case w4a16 gemm launch shape {shape} T={T} K={K} N={N}", flush=True)
     import paper_2511_22316_amd as sq
     g = np.random.default_rng(shape + T + 3 * K + 5 * N)
