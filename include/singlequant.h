@@ -46,13 +46,15 @@ typedef enum {
 
 /* Limits (SQ_ERR_SHAPE beyond them): n1 <= 128, n2 <= 256 and n2 a multiple
  * of 8, K = n1*n2 <= 16384, P <= 64, at most 2^30 rows per call of the row
- * kernels (2^24 tokens for the GEMM), K a multiple of 32 for the GEMM. */
+ * kernels (2^24 tokens for the GEMM), K a multiple of 32 and at most
+ * SQ_GEMM_MAX_K for the GEMM. */
 #define SQ_MAX_N1 128
 #define SQ_MAX_N2 256
 #define SQ_MAX_K 16384
 #define SQ_MAX_GIVENS 64
 #define SQ_MAX_ROWS (1 << 30)
 #define SQ_DECODE_MAX_TOKENS 32
+#define SQ_GEMM_MAX_K 131040
 
 /*
  * sq_rotate_quantize -- online rotation fused with per-token 4-bit quantization.
@@ -135,8 +137,10 @@ sq_status sq_rotate_quantize_prepared(const void *X, int64_t T, int32_t K, int64
  *   Qw, sw   device, uint8 [N, K/2] and float [N]  (per-output-channel codes / steps)
  *   Y        device out, fp16 [T, ldy], ldy >= N
  *   acc_dbg  device out int32 [T, N], or NULL (parity checks only)
- * Requires K % 32 == 0, K <= 131072 (int32 accumulators cannot overflow),
- * Qx, Qw 16-byte aligned.  T == 0 or N == 0 is legal and enqueues nothing.
+ * Requires K % 32 == 0, K <= SQ_GEMM_MAX_K = 131040 (the kernels accumulate
+ * 256 * acc in int32, and 256 * 64 * K must stay below 2^31 when every product
+ * is (-8)(-8): at K = 131072 it would be 2^31 exactly), Qx, Qw 16-byte
+ * aligned.  T == 0 or N == 0 is legal and enqueues nothing.
  */
 sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T, int32_t K,
                        const uint8_t *Qw, const float *sw, int32_t N,

@@ -7,9 +7,9 @@
 // Nibbles are widened to int8 in registers as (code << 4): "w & 0xF0F0F0F0" yields the odd codes
 // of a dword times 16 with their sign in place, "(w << 4) & 0xF0F0F0F0" the even ones.  Both
 // operands carry the factor 16, so the int32 accumulator holds 256 * acc exactly
-// (64 * K * 256 < 2^31 for K <= 131072) and the epilogue shifts it out.  The split into even and
-// odd codes permutes the contraction index the same way on both operands, which a dot product
-// does not see.
+// (64 * K * 256 < 2^31 for K <= 131040, the limit of the entry point) and the epilogue shifts it
+// out.  The split into even and odd codes permutes the contraction index the same way on both
+// operands, which a dot product does not see.
 #include "sq_common.h"
 
 
@@ -743,7 +743,7 @@ extern "C" sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T,
                                   const uint8_t *Qw, const float *sw, int32_t N, void *Y,
                                   int64_t ldy, int32_t *acc_dbg, void *stream)
 {
-    if (T < 0 || N < 0 || K <= 0 || (K % 32) != 0 || K > 131072) return SQ_ERR_SHAPE;
+    if (T < 0 || N < 0 || K <= 0 || (K % 32) != 0 || K > SQ_GEMM_MAX_K) return SQ_ERR_SHAPE;
     if (T > (1 << 24) || ldy < N) return SQ_ERR_SHAPE;
     if (T == 0 || N == 0) return SQ_OK;
     if (!Qx || !sx || !Qw || !sw || !Y) return SQ_ERR_NULL;

@@ -194,6 +194,8 @@ def test_gemm_argument_errors(lib):
     assert _gemm(lib, T=-1) == 2
     assert _gemm(lib, ldy=6) == 2
     assert _gemm(lib, K=262144) == 2
+    assert _gemm(lib, K=131072) == 2                # 256 * 64 * K would be 2^31: one past the int32 accumulators
+    assert _gemm(lib, K=131040, T=0) == 0           # the largest K the entry point takes
     assert _gemm(lib, Qx=None) == 1
     assert _gemm(lib, Y=None) == 1
     assert _gemm(lib, Qw=FAKE + 8) == 4
