@@ -82,7 +82,10 @@ struct RotqShape {
     static constexpr int LO_STEP_BYTES = N1P * 32;        // side tile: [step][row p][16 fp16]
     static constexpr int OFF_X = 0;                                   // [TPP][NSX][TILE]
     static constexpr int OFF_R1F = TPP * NSX * TILE_BYTES;            // [MB][KSB][64 lanes][16 bytes]
-    static constexpr int R1F_BYTES = R1LDS_ ? MB * KSB * 1024 : 0;
+    // R1's fragments pass through LDS whenever one wave per column block can build them for all
+    // (up to four column blocks): to stay there (R1LDS_) or to be copied into every wave's registers
+    static constexpr bool R1_SHARED = R1LDS_ || MB <= 2;
+    static constexpr int R1F_BYTES = R1_SHARED ? MB * KSB * 1024 : 0;
     static constexpr int OFF_LO = OFF_R1F + R1F_BYTES;                // [TPP][side tiles][qsteps][LO_STEP]
     // after the side tiles (runtime size): [TPP][128] float, [2][TPP][4] float
     static constexpr int TAIL_BYTES = TPP * (kRotqMaxSlots * 4 + 32);
@@ -246,6 +249,12 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
 
     v8h r2f[KSA], r2x[QS_MAX], r1f[R1LDS ? 1 : MB][R1LDS ? 1 : KSB];
     static_assert(!R1LDS || MB <= 4, "one wave per column block of R1 builds the shared fragments");
+    // The fragments of R1 are the same for every wave.  Fetched by each wave for itself they are
+    // two thirds of all the prologue's loads (64 x 64 at 2048 tokens: 10.2 us with them, 8.9 us when
+    // a timing-only build fetched one fragment instead of eight), so wave nb fetches (and, from a
+    // row-major R1, transposes) column block nb alone and hands it to the others through LDS: to
+    // stay there (R1LDS) or, with at most two row blocks, to be copied into every wave's registers.
+    constexpr bool R1_SHARED = S::R1_SHARED;
     {
         v8h sel[2];                       // identity slices: B[k][n] = (16kk + k == n), k = 8g + e
 #pragma unroll
@@ -307,7 +316,7 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
         // Up to three row blocks, all of R1 is requested at once.  With four, that would not fit
         // the registers: the blocks of column block nb + 1 are requested while those of nb are
         // transposed, in two alternating sets.
-        constexpr int RAW1_SETS = R1LDS ? 1 : (MB <= 3 ? MB : 2);
+        constexpr int RAW1_SETS = R1_SHARED ? 1 : (MB <= 3 ? MB : 2);
         v8h raw2[N2 / 32][2], raw1[RAW1_SETS][MB][2];
         auto load_raw1 = [&](int nb, v8h (&dst)[MB][2]) {
 #pragma unroll
@@ -341,7 +350,7 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
 #pragma unroll
             for (int ks = 0; ks < KSA; ++ks) r2f[ks] = f2[ks * kWave];
             const v8h *f1 = reinterpret_cast<const v8h *>(R1) + lane;
-            if constexpr (R1LDS) {
+            if constexpr (R1_SHARED) {
                 if (wave_s < MB) {
 #pragma unroll
                     for (int blk = 0; blk < MB; ++blk) {
@@ -361,7 +370,7 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
                 raw2[blk][0] = chunk(r2col + (32 * blk + lsw) * N2, C0{}, CN2{});
                 raw2[blk][1] = chunk(r2col + (32 * blk + lsw) * N2, C16{}, CN2{});
             }
-            if constexpr (R1LDS) {
+            if constexpr (R1_SHARED) {
                 if (wave_s < MB) load_raw1(wave_s, raw1[0]);
             } else {
 #pragma unroll
@@ -401,7 +410,7 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
                 r2f[2 * blk + 1] = to_frag(c, 1);
             }
         }
-        if constexpr (R1LDS) {
+        if constexpr (R1_SHARED) {
             // visible to the other waves after the barrier that precedes the first stage A
             if (wave_s < MB) {
                 v8h *dst = reinterpret_cast<v8h *>(lds + S::OFF_R1F) + (wave_s * KSB) * kWave + lane;
@@ -511,7 +520,14 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
     };
 
     // ---- pipeline prologue: first row rotated, its stage A done -------------------------------
-    __syncthreads();                       // first row rotated
+    __syncthreads();                       // first row rotated; the fragments of R1 are in LDS
+    if constexpr (R1_SHARED && !R1LDS) {
+        const v8h *r1s0 = reinterpret_cast<const v8h *>(lds + S::OFF_R1F) + lane;
+#pragma unroll
+        for (int nb = 0; nb < MB; ++nb)
+#pragma unroll
+            for (int ks = 0; ks < KSB; ++ks) r1f[nb][ks] = r1s0[(nb * KSB + ks) * kWave];
+    }
     stage_a(0, 0, [](int) {});
     if (sides == 1) __syncthreads();       // the one side tile is rewritten in the first iteration
 
