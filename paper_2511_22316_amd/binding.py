@@ -36,6 +36,11 @@ def _load():
             raise RuntimeError(
                 f"{_LIB_PATH} is missing: build it with `python -m paper_2511_22316_amd.build` "
                 "(there is no CPU fallback)")
+        # torch first: it brings its own copy of the HIP runtime, and the device memory this binding
+        # passes around belongs to that copy.  Loaded the other way round (this library, which
+        # names the runtime of the ROCm installation, before torch) the process ends up with two
+        # runtimes, and the one the library talks to reports "no ROCm-capable device".
+        import torch  # noqa: F401
         lib = C.CDLL(_LIB_PATH)
         lib.sq_rotate_quantize.restype = C.c_int
         lib.sq_rotate_quantize.argtypes = [

@@ -158,29 +158,42 @@ __device__ __forceinline__ void store_tile(const v16i (&acc)[FM][FN], int row_ba
 // KG = 2: two groups of WM x WN waves share the block tile and split K in halves (group g walks
 // bytes [g Kb/2, (g+1) Kb/2) of every row); the second group's accumulators are added to the
 // first's through LDS before the epilogue.  For tiles so small that the time is the walk over K.
-template <int WM, int WN, int FM, int FN, int BKB, int OCC, int KG, int NS>
-__global__ __launch_bounds__(KG *WM *WN *kWave, OCC) void w4a4_gemm_kernel(
+// LW > 0: LW more waves that do nothing but move the tiles (global -> LDS, the waits for them) while
+// the WM x WN others never issue a memory instruction inside the loop.  A global -> LDS load holds
+// the wave that issues it for some tens of ns, in which it issues no MFMA either; with the loads
+// of a 128 x 256 tile spread over the eight multiplying waves that was a tenth of the kernel (a
+// timing-only build without the weights' loads: 28.3 against 31.5 us with them cache-hot).  The
+// loading waves cost registers (every wave of a workgroup gets the same allocation), so this form
+// needs at most 168 of them per wave: three waves per SIMD.
+template <int WM, int WN, int FM, int FN, int BKB, int OCC, int KG, int NS, int LW>
+__global__ __launch_bounds__((KG * WM * WN + LW) * kWave, OCC) void w4a4_gemm_kernel(
     const uint8_t *__restrict__ Qx, const float *__restrict__ sx, int T, int Kb,
     const uint8_t *__restrict__ Qw, const float *__restrict__ sw, int N, __half *__restrict__ Y,
     int64_t ldy, int32_t *__restrict__ acc_dbg, int tiles_m, int tiles_n, int vec_store)
 {
     static_assert(NS >= 3 && NS <= 6, "ring of three to six stages");
     static_assert(KG == 1 || KG == 2, "one or two K groups");
-    constexpr int NW = WM * WN, NT = KG * NW * kWave;          // NW: waves of one K group
+    static_assert(LW == 0 || KG == 1, "loading waves: one K group");
+    constexpr int NW = WM * WN;                                // NW: multiplying waves of one K group
+    constexpr int NTC = KG * NW * kWave, NT = NTC + LW * kWave;  // multiplying threads; all threads
+    constexpr int NL = LW > 0 ? LW : NW;                       // waves that share the loads of a tile
+    constexpr bool SELF_LOAD = LW == 0;                        // the multiplying waves load for themselves
     constexpr int CPR = BKB / 16;                 // 16-byte chunks per tile row
     constexpr int STEPS = CPR / 2;                // steps of 64 codes per tile
     constexpr int RPL = kWave / CPR;              // tile rows filled by one wave-wide load
     constexpr int BM = WM * FM * 32, BN = WN * FN * 32;
     constexpr int A_SLOTS = BM * CPR, B_SLOTS = BN * CPR, STAGE_SLOTS = A_SLOTS + B_SLOTS;
-    constexpr int A_LOADS = BM / RPL / NW, B_LOADS = BN / RPL / NW;   // loads per wave per tile
+    constexpr int A_LOADS = BM / RPL / NL, B_LOADS = BN / RPL / NL;   // loads per loading wave per tile
     constexpr int LOADS = A_LOADS + B_LOADS;
-    static_assert((BM / RPL) % NW == 0 && (BN / RPL) % NW == 0, "loads must split evenly over waves");
+    static_assert((BM / RPL) % NL == 0 && (BN / RPL) % NL == 0, "loads must split evenly over waves");
     static_assert(STEPS == 2 || STEPS == 4, "tile rows of 64 or 128 bytes");
 
     extern __shared__ uint4 smem[];
 
     const int tid = threadIdx.x, lane = tid & (kWave - 1);
-    const int kg = (tid / kWave) / NW, wave = (tid / kWave) % NW;   // K group, wave within it
+    // K group and wave within it; a loading wave (index NW and up) counts from 0 again
+    const bool loader = LW > 0 && tid / kWave >= NW;
+    const int kg = LW > 0 ? 0 : (tid / kWave) / NW, wave = (tid / kWave) % NW;
     const int wm = wave / WN, wn = wave % WN;
     if constexpr (KG == 2) {                 // this group's half of K
         Kb /= 2;
@@ -201,10 +214,10 @@ __global__ __launch_bounds__(KG *WM *WN *kWave, OCC) void w4a4_gemm_kernel(
     const uint8_t *b_src[B_LOADS];
 #pragma unroll
     for (int g = 0; g < A_LOADS; ++g)   // rows past the end are clamped: their products are never stored
-        a_src[g] = Qx + (int64_t)min(row0 + RPL * (wave + NW * g) + lrow, T - 1) * row_bytes + lchunk * 16;
+        a_src[g] = Qx + (int64_t)min(row0 + RPL * (wave + NL * g) + lrow, T - 1) * row_bytes + lchunk * 16;
 #pragma unroll
     for (int g = 0; g < B_LOADS; ++g)
-        b_src[g] = Qw + (int64_t)min(col0 + RPL * (wave + NW * g) + lrow, N - 1) * row_bytes + lchunk * 16;
+        b_src[g] = Qw + (int64_t)min(col0 + RPL * (wave + NL * g) + lrow, N - 1) * row_bytes + lchunk * 16;
 
     const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint4 *)smem;
     const uint32_t wave_u = __builtin_amdgcn_readfirstlane(wave);
@@ -215,16 +228,16 @@ __global__ __launch_bounds__(KG *WM *WN *kWave, OCC) void w4a4_gemm_kernel(
         const uint32_t sb = sa + A_SLOTS * 16;
         const int kb0 = kt * BKB;
 #pragma unroll
-        for (int g = 0; g < A_LOADS; ++g) load_to_lds_16_if(a_src[g] + kb0, sa + g * NW * 1024, kt, limit);
+        for (int g = 0; g < A_LOADS; ++g) load_to_lds_16_if(a_src[g] + kb0, sa + g * NL * 1024, kt, limit);
 #pragma unroll
-        for (int g = 0; g < B_LOADS; ++g) load_to_lds_16_if(b_src[g] + kb0, sb + g * NW * 1024, kt, limit);
+        for (int g = 0; g < B_LOADS; ++g) load_to_lds_16_if(b_src[g] + kb0, sb + g * NL * 1024, kt, limit);
     };
     // one of those loads: index 0 .. A_LOADS-1 the tokens' part, then the weights' part
     auto issue_one = [&](int idx, int kt, int stage, int limit) {
         const uint32_t sa = lds_base + (uint32_t)stage * (KG * STAGE_SLOTS * 16) + group_byte + wave_u * 1024;
         const int kb0 = kt * BKB;
-        if (idx < A_LOADS) load_to_lds_16_if(a_src[idx] + kb0, sa + idx * NW * 1024, kt, limit);
-        else load_to_lds_16_if(b_src[idx - A_LOADS] + kb0, sa + A_SLOTS * 16 + (idx - A_LOADS) * NW * 1024, kt, limit);
+        if (idx < A_LOADS) load_to_lds_16_if(a_src[idx] + kb0, sa + idx * NL * 1024, kt, limit);
+        else load_to_lds_16_if(b_src[idx - A_LOADS] + kb0, sa + A_SLOTS * 16 + (idx - A_LOADS) * NL * 1024, kt, limit);
     };
 
     v16i acc[FM][FN];
@@ -305,11 +318,17 @@ __global__ __launch_bounds__(KG *WM *WN *kWave, OCC) void w4a4_gemm_kernel(
     // tile kt+2 (if it exists) are outstanding.  After the barrier every wave's share of tile kt+1
     // is in LDS and nobody reads tile kt any more (all its reads were issued, and the barrier
     // drains them), so its stage can take tile kt+3.
-#define SQ_GEMM_TURN() wait_tile_and_barrier<LOADS, NS>(ktiles - kt - 2)
+#define SQ_GEMM_TURN()                                                                               \
+    do {                                                                                             \
+        if constexpr (SELF_LOAD) wait_tile_and_barrier<LOADS, NS>(ktiles - kt - 2);                  \
+        else block_barrier();                                                                        \
+    } while (0)
 
     // prologue: tiles 0 and 1 in flight, wait for tile 0, start tile 2, first fragments ready
+    if (SELF_LOAD || loader) {
 #pragma unroll
-    for (int t = 0; t < NS - 1; ++t) issue_tile(t, t, ktiles);
+        for (int t = 0; t < NS - 1; ++t) issue_tile(t, t, ktiles);
+    }
     // While the first tiles are on their way, the block's dequantization steps are parked in LDS
     // behind the ring and the staged output tile, so that the epilogue does not wait on global
     // memory: sx * 2^-8 for the BM tokens (the accumulators carry a factor 256), then sw for the
@@ -323,8 +342,27 @@ __global__ __launch_bounds__(KG *WM *WN *kWave, OCC) void w4a4_gemm_kernel(
         scale_lds[r] = v;
     }
 
-    wait_tile_and_barrier<LOADS, NS>(ktiles - 1);
-    issue_tile(NS - 1, NS - 1, ktiles);
+    if constexpr (!SELF_LOAD) {
+        if (loader) {
+            // A loading wave: the waits and requests of the multiplying waves' loop, nothing else.  It
+            // meets them at every barrier of the kernel, the epilogue's two included.
+            wait_tile_and_barrier<LOADS, NS>(ktiles - 1);
+            issue_tile(NS - 1, NS - 1, ktiles);
+            int st = 0;
+            for (int kt = 0; kt < ktiles; ++kt) {
+                wait_tile_and_barrier<LOADS, NS>(ktiles - kt - 2);
+                issue_tile(kt + NS, st, ktiles);
+                st = (st + 1 == NS) ? 0 : st + 1;
+            }
+            block_barrier();
+            __syncthreads();
+            return;
+        }
+        block_barrier();                   // tile 0 has landed (the loading waves waited for it)
+    } else {
+        wait_tile_and_barrier<LOADS, NS>(ktiles - 1);
+        issue_tile(NS - 1, NS - 1, ktiles);
+    }
     read_step(0, 0);
 #pragma unroll
     for (int c = 0; c < FM + FN; ++c) widen_chunk(raw[c], frag[0][c][0], frag[0][c][1]);
@@ -340,12 +378,12 @@ __global__ __launch_bounds__(KG *WM *WN *kWave, OCC) void w4a4_gemm_kernel(
             SQ_GEMM_STEP(0, cur_byte, 2, -1);
             SQ_GEMM_STEP(1, cur_byte, 3, -1);
             SQ_GEMM_TURN();
-            SQ_GEMM_STEP(0, next_byte, 0, 0);
-            SQ_GEMM_STEP(1, next_byte, 1, 1);
+            SQ_GEMM_STEP(0, next_byte, 0, SELF_LOAD ? 0 : -1);
+            SQ_GEMM_STEP(1, next_byte, 1, SELF_LOAD ? 1 : -1);
         } else {
             SQ_GEMM_TURN();
-            SQ_GEMM_STEP(0, next_byte, 0, 0);
-            SQ_GEMM_STEP(1, next_byte, 1, 1);
+            SQ_GEMM_STEP(0, next_byte, 0, SELF_LOAD ? 0 : -1);
+            SQ_GEMM_STEP(1, next_byte, 1, SELF_LOAD ? 1 : -1);
         }
         st_cur = st_next;
     }
@@ -421,18 +459,18 @@ __global__ __launch_bounds__(KG *WM *WN *kWave, OCC) void w4a4_gemm_kernel(
     }   // kg == 0
     __syncthreads();
     constexpr int CPRY = BN / 8;         // 16-byte chunks per output row
-    constexpr int ROUNDS = BM * CPRY / NT, BATCH = (ROUNDS % 4 == 0) ? 4 : (ROUNDS % 2 == 0) ? 2 : 1;
-    static_assert((BM * CPRY) % NT == 0, "every thread copies the same number of chunks");
+    constexpr int ROUNDS = BM * CPRY / NTC, BATCH = (ROUNDS % 4 == 0) ? 4 : (ROUNDS % 2 == 0) ? 2 : 1;
+    static_assert((BM * CPRY) % NTC == 0, "every multiplying thread copies the same number of chunks");
     for (int r0 = 0; r0 < ROUNDS; r0 += BATCH) {       // up to four LDS reads in flight, then their stores
         uint4 v[BATCH];
 #pragma unroll
         for (int u = 0; u < BATCH; ++u) {
-            const int idx = (r0 + u) * NT + tid;
+            const int idx = (r0 + u) * NTC + tid;
             v[u] = *reinterpret_cast<const uint4 *>(ys + (idx / CPRY) * YS + (idx % CPRY) * 16);
         }
 #pragma unroll
         for (int u = 0; u < BATCH; ++u) {
-            const int idx = (r0 + u) * NT + tid;
+            const int idx = (r0 + u) * NTC + tid;
             const int t = row0 + idx / CPRY, n0 = col0 + (idx % CPRY) * 8;
             if (t >= T || n0 >= N) continue;
             __half *dst = Y + (int64_t)t * ldy + n0;
@@ -684,7 +722,7 @@ __global__ __launch_bounds__(256) void w4a4_gemm_generic_kernel(
     store_tile<FM, FN>(acc, row0 + wm * FM * 32, col0 + wn * FN * 32, lane, sx, sw, T, N, Y, ldy, acc_dbg);
 }
 
-template <int WM, int WN, int FM, int FN, int BKB, int OCC, int KG = 1, int NS = 3>
+template <int WM, int WN, int FM, int FN, int BKB, int OCC, int KG = 1, int NS = 3, int LW = 0>
 static sq_status launch_main(const uint8_t *Qx, const float *sx, int T, int K, const uint8_t *Qw,
                              const float *sw, int N, __half *Y, int64_t ldy, int32_t *acc_dbg,
                              hipStream_t st)
@@ -694,12 +732,12 @@ static sq_status launch_main(const uint8_t *Qx, const float *sx, int T, int K, c
     // the epilogue reuses the ring for the output tile; the scales sit behind both
     constexpr size_t lds = (ring > out_tile ? ring : out_tile) + (size_t)(BM + BN) * 4;
     static_assert(lds <= (size_t)kMaxDynamicLds, "ring does not fit in LDS");
-    auto kernel = w4a4_gemm_kernel<WM, WN, FM, FN, BKB, OCC, KG, NS>;
+    auto kernel = w4a4_gemm_kernel<WM, WN, FM, FN, BKB, OCC, KG, NS, LW>;
     if ((K / 2) % (KG * BKB) != 0) return SQ_ERR_SHAPE;      // every K group walks whole tiles
     if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return SQ_ERR_LAUNCH;
     const int tiles_m = (T + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int vec_store = (((uintptr_t)Y & 15) == 0 && (ldy % 8) == 0) ? 1 : 0;
-    hipLaunchKernelGGL(kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3(KG * WM * WN * kWave), lds, st, Qx,
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(tiles_m * tiles_n)), dim3((KG * WM * WN + LW) * kWave), lds, st, Qx,
                        sx, T, K / 2, Qw, sw, N, Y, ldy, acc_dbg, tiles_m, tiles_n, vec_store);
     return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
@@ -800,7 +838,9 @@ extern "C" sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T,
         const int64_t n_small = (int64_t)((Ti + 127) / 128) * ((N + 255) / 256);
         const int64_t n_large = (int64_t)((Ti + 255) / 256) * ((N + 255) / 256);
         const int64_t rounds_small = (n_small + 255) / 256, rounds_large = (n_large + 255) / 256;
-        choice = (20 * rounds_small > 37 * rounds_large) ? 4 : 1;
+        // (the 128x256 tile in its form with four loading waves, case 16: attn_proj 32.0 -> 31.5 us,
+        // mlp_down 74.5 -> 73.4 us against case 1, the same tile with the loads in the multiplying waves)
+        choice = (20 * rounds_small > 37 * rounds_large) ? 4 : 16;
     }
     switch (choice) {
         case 0: return sq::launch_main<2, 2, 2, 4, 128, 1>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
@@ -811,6 +851,7 @@ extern "C" sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T,
         case 6: return sq::launch_main<2, 4, 2, 2, 64, 1>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
         case 10: return sq::launch_main<2, 2, 1, 1, 128, 2>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
         case 11: return sq::launch_main<2, 2, 1, 2, 128, 2>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
+        case 16: return sq::launch_main<2, 4, 2, 2, 128, 1, 1, 3, 4>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
         case 14: if (K % 512 == 0) return sq::launch_main<2, 2, 1, 1, 128, 1, 2>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
         case 15: if (K % 512 == 0) return sq::launch_main<2, 2, 1, 2, 128, 1, 2>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
         case 7: if (Ti <= 32) return sq::launch_skinny<1, 1, 16>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;

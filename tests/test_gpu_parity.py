@@ -338,6 +338,29 @@ def test_gemm_random_codes_bit_exact(oracle, T, K, N):
     assert np.all(accm == 64 * K)
 
 
+@pytest.mark.parametrize("case", [0, 1, 2, 3, 4, 5, 6, 10, 11, 16])
+@pytest.mark.parametrize("T,K,N", [(300, 512, 520), (130, 768, 257)])
+def test_gemm_every_tile_launch_shape(oracle, case, T, K, N):
+    """Every launch shape of the tile kernel (tile sizes, waves per workgroup, the form with
+    separate loading waves), forced through the debug option onto shapes with ragged token and
+    channel tails: int32 accumulators bit-exact, Y within one fp16 ulp."""
+    print(f"case gemm forced launch shape {case} T={T} K={K} N={N}", flush=True)
+    import paper_2511_22316_amd as sq
+    g = np.random.default_rng(case + T + K + N)
+    Qx = synth.random_codes(T, K, 500 + T)
+    Qw = synth.random_codes(N, K, 600 + N)
+    sx = g.uniform(0.05, 4.0, T).astype(np.float32)
+    sw = g.uniform(1e-4, 5e-3, N).astype(np.float32)
+    Yo, acco = oracle.gemm(Qx, sx, Qw, sw)
+    sq.sq_debug_set_option(sq.binding.SQ_DEBUG_GEMM_LAUNCH_SHAPE, case + 1)
+    try:
+        Yg, accg = run_gemm(Qx, sx, Qw, sw)
+    finally:
+        sq.sq_debug_set_option(sq.binding.SQ_DEBUG_GEMM_LAUNCH_SHAPE, 0)
+    assert np.array_equal(accg, acco)
+    assert half_ulp_distance(Yg, Yo).max() <= 1
+
+
 def test_gemm_strided_output_and_empty(oracle):
     print("case gemm strided output / empty", flush=True)
     import torch
