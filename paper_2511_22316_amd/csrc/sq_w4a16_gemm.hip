@@ -99,7 +99,7 @@ __device__ __forceinline__ void wait_tile_then_barrier(int rem)
 // of FM x FN fragments of 32 x 32; K walked in tiles of 64.  Both operands travel global -> LDS
 // without passing registers (16 bytes per lane), through a ring of three stages, two tiles ahead,
 // completion tracked by hand: activations as they are (rows of 128 bytes, the 16-byte chunks of a
-// row XOR-swizzled by row % 8), weight codes packed (rows of 32 bytes).  A wave widens the codes
+// row XOR-swizzled by (row / 2) % 8), weight codes packed (rows of 32 bytes).  A wave widens the codes
 // of its own channels in registers, in order, so the activations need no reordering; one dword
 // makes the operand of FM MFMAs, which is why a wave's tile is tall (FM = 4: 128 tokens x 64
 // channels, 13 VALU instructions per 4 MFMAs) rather than wide.  Within a K tile lane half g takes
@@ -144,14 +144,15 @@ __global__ __launch_bounds__(WM *WN *kWave, OCC) void w4a16_gemm_ring_kernel(
 
     // global -> LDS.  One wave-wide load fills 64 consecutive chunk slots: A_RPL rows of activations
     // (lane l lands in row l / A_CPR, physical chunk l % A_CPR, which holds the logical chunk
-    // (l % A_CPR) ^ (row % 8)) or B_RPL rows of codes.  Rows past the ends are clamped: their
+    // (l % A_CPR) ^ ((row / 2) % 8): sixteen consecutive rows, two per 256 bytes of the 64 banks, then
+    // keep the same logical chunk in sixteen different bank groups) or B_RPL rows of codes.  Rows past the ends are clamped: their
     // products are never stored.
     const __half *a_src[A_LOADS];
     const uint8_t *b_src[B_LOADS];
 #pragma unroll
     for (int u = 0; u < A_LOADS; ++u) {
         const int r = A_RPL * (wave + NW * u) + lane / A_CPR;
-        a_src[u] = X + (int64_t)min(row0 + r, T - 1) * ldx + (((lane % A_CPR) ^ (r & 7)) * 8);
+        a_src[u] = X + (int64_t)min(row0 + r, T - 1) * ldx + (((lane % A_CPR) ^ ((r >> 1) & 7)) * 8);
     }
 #pragma unroll
     for (int u = 0; u < B_LOADS; ++u) {
@@ -182,7 +183,7 @@ __global__ __launch_bounds__(WM *WN *kWave, OCC) void w4a16_gemm_ring_kernel(
     int a_off[STEPS];
 #pragma unroll
     for (int s = 0; s < STEPS; ++s)
-        a_off[s] = (wm * FM * 32 + l32) * A_ROW + (((STEPS * g + s) ^ (l32 & 7)) * 16);
+        a_off[s] = (wm * FM * 32 + l32) * A_ROW + (((STEPS * g + s) ^ ((l32 >> 1) & 7)) * 16);
     const int b_off = A_BYTES + (wn * FN * 32 + l32) * B_ROW + g * (STEPS * 4);
     const char *lds = reinterpret_cast<const char *>(ring);
 

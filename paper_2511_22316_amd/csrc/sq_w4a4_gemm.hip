@@ -16,14 +16,18 @@
 namespace sq {
 
 // LDS tile of one operand: rows of BKB bytes (2*BKB codes), stored as 16-byte chunks.
-// Chunk c of row r sits at chunk slot r*CPR + (c ^ swz(r)): 8 consecutive rows then touch 8
-// different 16-byte bank groups both for the row-major writes and for the MFMA-fragment reads.
+// Chunk c of row r sits at chunk slot r*CPR + (c ^ swz(r)).  The LDS of this part serves a
+// 16-byte read of sixteen lanes per cycle from 64 banks (256 bytes): with swz(r) = (r / 2) % 8 for
+// rows of 128 bytes (two rows per 256 bytes) and (r / 4) % 4 for rows of 64 bytes, the sixteen
+// consecutive rows that read the same logical chunk land in sixteen different 16-byte bank groups
+// (SQ_LDS_BANK_CONFLICT reads 0 for the kernel; with swz(r) = r % 8, which would be right for 32
+// banks, it read 46 % of the LDS-active cycles -- at no difference in time: LDS is a third busy).
 template <int BKB>
 __device__ __forceinline__ int lds_chunk_slot(int row, int chunk)
 {
     constexpr int CPR = BKB / 16;
     static_assert(CPR == 4 || CPR == 8, "tile row must be 64 or 128 bytes");
-    const int swz = (CPR == 8) ? (row & 7) : ((row >> 1) & 3);
+    const int swz = (CPR == 8) ? ((row >> 1) & 7) : ((row >> 2) & 3);
     return row * CPR + (chunk ^ swz);
 }
 
@@ -209,7 +213,10 @@ __global__ __launch_bounds__((KG * WM * WN + LW) * kWave, OCC) void w4a4_gemm_ke
     // lane l lands in slot base + l, i.e. row l/CPR, physical chunk l%CPR, which holds the logical
     // chunk (l%CPR) ^ swizzle(row).  Wave w issues the loads for row groups w, w+NW, w+2NW, ...
     const int lrow = lane / CPR;
-    const int lchunk = (lane % CPR) ^ (CPR == 8 ? (lrow & 7) : ((lrow >> 1) & 3));
+    // (the swizzle has a period of 16 rows, and every load of a wave starts a multiple of 16 rows from its first)
+    static_assert((RPL * NL) % 16 == 0, "loads of one wave must start at the same row modulo 16");
+    const int lrow16 = (RPL * wave + lrow) & 15;
+    const int lchunk = (lane % CPR) ^ (CPR == 8 ? ((lrow16 >> 1) & 7) : ((lrow16 >> 2) & 3));
     const uint8_t *a_src[A_LOADS];
     const uint8_t *b_src[B_LOADS];
 #pragma unroll
