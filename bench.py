@@ -50,14 +50,14 @@ MIN_BLOCKS = 3
 # summaries profiles/w4a4_gemm_<workload>.md and profiles/rotate_quantize_<workload>.md (FETCH_SIZE
 # and WRITE_SIZE, each scaled by what the counter reads for a plain 256 MiB copy: x2.000, x1.000).
 PROFILED_TRAFFIC = {
-    "attn_proj": {"gemm": {"fetch": 33808680, "write": 16777216},
-                  "rotate_quantize": {"fetch": 17070209, "write": 4227072}},
-    "mlp_down": {"gemm": {"fetch": 90425379, "write": 16777216},
-                 "rotate_quantize": {"fetch": 45743061, "write": 11337728}},
-    "decode": {"gemm": {"fetch": 118383296, "write": 458752},
-               "rotate_quantize": {"fetch": 665532, "write": 33024}},
-    "large_prefill": {"gemm": {"fetch": 1414425910, "write": 469762048},
-                      "rotate_quantize": {"fetch": 134738592, "write": 33816576}},
+    "attn_proj": {"gemm": {"fetch": 33809731, "write": 16777216},
+                  "rotate_quantize": {"fetch": 17070223, "write": 4227072}},
+    "mlp_down": {"gemm": {"fetch": 90426633, "write": 16777216},
+                 "rotate_quantize": {"fetch": 45743178, "write": 11337728}},
+    "decode": {"gemm": {"fetch": 118380409, "write": 458752},
+               "rotate_quantize": {"fetch": 665525, "write": 33024}},
+    "large_prefill": {"gemm": {"fetch": 1414509012, "write": 469762048},
+                      "rotate_quantize": {"fetch": 134738742, "write": 33816576}},
 }
 
 
