@@ -112,7 +112,9 @@ def check_w4a16(Yg, Yo, m, K):
                                    # shapes, one and two token blocks, ragged channel tails, one slice only;
                                    # K % 256 != 0: the tile kernel on few tokens
                                    (8, 1024, 24700), (32, 768, 10300), (20, 256, 50), (16, 8192, 300), (17, 2048, 33),
-                                   (1, 4096, 4096), (16, 320, 100)])
+                                   (1, 4096, 4096), (16, 320, 100),
+                                   # just past the decode-shaped kernel's 32 tokens; fewer channels than a fragment
+                                   (33, 64, 5), (33, 256, 31)])
 def test_w4a16_gemm_random_operands(oracle, T, K, N):
     print(f"case w4a16 gemm random T={T} K={K} N={N}", flush=True)
     g = np.random.default_rng(T + 3 * K + 5 * N)
@@ -179,6 +181,18 @@ def test_w4a16_gemm_strided_and_empty(oracle):
     torch.cuda.synchronize()
     check_w4a16(host(Y), Yo, m, K)
     sq.sq_w4a16_gemm(wide[:0, :K], dev(Qw), dev(sw), Y[:0])
+    # the decode-shaped kernel on a strided input and output
+    T, K, N = 9, 512, 40
+    X = g.standard_normal((T, K)).astype(np.float16)
+    Qw, sw = synth.random_codes(N, K, 3), np.full(N, 0.01, np.float32)
+    Yo, m = oracle.gemm_w4a16(X, Qw, sw, want_abs_sum=True)
+    wide = torch.full((T, K + 24), 1000.0, dtype=torch.float16, device="cuda")
+    wide[:, :K] = dev(X)
+    Y = torch.full((T, N + 5), -9.0, dtype=torch.float16, device="cuda")
+    sq.sq_w4a16_gemm(wide[:, :K], dev(Qw), dev(sw), Y[:, :N])
+    torch.cuda.synchronize()
+    check_w4a16(host(Y)[:, :N], Yo, m, K)
+    assert np.all(host(Y)[:, N:] == -9.0)
 
 
 @pytest.mark.parametrize("name,T,N", [("tiny", 16, 512), ("attn_proj", 96, 300), ("mlp_down", 40, 130)])
