@@ -209,7 +209,7 @@ sq_status sq_w4a16_gemm(const void *X, int64_t T, int32_t K, int64_t ldx,
  *              than lowest-index-first would run into.)
  * The only benefit of this entry point is one host call per layer instead of
  * two.  It saves no GPU time: on one MI355X the single launch takes slightly
- * longer than the two launches it replaces (35.6 us against 33.8 us at T = 8,
+ * longer than the two launches it replaces (35.4 us against 32.9 us at T = 8,
  * K = 8192, N = 28672), because the multiplying workgroups wait for the
  * rotating ones across the chip and then read the codes with agent-coherent
  * loads (the writers release their stores at agent scope; the readers' loads
