@@ -377,8 +377,8 @@ typedef enum {
     SQ_DEBUG_ROTQ_PLAIN_KERNEL = 3,     /* 1: every shape takes the plain-FMA rotate kernel         */
     SQ_DEBUG_DECODE_SPIN_LIMIT = 4,     /* polls after which a waiting workgroup of sq_decode_layer
                                            gives up (default 2^20, about a second)                */
-    SQ_DEBUG_W4A16_LAUNCH_SHAPE = 5,    /* sq_w4a16_gemm: the tile kernel with 128 x 256 (1) or
-                                           256 x 256 (2) tiles, whatever T                         */
+    SQ_DEBUG_W4A16_LAUNCH_SHAPE = 5,    /* sq_w4a16_gemm: the tile kernel with 128 x 256 tiles and
+                                           loading waves (1) or 256 x 256 tiles (2), whatever T     */
     SQ_DEBUG_OPTION_COUNT = 6
 } sq_debug_option;
 sq_status sq_debug_set_option(sq_debug_option option, int32_t value);
