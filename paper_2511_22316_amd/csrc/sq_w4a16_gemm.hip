@@ -77,8 +77,9 @@ __device__ __forceinline__ void dma_16_if(const void *gptr, uint32_t lds_addr, i
                  : "memory", "m0", "scc");
 }
 
-// the tile that must have landed is followed by `rem` more tiles in flight at most one of which
-// may still be outstanding (L loads per wave and tile, in order); then the waves meet
+// Wait for a tile of the ring.  Behind it at most one more tile is in flight, if rem >= 1 (L loads
+// per loading wave and tile, and loads complete in order): then L loads may stay outstanding, else
+// none.  After that the wave's own LDS reads are drained and the waves meet.
 template <int L>
 __device__ __forceinline__ void wait_tile_then_barrier(int rem)
 {
@@ -109,7 +110,9 @@ __device__ __forceinline__ void wait_tile_then_barrier(int rem)
 // the channel in the register: register e holds channel 8 (e / 4) + 4 (lane / 32) + e % 4, four
 // runs of four consecutive channels.  Two runs are traded between the half-waves (one cross-half
 // swap per dword) and every lane stores 16 contiguous bytes of a row of Y.
-// BK: elements of K per tile, 64 or 128 (a tile row of activations is 2 BK bytes, of codes BK / 2).
+// BK: elements of K per tile (a tile row of activations is 2 BK bytes, of codes BK / 2); 64 is what
+// is built (128 was measured: 2 % faster at 2048 tokens, 10 % slower at 8192, and its 256-byte rows
+// would want another swizzle).
 // LW > 0: LW more waves that only request the tiles and wait for them; the multiplying waves then
 // issue no memory instruction inside the loop and meet the others at the barrier of each tile.
 template <int WM, int WN, int FM, int FN, int OCC, int BK, int LW>
@@ -118,7 +121,7 @@ __global__ __launch_bounds__((WM * WN + LW) * kWave, OCC) void w4a16_gemm_ring_k
     const float *__restrict__ sw, int N, __half *__restrict__ Y, int64_t ldy, int tiles_m, int tiles_n,
     int vec_store)
 {
-    static_assert(BK == 64 || BK == 128, "tiles of 64 or 128 elements of K");
+    static_assert(BK == 64, "tiles of 64 elements of K");
     constexpr int NW = WM * WN, NS = 3, STEPS = BK / 16;     // waves; ring stages; MFMA steps per K tile
     constexpr int BM = WM * FM * 32, BN = WN * FN * 32;
     constexpr int A_ROW = 2 * BK, B_ROW = BK / 2;            // bytes of a tile row
