@@ -361,6 +361,26 @@ def test_gemm_every_tile_launch_shape(oracle, case, T, K, N):
     assert half_ulp_distance(Yg, Yo).max() <= 1
 
 
+def test_gemm_seeded_random_shapes_bit_exact(oracle):
+    """Thirty shapes drawn from a seed (T up to 700, K a multiple of 32 up to 2304, N up to 3000, a
+    third of them with at most 64 tokens): whatever kernel and launch shape the dispatcher picks,
+    the int32 accumulators are the oracle's and Y is within one fp16 ulp."""
+    g = np.random.default_rng(20251122)
+    for case in range(30):
+        T = int(g.integers(1, 65)) if case % 3 == 0 else int(g.integers(65, 700))
+        K = 32 * int(g.integers(1, 73))
+        N = int(g.integers(1, 3000))
+        print(f"case gemm seeded shape {case}: T={T} K={K} N={N}", flush=True)
+        Qx = synth.random_codes(T, K, 700 + case)
+        Qw = synth.random_codes(N, K, 800 + case)
+        sx = g.uniform(0.05, 4.0, T).astype(np.float32)
+        sw = g.uniform(1e-4, 5e-3, N).astype(np.float32)
+        Yg, accg = run_gemm(Qx, sx, Qw, sw)
+        Yo, acco = oracle.gemm(Qx, sx, Qw, sw)
+        assert np.array_equal(accg, acco), f"accumulators differ at T={T} K={K} N={N}"
+        assert half_ulp_distance(Yg, Yo).max() <= 1
+
+
 def test_gemm_strided_output_and_empty(oracle):
     print("case gemm strided output / empty", flush=True)
     import torch

@@ -162,6 +162,22 @@ def test_w4a16_gemm_every_tile_kernel(oracle, shape, T, K, N):
         assert np.array_equal(goti, Yi)
 
 
+def test_w4a16_gemm_seeded_random_shapes(oracle):
+    """Twenty shapes drawn from a seed (T up to 400, K a multiple of 64 up to 1536, N up to 1500,
+    a third of them with at most 32 tokens), whatever kernel the dispatcher picks."""
+    g = np.random.default_rng(1122)
+    for case in range(20):
+        T = int(g.integers(1, 33)) if case % 3 == 0 else int(g.integers(33, 400))
+        K = 64 * int(g.integers(1, 25))
+        N = int(g.integers(1, 1500))
+        print(f"case w4a16 seeded shape {case}: T={T} K={K} N={N}", flush=True)
+        X = (g.standard_normal((T, K)) * g.choice([0.1, 1.0, 30.0], size=(T, 1))).astype(np.float16)
+        Qw = synth.random_codes(N, K, 900 + case)
+        sw = g.uniform(1e-4, 5e-3, N).astype(np.float32)
+        Yo, m = oracle.gemm_w4a16(X, Qw, sw, want_abs_sum=True)
+        check_w4a16(run_w4a16(X, Qw, sw), Yo, m, K)
+
+
 def test_w4a16_gemm_strided_and_empty(oracle):
     print("case w4a16 gemm strided output / input, empty", flush=True)
     import torch
