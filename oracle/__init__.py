@@ -56,6 +56,13 @@ def _load():
         lib.sqo_quantize_rows.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_void_p]
         lib.sqo_quantize_rows_f32.restype = C.c_int
         lib.sqo_quantize_rows_f32.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_void_p]
+        lib.sqo_quantize_rows_variant.restype = C.c_int
+        lib.sqo_quantize_rows_variant.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_int, C.c_double,
+                                                  C.c_void_p, C.c_void_p]
+        lib.sqo_pack_w3.restype = C.c_int
+        lib.sqo_pack_w3.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_void_p]
+        lib.sqo_unpack_w3.restype = C.c_int
+        lib.sqo_unpack_w3.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_void_p]
         lib.sqo_unpack_codes.restype = None
         lib.sqo_unpack_codes.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_void_p]
         lib.sqo_gemm.restype = C.c_int
@@ -173,6 +180,41 @@ def quantize_rows(Xrot):
     return Q, s
 
 
+def quantize_rows_variant(Xrot, bits: int = 4, clip_ratio: float = 1.0):
+    """The quantizer with ``bits`` bits (2..4) and a clipping ratio in (0, 1]: step
+    ratio * max|z| / (2^(bits-1) - 1), codes clamped to [-2^(bits-1), 2^(bits-1) - 1], stored as
+    nibbles.  fp64 input and decisions.  -> (Q uint8 [T, K/2], scales float32 [T])."""
+    Xrot = np.ascontiguousarray(Xrot, dtype=np.float64)
+    T, K = Xrot.shape
+    Q = np.empty((T, K // 2), np.uint8)
+    s = np.empty(T, np.float32)
+    if _load().sqo_quantize_rows_variant(_ptr(Xrot), T, K, int(bits), float(clip_ratio), _ptr(Q), _ptr(s)) != 0:
+        raise ValueError("quantize_rows_variant: bad argument")
+    return Q, s
+
+
+def pack_w3(Q) -> np.ndarray:
+    """Nibble codes [N, K/2] (all in [-4, 3], K % 64 == 0) -> 3-bit storage [N, 3K/8]."""
+    Q = _c(Q, np.uint8)
+    N, Kh = Q.shape
+    out = np.empty((N, 3 * Kh // 4), np.uint8)
+    rc = _load().sqo_pack_w3(_ptr(Q), N, 2 * Kh, _ptr(out))
+    if rc != 0:
+        raise ValueError(f"pack_w3 failed rc={rc}")
+    return out
+
+
+def unpack_w3(Q3) -> np.ndarray:
+    """3-bit storage [N, 3K/8] -> nibble codes [N, K/2]."""
+    Q3 = _c(Q3, np.uint8)
+    N, B = Q3.shape
+    K = B * 8 // 3
+    out = np.empty((N, K // 2), np.uint8)
+    if _load().sqo_unpack_w3(_ptr(Q3), N, K, _ptr(out)) != 0:
+        raise ValueError("unpack_w3: bad argument")
+    return out
+
+
 def unpack_codes(Q) -> np.ndarray:
     Q = _c(Q, np.uint8)
     T, Kh = Q.shape
@@ -242,6 +284,16 @@ def gemm_w4a16(Xh, Qw, sw, want_abs_sum=False):
     if rc != 0:
         raise ValueError("sqo_gemm_w4a16: bad argument")
     return (Y.view(np.float16), m) if want_abs_sum else Y.view(np.float16)
+
+
+def prepare_weights_variant(Wt_f16, giv_i, giv_j, giv_theta, R1, R2, bits=4, clip_ratio=1.0):
+    """prepare_weights with the b-bit / clipped quantizer (W3A16 of the weight-only table)."""
+    return quantize_rows_variant(rotate(Wt_f16, giv_i, giv_j, giv_theta, R1, R2), bits, clip_ratio)
+
+
+def gemm_w3a16(Xh, Qw3, sw, want_abs_sum=False):
+    """gemm_w4a16 on weights kept in the 3-bit storage."""
+    return gemm_w4a16(Xh, unpack_w3(Qw3), sw, want_abs_sum)
 
 
 # ------------------------------------------------------------------ Alg. 1 ---

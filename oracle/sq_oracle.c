@@ -22,6 +22,16 @@
  *   sqo_quantize_rows     the rounding quantizer of Sec. 3.2,
  *                         Q_D(z) = D floor(z/D + 1/2), with a per-row step
  *                         D = max|z| / 7 and codes clamped to [-8, 7].
+ *   sqo_quantize_rows_variant  the same quantizer Q_D of Sec. 3.2 with b bits
+ *                         (the W3A16 column of the weight-only table in the
+ *                         appendix) and a clipping ratio (the clipping
+ *                         thresholds named in the comparison with FlatQuant,
+ *                         read as a fixed fraction of the row maximum):
+ *                         D = ratio max|z| / (2^(b-1) - 1), codes clamped to
+ *                         [-2^(b-1), 2^(b-1) - 1].
+ *   sqo_pack_w3 / sqo_unpack_w3  storage of 3-bit codes in three bits each.  The
+ *                         paper does not give a storage format; the one used
+ *                         is stated at the function.
  *   sqo_gemm              Eq. 1 / Eq. (xw): (XR)(R^T W) evaluated on the integer
  *                         codes, then scaled back: y = acc * s_x * s_w.
  *   sqo_kron_factor       Alg. 1 (Kronecker dimension factorization).
@@ -29,7 +39,10 @@
  * Parity pins (tests/test_oracle_*.py): Lemma 1's closed form and a brute
  * force over theta; explicit dense kron(R1,R2) from numpy; norm and inner
  * product preservation; XW = (XR)(R^T W); hand-worked rounding ties;
- * brute-force integer GEMM; fp16 conversion against IEEE binary16 tables.
+ * brute-force integer GEMM; fp16 conversion against IEEE binary16 tables;
+ * the variant quantizer against sqo_quantize_rows at b = 4, ratio 1, against
+ * hand-worked rows at b = 3 and at ratio 1/2, and against its error bound;
+ * the 3-bit storage against bytes worked out by hand from the format.
  * No function here is "parity unpinned".
  */
 #include <math.h>
@@ -247,6 +260,45 @@ int sqo_quantize_rows_f32(const float *Xrot, int64_t T, int K,
     return 0;
 }
 
+/* The quantizer with b bits and a clipping ratio.  Levels: the integers
+   -2^(b-1) .. 2^(b-1) - 1 (Sec. 3.2 rounds to the grid D Z; b bits keep that
+   many of its points around zero).  Step D = ratio max|z| / (2^(b-1) - 1),
+   evaluated in fp64 and rounded to fp32 (D = 1 for an all-zero row);
+   code = clamp(floor(z/D + 1/2), -2^(b-1), 2^(b-1) - 1) decided in fp64.
+   With b = 4 and ratio = 1 this is sqo_quantize_rows.  Codes are stored as
+   two's-complement nibbles whatever b is.  2 <= bits <= 4, 0 < ratio <= 1. */
+int sqo_quantize_rows_variant(const double *Xrot, int64_t T, int K, int bits,
+                              double ratio, uint8_t *Q, float *scales)
+{
+    if (K <= 0 || (K & 1) || bits < 2 || bits > 4) return -1;
+    if (!(ratio > 0.0) || ratio > 1.0) return -1;
+    const double top = (double)((1 << (bits - 1)) - 1);
+    const double bottom = -(double)(1 << (bits - 1));
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        const double *z = Xrot + t * (int64_t)K;
+        double amax = 0.0;
+        for (int k = 0; k < K; ++k) {
+            double a = fabs(z[k]);
+            if (a > amax) amax = a;
+        }
+        float D = (amax == 0.0) ? 1.0f : (float)(ratio * amax / top);
+        scales[t] = D;
+        for (int k = 0; k < K; k += 2) {
+            int q[2];
+            for (int u = 0; u < 2; ++u) {
+                double c = floor(z[k + u] / (double)D + 0.5);
+                if (c < bottom) c = bottom;
+                if (c > top) c = top;
+                q[u] = (int)c;
+            }
+            Q[t * (int64_t)(K / 2) + k / 2] =
+                (uint8_t)(nibble(q[0]) | (nibble(q[1]) << 4));
+        }
+    }
+    return 0;
+}
+
 /* Signed value of nibble number k of a packed row. */
 static int code_at(const uint8_t *rowq, int k)
 {
@@ -260,6 +312,78 @@ void sqo_unpack_codes(const uint8_t *Q, int64_t T, int K, int8_t *codes)
     for (int64_t t = 0; t < T; ++t)
         for (int k = 0; k < K; ++k)
             codes[t * (int64_t)K + k] = (int8_t)code_at(Q + t * (int64_t)(K / 2), k);
+}
+
+/* ------------------------------------------ 3-bit storage (W3A16) --------- */
+
+/* Where code number k of a row lives in the 3-bit storage.  The paper gives no
+   format; this one is the library's (stated in its header) and is written
+   out here from that statement, not from the library's code:
+     - a row of K codes (K a multiple of 64) takes 3K/8 bytes: 24 bytes for
+       every 64 codes, read as six little-endian 32-bit words w[0..5];
+     - code k = 64 g + 32 h + 8 m + i  (h in 0..1, m in 0..3, i in 0..7) is
+       stored as u = code + 4 in 0..7;
+     - the two low bits of u are bits 4i + 2 (m % 2) and the next one of word
+       w[3h + m / 2] of group g;
+     - the high bit of u is bit 4i + m of word w[3h + 2] of group g. */
+static void w3_place(int k, int64_t *word_lo, int *bit_lo, int64_t *word_hi, int *bit_hi)
+{
+    int g = k / 64, h = (k / 32) % 2, m = (k / 8) % 4, i = k % 8;
+    *word_lo = 6 * (int64_t)g + 3 * h + m / 2;
+    *bit_lo = 4 * i + 2 * (m % 2);
+    *word_hi = 6 * (int64_t)g + 3 * h + 2;
+    *bit_hi = 4 * i + m;
+}
+
+static void w3_set_bit(uint8_t *row, int64_t word, int bit)
+{
+    row[4 * word + bit / 8] |= (uint8_t)(1u << (bit % 8));     /* little endian */
+}
+
+static int w3_get_bit(const uint8_t *row, int64_t word, int bit)
+{
+    return (row[4 * word + bit / 8] >> (bit % 8)) & 1;
+}
+
+/* Q: [N, K/2] nibble codes, every code in [-4, 3] (else -2 is returned);
+   Q3: [N, 3K/8] bytes. */
+int sqo_pack_w3(const uint8_t *Q, int64_t N, int K, uint8_t *Q3)
+{
+    if (K <= 0 || (K % 64)) return -1;
+    memset(Q3, 0, (size_t)N * (size_t)(3 * K / 8));
+    for (int64_t n = 0; n < N; ++n) {
+        uint8_t *row = Q3 + n * (int64_t)(3 * K / 8);
+        for (int k = 0; k < K; ++k) {
+            int c = code_at(Q + n * (int64_t)(K / 2), k);
+            if (c < -4 || c > 3) return -2;
+            int u = c + 4, bl, bh;
+            int64_t wl, wh;
+            w3_place(k, &wl, &bl, &wh, &bh);
+            if (u & 1) w3_set_bit(row, wl, bl);
+            if (u & 2) w3_set_bit(row, wl, bl + 1);
+            if (u & 4) w3_set_bit(row, wh, bh);
+        }
+    }
+    return 0;
+}
+
+/* Back to nibble codes: Q3 [N, 3K/8] -> Q [N, K/2]. */
+int sqo_unpack_w3(const uint8_t *Q3, int64_t N, int K, uint8_t *Q)
+{
+    if (K <= 0 || (K % 64)) return -1;
+    memset(Q, 0, (size_t)N * (size_t)(K / 2));
+    for (int64_t n = 0; n < N; ++n) {
+        const uint8_t *row = Q3 + n * (int64_t)(3 * K / 8);
+        for (int k = 0; k < K; ++k) {
+            int bl, bh;
+            int64_t wl, wh;
+            w3_place(k, &wl, &bl, &wh, &bh);
+            int u = w3_get_bit(row, wl, bl) | (w3_get_bit(row, wl, bl + 1) << 1) |
+                    (w3_get_bit(row, wh, bh) << 2);
+            Q[n * (int64_t)(K / 2) + k / 2] |= (uint8_t)(nibble(u - 4) << ((k & 1) * 4));
+        }
+    }
+    return 0;
 }
 
 /* ---------------------------------------------------- Eq. 1 on the codes -- */

@@ -397,3 +397,125 @@ def test_weight_only_pipeline_reproduces_xw(oracle):
     # and the quantized product differs from that one by the weight rounding only: |dW| <= s/2
     bound = np.abs(xh.astype(np.float64)) @ np.tile((sw.astype(np.float64) / 2)[None, :], (cfg.K, 1))
     assert np.all(np.abs(Y - exact) <= bound * (1 + 1e-6) + 2.0 ** -10 * np.abs(exact))
+
+
+# ------------------------------- quantizer with b bits and a clipping ratio; 3-bit storage --
+
+def test_variant_quantizer_reduces_to_the_four_bit_one(oracle):
+    """b = 4, ratio 1 is the quantizer of Sec. 3.2 as sqo_quantize_rows writes it: same bytes,
+    same steps, on rotated outlier-laden rows."""
+    cfg, L = _tiny_layer()
+    Xr = oracle.rotate(L.X, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)
+    Q0, s0 = oracle.quantize_rows(Xr)
+    Q1, s1 = oracle.quantize_rows_variant(Xr, 4, 1.0)
+    assert np.array_equal(Q0, Q1) and np.array_equal(s0, s1)
+
+
+def test_variant_quantizer_hand_worked_rows(oracle):
+    # three bits: levels -4 .. 3, step max|z| / 3 = 1; ties go up (floor(z + 1/2))
+    z = np.array([[3.0, -3.0, 1.4, 1.6, -0.5, 0.5, 2.5, -2.5]])
+    Q, s = oracle.quantize_rows_variant(z, 3, 1.0)
+    assert s[0] == 1.0 and _codes(Q)[0].tolist() == [3, -3, 1, 2, 0, 1, 3, -2]
+    # ratio 1/2 at four bits: step 0.5 * 14 / 7 = 1; what lies beyond the levels is clamped to -8, 7
+    z = np.array([[14.0, -14.0, 9.0, -12.0, 3.5, -3.5, 0.49, 7.5, -8.5, -8.6]])
+    Q, s = oracle.quantize_rows_variant(z, 4, 0.5)
+    assert s[0] == 1.0 and _codes(Q)[0].tolist() == [7, -8, 7, -8, 4, -3, 0, 7, -8, -8]
+    # two bits: levels -2 .. 1, step max|z|
+    Q, s = oracle.quantize_rows_variant(np.array([[2.0, -2.0, 0.9, -1.1, -3.1, 1.1]]), 2, 1.0)
+    assert s[0] == np.float32(3.1) and _codes(Q)[0].tolist() == [1, -1, 0, 0, -1, 0]
+    # zero row
+    Q, s = oracle.quantize_rows_variant(np.zeros((1, 4)), 3, 0.7)
+    assert s[0] == 1.0 and np.all(Q == 0)
+    for bad in [(1, 1.0), (5, 1.0), (4, 0.0), (4, 1.5), (4, float("nan"))]:
+        with pytest.raises(ValueError):
+            oracle.quantize_rows_variant(np.ones((1, 4)), *bad)
+
+
+@pytest.mark.parametrize("bits,ratio", [(3, 1.0), (4, 0.8), (3, 0.6), (2, 1.0)])
+def test_variant_quantizer_error_bound_and_range(oracle, bits, ratio):
+    """Inside the clipping range the rounding error is at most half a step (Sec. 3.2: the
+    boundaries sit at (k + 1/2) D); outside, the code is the nearest end level; the step is
+    ratio max|z| / (2^(b-1) - 1)."""
+    cfg, L = _tiny_layer()
+    Xr = oracle.rotate(L.X, L.giv_i, L.giv_j, L.giv_theta, L.R1, L.R2)
+    Q, s = oracle.quantize_rows_variant(Xr, bits, ratio)
+    q = _codes(Q).astype(np.float64)
+    top, bottom = 2 ** (bits - 1) - 1, -(2 ** (bits - 1))
+    assert q.min() >= bottom and q.max() <= top
+    s64 = s.astype(np.float64)[:, None]
+    np.testing.assert_allclose(s, ratio * np.max(np.abs(Xr), axis=1) / top, rtol=1e-6)
+    inside = (Xr >= (bottom - 0.5) * s64) & (Xr < (top + 0.5) * s64)
+    assert np.all(np.abs(Xr - q * s64)[inside] <= 0.5 * s64.repeat(Xr.shape[1], 1)[inside] * (1 + 1e-6))
+    assert np.all(q[Xr >= (top + 0.5) * s64] == top) and np.all(q[Xr < (bottom - 0.5) * s64] == bottom)
+    if ratio == 1.0:
+        assert inside.all() and np.all(np.max(np.abs(q), axis=1) >= top)
+    else:
+        assert not inside.all()              # the case does clip
+
+
+def test_w3_storage_matches_the_hand_worked_bytes(oracle):
+    import os
+    codes = np.full(64, -4, np.int64)
+    want = np.zeros(24, np.uint8)
+    with open(os.path.join(os.path.dirname(__file__), "golden", "w3_storage_example.txt")) as f:
+        for line in f:
+            parts = line.split()
+            if not parts or parts[0].startswith("#"):
+                continue
+            if parts[0] == "code":
+                codes[int(parts[1])] = int(parts[2])
+            else:
+                want[int(parts[1])] = int(parts[2], 16)
+    nib = (codes & 0xF).astype(np.uint8)
+    Q = (nib[0::2] | (nib[1::2] << 4))[None, :]
+    Q3 = oracle.pack_w3(Q)
+    assert Q3.shape == (1, 24) and Q3[0].tolist() == want.tolist()
+    assert np.array_equal(oracle.unpack_w3(Q3), Q)
+
+
+def test_w3_storage_is_a_bijection_on_every_position(oracle):
+    """Every (position, value) changes its own bits only: a row with one code raised from -4 to
+    v has exactly popcount(v + 4) bits set, bit sets of different positions are disjoint, and
+    packing then unpacking returns every row; three bits per code exactly (3K/8 bytes)."""
+    K = 128
+    seen = np.zeros((K, 3 * K // 8), np.uint8)
+    for k in range(K):
+        codes = np.full(K, -4, np.int64)
+        codes[k] = 3
+        nib = (codes & 0xF).astype(np.uint8)
+        Q = (nib[0::2] | (nib[1::2] << 4))[None, :]
+        seen[k] = oracle.pack_w3(Q)[0]
+        assert int(np.unpackbits(seen[k]).sum()) == 3
+        for v in range(-4, 4):
+            codes[k] = v
+            nib = (codes & 0xF).astype(np.uint8)
+            Qv = (nib[0::2] | (nib[1::2] << 4))[None, :]
+            pv = oracle.pack_w3(Qv)[0]
+            assert int(np.unpackbits(pv).sum()) == bin(v + 4).count("1")
+            assert np.all((pv & ~seen[k]) == 0)
+    assert np.all(np.bitwise_or.reduce(seen, axis=0) == 0xFF)          # every stored bit is used ...
+    assert int(np.unpackbits(seen).sum()) == 3 * K                          # ... by exactly one position
+    # codes 64 .. 127 live in the second 24 bytes, laid out like the first
+    assert np.all(seen[:64, 24:] == 0) and np.array_equal(seen[64:, 24:], seen[:64, :24])
+    g = np.random.default_rng(3)
+    codes = g.integers(-4, 4, size=(5, 256))
+    nib = (codes & 0xF).astype(np.uint8)
+    Q = nib[:, 0::2] | (nib[:, 1::2] << 4)
+    assert np.array_equal(oracle.unpack_w3(oracle.pack_w3(Q)), Q)
+    bad = Q.copy()
+    bad[0, 0] = 0x07                                                     # code 7 is not a 3-bit code
+    with pytest.raises(ValueError):
+        oracle.pack_w3(bad)
+
+
+def test_gemm_w3a16_is_the_weight_only_product_on_three_bit_codes(oracle):
+    g = np.random.default_rng(12)
+    T, K, N = 3, 64, 5
+    X = g.standard_normal((T, K)).astype(np.float16)
+    codes = g.integers(-4, 4, size=(N, K))
+    nib = (codes & 0xF).astype(np.uint8)
+    Q = nib[:, 0::2] | (nib[:, 1::2] << 4)
+    sw = g.uniform(1e-2, 1e-1, N).astype(np.float32)
+    Y = oracle.gemm_w3a16(X, oracle.pack_w3(Q), sw).astype(np.float64)
+    want = X.astype(np.float64) @ (codes * sw.astype(np.float64)[:, None]).T
+    assert np.all(np.abs(Y - want) <= 2.0 ** -11 * np.abs(want) + 1e-300)
