@@ -322,6 +322,24 @@ def measure_weight_only(cfg, torch, sq, synth, steps, warmup):
     if T <= 32:      # decode-shaped: one pass over the weight codes, HBM-bound
         out["gemm_weight_stream_GBps"] = N * K / 2.0 / (g["mean_us"] * 1e-6) / 1e9
         out["gemm_frac_of_hbm_peak"] = out["gemm_weight_stream_GBps"] / HBM_PEAK_GBPS
+        # W3A16: the same weights through the 3-bit quantizer and the 3-bit storage (3K/8 bytes a row)
+        dev = B.Y[0].device
+        Q3n = torch.empty((N, K // 2), dtype=torch.uint8, device=dev)
+        s3 = torch.empty((N,), dtype=torch.float32, device=dev)
+        for lo in range(0, N, 4096):
+            hi = min(N, lo + 4096)
+            Wt = torch.from_numpy(synth.weight_rows_t(cfg, np.arange(lo, hi))).to(dev)
+            sq.sq_rotate_quantize_variant(Wt, L.giv_i, L.giv_j, L.giv_theta, B.R1, B.R2, 3, 1.0, Q3n[lo:hi], s3[lo:hi])
+        Q3 = []
+        for i in range(B.sets):
+            Q3.append(torch.empty((N, 3 * K // 8), dtype=torch.uint8, device=dev))
+            sq.sq_pack_w3(Q3n if i == 0 else torch.roll(Q3n, shifts=5 * i, dims=0).contiguous(), Q3[i])
+        del Q3n
+        g3 = kernel_time(torch, lambda i: sq.sq_w3a16_gemm(Xr[i], Q3[i], s3, B.Y[i]), B.sets, steps, warmup)
+        out["w3a16_gemm_us"] = g3["mean_us"]
+        out["w3a16_weight_stream_GBps"] = N * K * 3.0 / 8.0 / (g3["mean_us"] * 1e-6) / 1e9
+        out["w3a16_frac_of_hbm_peak"] = out["w3a16_weight_stream_GBps"] / HBM_PEAK_GBPS
+        del Q3
     del B, Xr
     torch.cuda.empty_cache()
     return out

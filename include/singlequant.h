@@ -170,7 +170,10 @@ sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T, int32_t K,
  *     Y        device out, fp16 [T, ldy], ldy >= N
  *   Requires K % 64 == 0, K <= 131072.  T == 0 or N == 0 is legal and enqueues
  *   nothing.
- * W3A16 (three-bit codes) is not provided.
+ * Three-bit weights (W3A16, the other column of that table): codes written by
+ * sq_prepare_weights_variant with bits = 3 lie in [-4, 3] and are legal input
+ * here as they are (one nibble each); sq_pack_w3 / sq_w3a16_gemm below keep
+ * them in three bits each.
  */
 sq_status sq_rotate_fp16(const void *X, int64_t T, int32_t K, int64_t ldx,
                          const int32_t *giv_i, const int32_t *giv_j,
@@ -179,6 +182,38 @@ sq_status sq_rotate_fp16(const void *X, int64_t T, int32_t K, int64_t ldx,
                          void *Xrot, int64_t ldo, void *stream);
 sq_status sq_w4a16_gemm(const void *X, int64_t T, int32_t K, int64_t ldx,
                         const uint8_t *Qw, const float *sw, int32_t N,
+                        void *Y, int64_t ldy, void *stream);
+
+/*
+ * sq_pack_w3 / sq_w3a16_gemm -- W3A16 of the same table with the weight codes
+ * stored in three bits each, 3K/8 bytes per output channel.  The paper gives
+ * no storage format; this one is the library's, chosen so that eight codes
+ * become one dword of nibbles in two to four instructions:
+ *   - a row of K codes takes 24 bytes per 64 codes, read as six little-endian
+ *     32-bit words w[0..5];
+ *   - code k = 64 g + 32 h + 8 m + i  (h in 0..1, m in 0..3, i in 0..7) is
+ *     stored as u = code + 4 in 0..7;
+ *   - the two low bits of u are bits 4i + 2 (m % 2) and the next one of word
+ *     w[3h + m / 2] of group g; the high bit of u is bit 4i + m of w[3h + 2].
+ *
+ * sq_pack_w3      nibble codes -> 3-bit storage (offline, once per layer).
+ *     Qw    device, uint8 [N, K/2], 16-byte aligned, every code in [-4, 3]
+ *           (the low three bits of code + 4 are kept of any other)
+ *     Qw3   device out, uint8 [N, 3K/8], 8-byte aligned
+ *   Requires K % 64 == 0, K <= 131072.
+ *
+ * sq_w3a16_gemm   Y[t, n] = fp16( sw[n] * sum_k X[t, k] * Qw3[n, k] ), as
+ *   sq_w4a16_gemm.  The kernel is the decode-shaped one (one pass over the
+ *   weights per 16 tokens, which is where the smaller storage pays); for many
+ *   tokens keep the codes as nibbles and call sq_w4a16_gemm.
+ *     X, sw, Y as sq_w4a16_gemm; Qw3 device, 8-byte aligned
+ *   Requires K % 256 == 0, K <= 131072, T <= SQ_W3A16_MAX_ROWS.
+ * T == 0 or N == 0 is legal and enqueues nothing.
+ */
+#define SQ_W3A16_MAX_ROWS (16 * 65535)
+sq_status sq_pack_w3(const uint8_t *Qw, int32_t K, int32_t N, uint8_t *Qw3, void *stream);
+sq_status sq_w3a16_gemm(const void *X, int64_t T, int32_t K, int64_t ldx,
+                        const uint8_t *Qw3, const float *sw, int32_t N,
                         void *Y, int64_t ldy, void *stream);
 
 /*
@@ -294,6 +329,42 @@ sq_status sq_prepare_weights(const void *W, int32_t K, int32_t N, int64_t ldw,
                              const void *R2, int32_t n2,
                              void *workspace, uint8_t *Qw, float *sw,
                              void *stream);
+
+/*
+ * sq_rotate_quantize_variant / sq_prepare_weights_variant -- the same two calls
+ * with the quantizer of Sec. 3.2 taken at `bits` bits and with a clipping ratio:
+ *
+ *   step = clip_ratio * max|x'| / (2^(bits-1) - 1)      (1 for an all-zero row)
+ *   code = clamp( floor(x' / step + 1/2), -2^(bits-1), 2^(bits-1) - 1 )
+ *
+ * bits = 3 is the W3A16 column of the weight-only table in the appendix.
+ * clip_ratio is a reading: the paper names learnable clipping thresholds in
+ * its comparison with FlatQuant and does not define the operation; here the
+ * threshold is a fixed fraction of the row maximum, chosen by the caller, and
+ * entries beyond it take the end levels.  Codes are written as two's-complement
+ * nibbles whatever `bits` is, so every GEMM of this library takes them.
+ *
+ *   bits        2, 3 or 4, else SQ_ERR_SHAPE
+ *   clip_ratio  in (0, 1], else SQ_ERR_SHAPE
+ * All other arguments, limits and errors as sq_rotate_quantize /
+ * sq_prepare_weights, which are these calls with bits = 4, clip_ratio = 1.
+ */
+sq_status sq_rotate_quantize_variant(const void *X, int64_t T, int32_t K, int64_t ldx,
+                                     const int32_t *giv_i, const int32_t *giv_j,
+                                     const float *giv_theta, int32_t P,
+                                     const void *R1, int32_t n1,
+                                     const void *R2, int32_t n2,
+                                     int32_t bits, float clip_ratio,
+                                     uint8_t *Q, float *scales, float *xrot_dbg,
+                                     void *stream);
+sq_status sq_prepare_weights_variant(const void *W, int32_t K, int32_t N, int64_t ldw,
+                                     const int32_t *giv_i, const int32_t *giv_j,
+                                     const float *giv_theta, int32_t P,
+                                     const void *R1, int32_t n1,
+                                     const void *R2, int32_t n2,
+                                     int32_t bits, float clip_ratio,
+                                     void *workspace, uint8_t *Qw, float *sw,
+                                     void *stream);
 
 /*
  * sq_kron_factor -- Kronecker dimension factorization (Alg. 1): n2 is the power

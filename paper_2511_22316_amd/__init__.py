@@ -19,11 +19,15 @@ from .binding import (  # noqa: F401
     sq_decode_layer_workspace_bytes,
     sq_kron_factor,
     sq_prepare_rotation,
+    sq_pack_w3,
     sq_prepare_weights,
+    sq_prepare_weights_variant,
     sq_prepared_rotation_bytes,
     sq_rotate_fp16,
     sq_rotate_quantize,
     sq_rotate_quantize_prepared,
+    sq_rotate_quantize_variant,
+    sq_w3a16_gemm,
     sq_w4a4_gemm,
     sq_w4a16_gemm,
     sq_status_string,

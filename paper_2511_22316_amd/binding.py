@@ -82,6 +82,22 @@ def _load():
         lib.sq_w4a16_gemm.argtypes = [
             C.c_void_p, C.c_int64, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_int32,
             C.c_void_p, C.c_int64, C.c_void_p]
+        lib.sq_w3a16_gemm.restype = C.c_int
+        lib.sq_w3a16_gemm.argtypes = lib.sq_w4a16_gemm.argtypes
+        lib.sq_pack_w3.restype = C.c_int
+        lib.sq_pack_w3.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        lib.sq_rotate_quantize_variant.restype = C.c_int
+        lib.sq_rotate_quantize_variant.argtypes = [
+            C.c_void_p, C.c_int64, C.c_int32, C.c_int64,
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+            C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_float,
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.sq_prepare_weights_variant.restype = C.c_int
+        lib.sq_prepare_weights_variant.argtypes = [
+            C.c_void_p, C.c_int32, C.c_int32, C.c_int64,
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+            C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_int32, C.c_float,
+            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.sq_decode_layer_status.restype = C.c_int
         lib.sq_decode_layer_status.argtypes = [C.c_void_p, C.c_void_p]
         lib.sq_w4a4_gemm.restype = C.c_int
@@ -165,6 +181,22 @@ def sq_rotate_quantize(X, giv_i, giv_j, giv_theta, R1, R2, Q, scales, xrot_dbg=N
     _check(code)
 
 
+def sq_rotate_quantize_variant(X, giv_i, giv_j, giv_theta, R1, R2, bits, clip_ratio, Q, scales, xrot_dbg=None,
+                               stream=None) -> None:
+    """sq_rotate_quantize with the quantizer at ``bits`` bits (2..4) and a clipping ratio in (0, 1]."""
+    gi, gj, gt = _host(giv_i, np.int32), _host(giv_j, np.int32), _host(giv_theta, np.float32)
+    P = 0 if gi is None else int(gi.size)
+    T, K = int(X.shape[0]), int(X.shape[1])
+    ldx = int(X.stride(0)) if T > 1 else K
+    code = _load().sq_rotate_quantize_variant(
+        _dev_ptr(X), T, K, ldx,
+        None if gi is None else gi.ctypes.data, None if gj is None else gj.ctypes.data,
+        None if gt is None else gt.ctypes.data, P,
+        _dev_ptr(R1), int(R1.shape[0]), _dev_ptr(R2), int(R2.shape[0]), int(bits), float(clip_ratio),
+        _dev_ptr(Q), _dev_ptr(scales), _dev_ptr(xrot_dbg), _stream_handle(stream))
+    _check(code)
+
+
 def sq_prepared_rotation_bytes(n1: int, n2: int) -> int:
     return int(_load().sq_prepared_rotation_bytes(int(n1), int(n2)))
 
@@ -239,6 +271,26 @@ def sq_w4a16_gemm(X, Qw, sw, Y, stream=None) -> None:
                                  _stream_handle(stream)))
 
 
+def sq_pack_w3(Qw, Qw3, stream=None) -> None:
+    """Nibble codes Qw uint8 [N, K/2] (all in [-4, 3]) -> 3-bit storage Qw3 uint8 [N, 3K/8]."""
+    N, K = int(Qw.shape[0]), 2 * int(Qw.shape[1])
+    if Qw3 is not None and tuple(Qw3.shape) != (N, 3 * K // 8):
+        raise ValueError("Qw3 must be [N, 3K/8]")
+    _check(_load().sq_pack_w3(_dev_ptr(Qw), K, N, _dev_ptr(Qw3), _stream_handle(stream)))
+
+
+def sq_w3a16_gemm(X, Qw3, sw, Y, stream=None) -> None:
+    """sq_w4a16_gemm on weight codes in the 3-bit storage: Qw3 uint8 [N, 3K/8]."""
+    T, K = int(X.shape[0]), int(X.shape[1])
+    N = int(Qw3.shape[0])
+    if int(Qw3.shape[1]) * 8 != 3 * K:
+        raise ValueError("Qw3 must be [N, 3K/8]")
+    ldx = int(X.stride(0)) if T > 1 else K
+    ldy = int(Y.stride(0)) if T > 1 else max(N, 1)
+    _check(_load().sq_w3a16_gemm(_dev_ptr(X), T, K, ldx, _dev_ptr(Qw3), _dev_ptr(sw), N, _dev_ptr(Y), ldy,
+                                 _stream_handle(stream)))
+
+
 def sq_decode_layer_workspace_bytes(T: int, K: int) -> int:
     return int(_load().sq_decode_layer_workspace_bytes(int(T), int(K)))
 
@@ -309,6 +361,24 @@ def sq_prepare_weights(W, giv_i, giv_j, giv_theta, R1, R2, workspace, Qw, sw, st
         None if gi is None else gi.ctypes.data, None if gj is None else gj.ctypes.data,
         None if gt is None else gt.ctypes.data, P,
         _dev_ptr(R1), int(R1.shape[0]), _dev_ptr(R2), int(R2.shape[0]),
+        _dev_ptr(workspace), _dev_ptr(Qw), _dev_ptr(sw), _stream_handle(stream))
+    _check(code)
+
+
+def sq_prepare_weights_variant(W, giv_i, giv_j, giv_theta, R1, R2, bits, clip_ratio, workspace, Qw, sw,
+                               stream=None) -> None:
+    """sq_prepare_weights with the quantizer at ``bits`` bits (2..4) and a clipping ratio in (0, 1]."""
+    gi, gj, gt = _host(giv_i, np.int32), _host(giv_j, np.int32), _host(giv_theta, np.float32)
+    P = 0 if gi is None else int(gi.size)
+    K, N = int(W.shape[0]), int(W.shape[1])
+    ldw = int(W.stride(0)) if K > 1 else max(N, 1)
+    if workspace is not None and workspace.numel() < N * K:
+        raise ValueError("workspace holds fewer than N*K elements")
+    code = _load().sq_prepare_weights_variant(
+        _dev_ptr(W), K, N, ldw,
+        None if gi is None else gi.ctypes.data, None if gj is None else gj.ctypes.data,
+        None if gt is None else gt.ctypes.data, P,
+        _dev_ptr(R1), int(R1.shape[0]), _dev_ptr(R2), int(R2.shape[0]), int(bits), float(clip_ratio),
         _dev_ptr(workspace), _dev_ptr(Qw), _dev_ptr(sw), _stream_handle(stream))
     _check(code)
 

@@ -56,19 +56,20 @@ __global__ __launch_bounds__(256) void transpose_fp16_kernel(const __half *__res
 
 }  // namespace sq
 
-extern "C" sq_status sq_prepare_weights(const void *W, int32_t K, int32_t N, int64_t ldw,
-                                        const int32_t *giv_i, const int32_t *giv_j,
-                                        const float *giv_theta, int32_t P, const void *R1, int32_t n1,
-                                        const void *R2, int32_t n2, void *workspace, uint8_t *Qw,
-                                        float *sw, void *stream)
+extern "C" sq_status sq_prepare_weights_variant(const void *W, int32_t K, int32_t N, int64_t ldw,
+                                                const int32_t *giv_i, const int32_t *giv_j,
+                                                const float *giv_theta, int32_t P, const void *R1,
+                                                int32_t n1, const void *R2, int32_t n2, int32_t bits,
+                                                float clip_ratio, void *workspace, uint8_t *Qw,
+                                                float *sw, void *stream)
 {
     if (N < 0 || K <= 0 || ldw < N) return SQ_ERR_SHAPE;
     if (N > 0 && (!W || !workspace)) return SQ_ERR_NULL;
     if (((uintptr_t)W & 1) || ((uintptr_t)workspace & 15)) return SQ_ERR_ALIGN;
     // every other check (shape limits, Givens indices, R1/R2/Qw/sw pointers) is the row kernel's;
     // run it on an empty batch first so that nothing is enqueued when an argument is bad
-    const sq_status pre = sq_rotate_quantize(workspace, 0, K, K, giv_i, giv_j, giv_theta, P, R1, n1, R2, n2,
-                                             Qw, sw, nullptr, stream);
+    const sq_status pre = sq_rotate_quantize_variant(workspace, 0, K, K, giv_i, giv_j, giv_theta, P, R1, n1, R2, n2,
+                                                     bits, clip_ratio, Qw, sw, nullptr, stream);
     if (pre != SQ_OK) return pre;
     if (N == 0) return SQ_OK;
     if (!Qw || !sw) return SQ_ERR_NULL;
@@ -78,6 +79,16 @@ extern "C" sq_status sq_prepare_weights(const void *W, int32_t K, int32_t N, int
                        static_cast<__half *>(workspace),
                        (((uintptr_t)W & 7) == 0 && (ldw % 4) == 0 && (K % 4) == 0) ? 1 : 0);
     if (hipGetLastError() != hipSuccess) return SQ_ERR_LAUNCH;
-    return sq_rotate_quantize(workspace, N, K, K, giv_i, giv_j, giv_theta, P, R1, n1, R2, n2, Qw, sw, nullptr,
-                              stream);
+    return sq_rotate_quantize_variant(workspace, N, K, K, giv_i, giv_j, giv_theta, P, R1, n1, R2, n2, bits,
+                                      clip_ratio, Qw, sw, nullptr, stream);
+}
+
+extern "C" sq_status sq_prepare_weights(const void *W, int32_t K, int32_t N, int64_t ldw,
+                                        const int32_t *giv_i, const int32_t *giv_j,
+                                        const float *giv_theta, int32_t P, const void *R1, int32_t n1,
+                                        const void *R2, int32_t n2, void *workspace, uint8_t *Qw,
+                                        float *sw, void *stream)
+{
+    return sq_prepare_weights_variant(W, K, N, ldw, giv_i, giv_j, giv_theta, P, R1, n1, R2, n2, 4, 1.0f,
+                                      workspace, Qw, sw, stream);
 }

@@ -14,14 +14,16 @@ namespace sq {
 //   stage 0  x <- x G_1 ... G_P                 (one lane, in list order: pairs may overlap)
 //   stage A  Z = X_mat R2                       (n1 x n2) (n2 x n2)
 //   stage B  Y = R1^T Z                         (n1 x n1)^T (n1 x n2)
-//   stage Q  s = max|Y| / 7, codes = floor(Y / s + 1/2), two nibbles per byte
+//   stage Q  s = max|Y| / 7, codes = floor(Y / s + 1/2), two nibbles per byte (in general
+//            s = max|Y| / (q_top / clip) and codes clamped to [-q_top - 1, q_top])
 // ------------------------------------------------------------------------------------------
 constexpr int kGenThreads = 256;
 
 __global__ __launch_bounds__(kGenThreads) void rotate_quantize_generic_kernel(
     const __half *__restrict__ X, int64_t ldx, int K, int n1, int n2, GivensList giv,
     const __half *__restrict__ R1, const __half *__restrict__ R2, uint8_t *__restrict__ Q,
-    float *__restrict__ scales, float *__restrict__ xrot, __half *__restrict__ xout, int64_t ldo)
+    float *__restrict__ scales, float *__restrict__ xrot, __half *__restrict__ xout, int64_t ldo,
+    float q_top, float q_div)
 {
     extern __shared__ float smem[];
     float *xs = smem;          // [K]  token row, then reused for Y
@@ -96,7 +98,7 @@ __global__ __launch_bounds__(kGenThreads) void rotate_quantize_generic_kernel(
     }
     amax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 
-    const float step = (amax == 0.f) ? 1.0f : amax / 7.0f;
+    const float step = (amax == 0.f) ? 1.0f : amax / q_div;             // q_div = q_top / clip; 7: max|Y| / 7
     if (tid == 0) scales[t] = step;
 
     uint32_t *qrow = reinterpret_cast<uint32_t *>(Q + t * (int64_t)(K / 2));
@@ -105,7 +107,7 @@ __global__ __launch_bounds__(kGenThreads) void rotate_quantize_generic_kernel(
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             float v = floorf(xs[c * 8 + u] / step + 0.5f);
-            v = fminf(fmaxf(v, -8.0f), 7.0f);
+            v = fminf(fmaxf(v, -q_top - 1.0f), q_top);
             word |= (static_cast<uint32_t>(static_cast<int>(v)) & 0xFu) << (4 * u);
         }
         qrow[c] = word;
@@ -151,6 +153,9 @@ static bool build_rotq_plan(const GivensList &giv, int n2, RotqPlan &plan)
         if (lv > levels) levels = lv;
     }
     plan.n_levels = levels;
+    plan.q_top = 7.0f;                        // four bits, no clipping, unless a call says otherwise
+    plan.clip = 1.0f;
+    plan.q_div = 7.0f;
     memset(plan.pair_level, 0xFF, sizeof(plan.pair_level));
     int pos = 0;
     for (int lv = 0; lv < levels; ++lv) {          // stable: list order is kept inside a level
@@ -326,8 +331,11 @@ static sq_status rotate_quantize_any(const void *X, int64_t T, int32_t K, int64_
                                      const float *giv_theta, int32_t P, const void *R1,
                                      int32_t n1, const void *R2, int32_t n2, uint8_t *Q,
                                      float *scales, float *xrot_dbg, void *stream, const void *frag1,
-                                     const void *frag2, void *xout = nullptr, int64_t ldo = 0)
+                                     const void *frag2, void *xout = nullptr, int64_t ldo = 0,
+                                     int32_t bits = 4, float clip_ratio = 1.0f)
 {
+    if (bits < 2 || bits > 4 || !(clip_ratio > 0.0f) || clip_ratio > 1.0f) return SQ_ERR_SHAPE;
+    const float q_top = (float)((1 << (bits - 1)) - 1);
     const bool f16out = ldo != 0;        // sq_rotate_fp16: Q and scales are unused, xout [T, ldo] is written
     if (T < 0 || K <= 0 || n1 <= 0 || n2 <= 0 || P < 0) return SQ_ERR_SHAPE;
     if (n1 > SQ_MAX_N1 || n2 > SQ_MAX_N2 || P > SQ_MAX_GIVENS) return SQ_ERR_SHAPE;
@@ -355,12 +363,21 @@ static sq_status rotate_quantize_any(const void *X, int64_t T, int32_t K, int64_
     if (!force_generic && prep.plan_ok) {
         sq_status status = SQ_OK;
         const bool prepared = frag1 != nullptr;
+        const bool plain_quantizer = bits == 4 && clip_ratio == 1.0f;
+        sq::RotqPlan variant;                     // the cached plan with this call's quantizer
+        if (!plain_quantizer) {
+            variant = prep.plan;
+            variant.q_top = q_top;
+            variant.clip = clip_ratio;
+            variant.q_div = q_top / clip_ratio;
+        }
+        const sq::RotqPlan &plan = plain_quantizer ? prep.plan : variant;
         if (f16out) {
-            if (sq::rotq_mfma_dispatch_f16(static_cast<const __half *>(X), ldx, (int)T, n1, n2, prep.plan,
+            if (sq::rotq_mfma_dispatch_f16(static_cast<const __half *>(X), ldx, (int)T, n1, n2, plan,
                                            static_cast<const __half *>(R1), static_cast<const __half *>(R2),
                                            static_cast<__half *>(xout), ldo, st, &status))
                 return status;
-        } else if (sq::rotq_mfma_dispatch(static_cast<const __half *>(X), ldx, (int)T, n1, n2, prep.plan,
+        } else if (sq::rotq_mfma_dispatch(static_cast<const __half *>(X), ldx, (int)T, n1, n2, plan,
                                    static_cast<const __half *>(prepared ? frag1 : R1),
                                    static_cast<const __half *>(prepared ? frag2 : R2), Q, scales, xrot_dbg, st,
                                    &status, prepared))
@@ -372,7 +389,7 @@ static sq_status rotate_quantize_any(const void *X, int64_t T, int32_t K, int64_
     hipLaunchKernelGGL(sq::rotate_quantize_generic_kernel, dim3((unsigned)T), dim3(sq::kGenThreads),
                        lds, st, static_cast<const __half *>(X), ldx, K, n1, n2, giv,
                        static_cast<const __half *>(R1), static_cast<const __half *>(R2), Q, scales,
-                       xrot_dbg, static_cast<__half *>(xout), ldo);
+                       xrot_dbg, static_cast<__half *>(xout), ldo, q_top, q_top / clip_ratio);
     return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
 }
 
@@ -394,6 +411,17 @@ extern "C" sq_status sq_rotate_quantize(const void *X, int64_t T, int32_t K, int
 {
     return rotate_quantize_any(X, T, K, ldx, giv_i, giv_j, giv_theta, P, R1, n1, R2, n2, Q, scales, xrot_dbg,
                                stream, nullptr, nullptr);
+}
+
+extern "C" sq_status sq_rotate_quantize_variant(const void *X, int64_t T, int32_t K, int64_t ldx,
+                                                const int32_t *giv_i, const int32_t *giv_j,
+                                                const float *giv_theta, int32_t P, const void *R1,
+                                                int32_t n1, const void *R2, int32_t n2, int32_t bits,
+                                                float clip_ratio, uint8_t *Q, float *scales,
+                                                float *xrot_dbg, void *stream)
+{
+    return rotate_quantize_any(X, T, K, ldx, giv_i, giv_j, giv_theta, P, R1, n1, R2, n2, Q, scales, xrot_dbg,
+                               stream, nullptr, nullptr, nullptr, 0, bits, clip_ratio);
 }
 
 extern "C" sq_status sq_rotate_quantize_prepared(const void *X, int64_t T, int32_t K, int64_t ldx,

@@ -119,7 +119,9 @@ struct RotqShape {
 // g0, stride: the workgroup takes token groups g0, g0 + stride, ... (a kernel of its own passes its
 // block index and grid size); smem_u4: the workgroup's dynamic LDS, RotqShape::lds_bytes() of it;
 // sides: side tiles per token slot (RotqShape::side_tiles).
-template <int N1, int N2, int QS_MAX, int NSX_, bool R1LDS, bool PREPARED, bool F16OUT = false>
+// CLIP: the quantizer has a clipping ratio below one (plan.clip): entries beyond the end levels
+// are clamped to them.  Without it nothing can lie beyond them and the clamp is not compiled in.
+template <int N1, int N2, int QS_MAX, int NSX_, bool R1LDS, bool PREPARED, bool F16OUT = false, bool CLIP = false>
 __device__ __forceinline__ void rotate_quantize_mfma_body(
     const __half *__restrict__ X, int64_t ldx, int T, const RotqPlan &plan,
     const __half *__restrict__ R1, const __half *__restrict__ R2, uint8_t *__restrict__ Q,
@@ -653,7 +655,7 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
             amax = red[0];
 #pragma unroll
             for (int w = 1; w < NCB; ++w) amax = fmaxf(amax, red[w]);
-            const float step = (amax == 0.f) ? 1.0f : amax / 7.0f;
+            const float step = (amax == 0.f) ? 1.0f : amax / plan.q_div;      // q_div = 7: max|Y| / 7
             inv = fz_inv / step;               // codes = Y / step with Y = accy * fz_inv
             if (live && cb == 0 && lane == 0) scales[t] = step;
         }
@@ -668,6 +670,18 @@ __device__ __forceinline__ void rotate_quantize_mfma_body(
                             accy[nb][e] * fz_inv;
                 }
             }
+        }
+
+        if constexpr (!F16OUT && CLIP) {
+            // With a clipping ratio below one, entries beyond the end levels are pulled back to
+            // values that round to those levels (-q_top - 1 and q_top), so that the conversion
+            // below keeps its range; without clipping |Y / step| <= q_top and nothing need be done.
+            const float unit = 1.0f / inv;           // the accumulator value of one step
+            const float lo = -(plan.q_top + 1.0f) * unit, hi = (plan.q_top + 0.25f) * unit;
+#pragma unroll
+            for (int nb = 0; nb < MB; ++nb)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) accy[nb][e] = fminf(fmaxf(accy[nb][e], lo), hi);
         }
 
         // ---- codes of this token, issued between the stage-A MFMAs of the next one ------------

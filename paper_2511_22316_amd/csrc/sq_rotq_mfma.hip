@@ -30,20 +30,23 @@
 
 namespace sq {
 
-// value of the launch chain's `prepared` argument that selects the fp16-output kernel
+// values of the launch chain's `prepared` argument beyond 0 (R1, R2 as they are) and 1 (prepared
+// fragments): the fp16-output kernel, and the quantizer with a clipping ratio (R1, R2 as they are)
 constexpr int kRotqFp16Out = 2;
+constexpr int kRotqClip = 3;
 
 // QS_MAX: repair steps of 16 q-slots each the kernel holds rotation rows for (4 or 8).
 // PREPARED: R1 and R2 point at the operand fragments written by rotation_fragments_kernel.
-template <int N1, int N2, int OCC, int QS_MAX, int NSX_, bool R1LDS, bool PREPARED>
+template <int N1, int N2, int OCC, int QS_MAX, int NSX_, bool R1LDS, bool PREPARED, bool CLIP = false>
 __global__ __launch_bounds__(256, OCC) void rotate_quantize_mfma_kernel(
     const __half *__restrict__ X, int64_t ldx, int T, RotqPlan plan,
     const __half *__restrict__ R1, const __half *__restrict__ R2, uint8_t *__restrict__ Q,
     float *__restrict__ scales, float *__restrict__ xrot, int sides)
 {
     extern __shared__ uint4 smem_u4[];
-    rotate_quantize_mfma_body<N1, N2, QS_MAX, NSX_, R1LDS, PREPARED>(X, ldx, T, plan, R1, R2, Q, scales, xrot,
-                                                                    (int)blockIdx.x, (int)gridDim.x, smem_u4, sides);
+    rotate_quantize_mfma_body<N1, N2, QS_MAX, NSX_, R1LDS, PREPARED, false, CLIP>(X, ldx, T, plan, R1, R2, Q, scales, xrot,
+                                                                                 (int)blockIdx.x, (int)gridDim.x,
+                                                                                 smem_u4, sides);
 }
 
 // The same rotation without the quantizer: the rotated rows leave as fp16 (the 16-bit activations
@@ -82,8 +85,9 @@ static sq_status launch_rotq_mfma_ring(const __half *X, int64_t ldx, int T, cons
         hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), lds, st, X, ldx, T, plan, R1, R2, xout, ldo, sides);
         return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
     }
-    auto kernel = prepared ? rotate_quantize_mfma_kernel<N1, N2, OCC, QS_MAX, NSX, R1LDS, true>
-                           : rotate_quantize_mfma_kernel<N1, N2, OCC, QS_MAX, NSX, R1LDS, false>;
+    auto kernel = prepared == kRotqClip ? rotate_quantize_mfma_kernel<N1, N2, OCC, QS_MAX, NSX, R1LDS, false, true>
+                  : prepared            ? rotate_quantize_mfma_kernel<N1, N2, OCC, QS_MAX, NSX, R1LDS, true>
+                                        : rotate_quantize_mfma_kernel<N1, N2, OCC, QS_MAX, NSX, R1LDS, false>;
     if (!allow_large_lds(reinterpret_cast<const void *>(kernel))) return SQ_ERR_LAUNCH;
     hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), lds, st, X, ldx, T, plan, R1, R2, Q, scales, xrot, sides);
     return hipGetLastError() == hipSuccess ? SQ_OK : SQ_ERR_LAUNCH;
@@ -215,8 +219,13 @@ bool rotq_mfma_dispatch(const __half *X, int64_t ldx, int T, int n1, int n2, con
                         const __half *R1, const __half *R2, uint8_t *Q, float *scales, float *xrot,
                         hipStream_t st, sq_status *status, bool prepared)
 {
-    return rotq_mfma_dispatch_mode(X, ldx, T, n1, n2, plan, R1, R2, Q, scales, xrot, st, status, prepared ? 1 : 0,
-                                   nullptr, 0);
+    // a clipping ratio below one comes with R1, R2 as they are only (sq_rotate_quantize_variant)
+    const int mode = plan.clip < 1.0f ? kRotqClip : prepared ? 1 : 0;
+    if (plan.clip < 1.0f && prepared) {
+        *status = SQ_ERR_SHAPE;
+        return true;
+    }
+    return rotq_mfma_dispatch_mode(X, ldx, T, n1, n2, plan, R1, R2, Q, scales, xrot, st, status, mode, nullptr, 0);
 }
 
 bool rotq_mfma_dispatch_f16(const __half *X, int64_t ldx, int T, int n1, int n2, const RotqPlan &plan,

@@ -27,6 +27,11 @@ struct RotqPlan {
     uint8_t pair_level[SQ_MAX_GIVENS];        // level of the pair, 0xFF behind the end of the list
     float c[SQ_MAX_GIVENS];                   // cos, sin of the pair's angle
     float s[SQ_MAX_GIVENS];
+    // the quantizer of Sec. 3.2: largest level 2^(bits-1) - 1 (7 for four bits) and the fraction
+    // of the row maximum that maps to it (1 = no clipping).  Per call, not part of the list.
+    float q_top;
+    float clip;
+    float q_div;                              // q_top / clip: the step is the row maximum divided by this
 };
 
 }  // namespace sq
