@@ -63,6 +63,8 @@ def _load():
         lib.sqo_pack_w3.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_void_p]
         lib.sqo_unpack_w3.restype = C.c_int
         lib.sqo_unpack_w3.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_void_p]
+        lib.sqo_tile_weights_decode.restype = C.c_int
+        lib.sqo_tile_weights_decode.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_void_p, C.c_int]
         lib.sqo_unpack_codes.restype = None
         lib.sqo_unpack_codes.argtypes = [C.c_void_p, C.c_int64, C.c_int, C.c_void_p]
         lib.sqo_gemm.restype = C.c_int
@@ -212,6 +214,26 @@ def unpack_w3(Q3) -> np.ndarray:
     out = np.empty((N, K // 2), np.uint8)
     if _load().sqo_unpack_w3(_ptr(Q3), N, K, _ptr(out)) != 0:
         raise ValueError("unpack_w3: bad argument")
+    return out
+
+
+def tile_weights_decode(Qw) -> np.ndarray:
+    """Weight codes [N, K/2] (K % 256 == 0) -> the decode layout, flat uint8 of ceil(N/32)*32*K/2 bytes."""
+    Qw = _c(Qw, np.uint8)
+    N, Kh = Qw.shape
+    out = np.empty(((N + 31) // 32) * 32 * Kh, np.uint8)
+    if _load().sqo_tile_weights_decode(_ptr(Qw), N, 2 * Kh, _ptr(out), 0) != 0:
+        raise ValueError("tile_weights_decode: bad argument")
+    return out
+
+
+def untile_weights_decode(Qt, N: int, K: int) -> np.ndarray:
+    """Inverse of tile_weights_decode."""
+    Qt = _c(Qt, np.uint8)
+    assert Qt.size == ((N + 31) // 32) * 32 * (K // 2)
+    out = np.empty((N, K // 2), np.uint8)
+    if _load().sqo_tile_weights_decode(_ptr(out), N, K, _ptr(Qt), 1) != 0:
+        raise ValueError("untile_weights_decode: bad argument")
     return out
 
 

@@ -32,6 +32,8 @@
  *   sqo_pack_w3 / sqo_unpack_w3  storage of 3-bit codes in three bits each.  The
  *                         paper does not give a storage format; the one used
  *                         is stated at the function.
+ *   sqo_tile_weights_decode  the library's second weight layout (a permutation
+ *                         of the bytes; no arithmetic), from its statement.
  *   sqo_gemm              Eq. 1 / Eq. (xw): (XR)(R^T W) evaluated on the integer
  *                         codes, then scaled back: y = acc * s_x * s_w.
  *   sqo_kron_factor       Alg. 1 (Kronecker dimension factorization).
@@ -42,7 +44,8 @@
  * brute-force integer GEMM; fp16 conversion against IEEE binary16 tables;
  * the variant quantizer against sqo_quantize_rows at b = 4, ratio 1, against
  * hand-worked rows at b = 3 and at ratio 1/2, and against its error bound;
- * the 3-bit storage against bytes worked out by hand from the format.
+ * the 3-bit storage against bytes worked out by hand from the format; the
+ * decode layout against hand-worked positions and as a bijection.
  * No function here is "parity unpinned".
  */
 #include <math.h>
@@ -381,6 +384,36 @@ int sqo_unpack_w3(const uint8_t *Q3, int64_t N, int K, uint8_t *Q)
             int u = w3_get_bit(row, wl, bl) | (w3_get_bit(row, wl, bl + 1) << 1) |
                     (w3_get_bit(row, wh, bh) << 2);
             Q[n * (int64_t)(K / 2) + k / 2] |= (uint8_t)(nibble(u - 4) << ((k & 1) * 4));
+        }
+    }
+    return 0;
+}
+
+/* ------------------------------- weight layout for few tokens (decode) ---- */
+
+/* The library's second layout of the weight codes, for its decode-shaped
+   GEMM (the paper fixes no layout beyond "one row per output channel",
+   Sec. 4.2).  Written out here from the statement in the library's header:
+     - channels in blocks of 32 (the last block padded with zero bytes), K in
+       slices of 256 codes, i.e. 128 bytes of a row;
+     - block b, slice S is one piece of 4096 bytes at byte offset
+       (b (K/256) + S) 4096;
+     - inside a piece, the 16-byte unit number 64 c + 32 g + r (c in 0..3,
+       g in 0..1, r in 0..31) holds bytes 64 g + 16 c .. + 15 of that slice of
+       channel 32 b + r.
+   Q: [N, K/2]; Qt: ceil(N/32) * 32 * K/2 bytes.  inverse != 0: Qt -> Q. */
+int sqo_tile_weights_decode(const uint8_t *Q, int64_t N, int K, uint8_t *Qt, int inverse)
+{
+    if (K <= 0 || (K % 256) || N < 0) return -1;
+    const int64_t Kb = K / 2, slices = K / 256, blocks = (N + 31) / 32;
+    if (!inverse) memset(Qt, 0, (size_t)(blocks * 32 * Kb));
+    for (int64_t n = 0; n < N; ++n) {
+        const int64_t b = n / 32, r = n % 32;
+        for (int64_t j = 0; j < Kb; ++j) {
+            const int64_t S = j / 128, w = j % 128, g = w / 64, c = (w % 64) / 16, e = w % 16;
+            const int64_t at = (b * slices + S) * 4096 + (64 * c + 32 * g + r) * 16 + e;
+            if (inverse) ((uint8_t *)Q)[n * Kb + j] = Qt[at];
+            else Qt[at] = Q[n * Kb + j];
         }
     }
     return 0;

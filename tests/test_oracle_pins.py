@@ -519,3 +519,32 @@ def test_gemm_w3a16_is_the_weight_only_product_on_three_bit_codes(oracle):
     Y = oracle.gemm_w3a16(X, oracle.pack_w3(Q), sw).astype(np.float64)
     want = X.astype(np.float64) @ (codes * sw.astype(np.float64)[:, None]).T
     assert np.all(np.abs(Y - want) <= 2.0 ** -11 * np.abs(want) + 1e-300)
+
+
+def test_decode_layout_matches_hand_worked_positions_and_is_a_bijection(oracle):
+    import os
+    K, N = 512, 33
+    Kb = K // 2
+    g = np.random.default_rng(17)
+    Q = g.integers(0, 256, size=(N, Kb), dtype=np.uint8)
+    Qt = oracle.tile_weights_decode(Q)
+    assert Qt.shape == (2 * 32 * Kb,)
+    with open(os.path.join(os.path.dirname(__file__), "golden", "decode_layout_positions.txt")) as f:
+        rows = [tuple(int(v) for v in line.split()) for line in f if line.strip() and not line.startswith("#")]
+    assert len(rows) == 9
+    for n, j, at in rows:
+        one = np.zeros((N, Kb), np.uint8)
+        one[n, j] = 0xC3
+        t = oracle.tile_weights_decode(one)
+        assert t[at] == 0xC3 and np.count_nonzero(t) == 1, (n, j, at)
+    # a permutation of the N * Kb bytes into distinct places; the padding channels stay zero
+    idx = oracle.tile_weights_decode(np.ones((N, Kb), np.uint8))
+    assert int(idx.sum()) == N * Kb and set(np.unique(idx)) == {0, 1}
+    assert np.array_equal(oracle.untile_weights_decode(Qt, N, K), Q)
+    # every 16-byte unit is 16 consecutive bytes of one channel's row
+    tags = (np.arange(N * Kb, dtype=np.int64) // 16).reshape(N, Kb)
+    low, high = oracle.tile_weights_decode((tags & 0xFF).astype(np.uint8)), oracle.tile_weights_decode((tags >> 8).astype(np.uint8))
+    units = (low.astype(np.int64) | (high.astype(np.int64) << 8)).reshape(-1, 16)
+    assert np.all(units == units[:, :1])
+    with pytest.raises(ValueError):
+        oracle.tile_weights_decode(np.zeros((4, 64), np.uint8))       # K = 128 is not a multiple of 256
