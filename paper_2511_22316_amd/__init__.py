@@ -29,6 +29,9 @@ from .binding import (  # noqa: F401
     sq_rotate_quantize_variant,
     sq_w3a16_gemm,
     sq_w4a4_gemm,
+    sq_w4a4_gemm_decode,
+    sq_tile_weights_decode,
+    sq_decode_weights_bytes,
     sq_w4a16_gemm,
     sq_status_string,
 )

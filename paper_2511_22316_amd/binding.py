@@ -82,6 +82,15 @@ def _load():
         lib.sq_w4a16_gemm.argtypes = [
             C.c_void_p, C.c_int64, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_int32,
             C.c_void_p, C.c_int64, C.c_void_p]
+        lib.sq_decode_weights_bytes.restype = C.c_int64
+        lib.sq_decode_weights_bytes.argtypes = [C.c_int32, C.c_int32]
+        lib.sq_tile_weights_decode.restype = C.c_int
+        lib.sq_tile_weights_decode.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        lib.sq_w4a4_gemm_decode.restype = C.c_int
+        lib.sq_w4a4_gemm_decode.argtypes = [
+            C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
+            C.c_void_p, C.c_void_p, C.c_int32,
+            C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
         lib.sq_w3a16_gemm.restype = C.c_int
         lib.sq_w3a16_gemm.argtypes = lib.sq_w4a16_gemm.argtypes
         lib.sq_pack_w3.restype = C.c_int
@@ -111,6 +120,8 @@ def _load():
             C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
             C.c_void_p, C.c_int32, C.c_void_p, C.c_int32,
             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.sq_debug_rotq_plan.restype = C.c_int32
+        lib.sq_debug_rotq_plan.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32] + [C.c_void_p] * 8
         lib.sq_debug_set_option.restype = C.c_int
         lib.sq_debug_set_option.argtypes = [C.c_int, C.c_int32]
         lib.sq_kron_factor.restype = C.c_int
@@ -240,6 +251,34 @@ def sq_w4a4_gemm(Qx, sx, Qw, sw, Y, acc_dbg=None, stream=None) -> None:
     ldy = int(Y.stride(0)) if T > 1 else max(N, 1)
     code = _load().sq_w4a4_gemm(
         _dev_ptr(Qx), _dev_ptr(sx), T, 2 * Kh, _dev_ptr(Qw), _dev_ptr(sw), N,
+        _dev_ptr(Y), ldy, _dev_ptr(acc_dbg), _stream_handle(stream))
+    _check(code)
+
+
+def sq_decode_weights_bytes(K: int, N: int) -> int:
+    return int(_load().sq_decode_weights_bytes(int(K), int(N)))
+
+
+def sq_tile_weights_decode(Qw, Qw_tiled, stream=None) -> None:
+    """Weight codes Qw uint8 [N, K/2] -> the decode layout in Qw_tiled (any uint8 device tensor of
+    at least sq_decode_weights_bytes(K, N) bytes)."""
+    N, K = int(Qw.shape[0]), 2 * int(Qw.shape[1])
+    need = sq_decode_weights_bytes(K, N)
+    if Qw_tiled is not None and Qw_tiled.numel() * Qw_tiled.element_size() < need:
+        raise ValueError("Qw_tiled is smaller than sq_decode_weights_bytes")
+    _check(_load().sq_tile_weights_decode(_dev_ptr(Qw), K, N, _dev_ptr(Qw_tiled), _stream_handle(stream)))
+
+
+def sq_w4a4_gemm_decode(Qx, sx, Qw_tiled, sw, Y, acc_dbg=None, stream=None) -> None:
+    """sq_w4a4_gemm for at most 32 tokens on weights in the decode layout; N = len(sw)."""
+    T, Kh = int(Qx.shape[0]), int(Qx.shape[1])
+    N = int(sw.shape[0])
+    need = sq_decode_weights_bytes(2 * Kh, N)
+    if Qw_tiled is not None and Qw_tiled.numel() * Qw_tiled.element_size() < need:
+        raise ValueError("Qw_tiled is smaller than sq_decode_weights_bytes")
+    ldy = int(Y.stride(0)) if T > 1 else max(N, 1)
+    code = _load().sq_w4a4_gemm_decode(
+        _dev_ptr(Qx), _dev_ptr(sx), T, 2 * Kh, _dev_ptr(Qw_tiled), _dev_ptr(sw), N,
         _dev_ptr(Y), ldy, _dev_ptr(acc_dbg), _stream_handle(stream))
     _check(code)
 

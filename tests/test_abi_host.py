@@ -37,6 +37,21 @@ def test_library_exports_every_declared_symbol(lib):
     assert exported and exported <= declared, f"exported but not declared: {sorted(exported - declared)}"
 
 
+def test_binding_declares_the_argument_types_of_every_entry_point(lib):
+    """A function called through ctypes without declared argument types gets its pointers cut to
+    32 bits.  Every function the header declares has them in the binding, with as many entries as
+    the declaration has parameters."""
+    header = open(os.path.join(ROOT, "include", "singlequant.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    found = re.findall(r"\b(sq_[a-z0-9_]+)\s*\(([^;{]*?)\)\s*;", header, flags=re.S)
+    assert len(found) >= 25
+    for name, params in found:
+        fn = getattr(lib, name)
+        n_params = 0 if params.strip() in ("", "void") else params.count(",") + 1
+        assert fn.argtypes is not None, f"{name}: argument types not declared in binding.py"
+        assert len(fn.argtypes) == n_params, f"{name}: {len(fn.argtypes)} argument types for {n_params} parameters"
+
+
 def test_status_strings(lib):
     texts = {sq.sq_status_string(c) for c in range(6)}
     assert len(texts) == 6 and sq.sq_status_string(0) == "ok"

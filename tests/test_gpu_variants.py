@@ -296,3 +296,73 @@ def test_w3a16_layer_end_to_end(oracle, name, T, N):
     e4 = np.linalg.norm(host(Y4).astype(np.float64) - ref) / np.linalg.norm(ref)
     print(f"  error against X W: W3A16 {e3:.3f}, W4A16 {e4:.3f}", flush=True)
     assert e4 < e3 < 0.5
+
+
+# ------------------------------------------------------ decode layout of the W4A4 weights --
+
+def run_tile_decode(Qw):
+    import torch
+    import paper_2511_22316_amd as sq
+    N, Kh = Qw.shape
+    need = sq.sq_decode_weights_bytes(2 * Kh, N)
+    assert need == ((N + 31) // 32) * 32 * Kh
+    out = torch.full((need + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+    sq.sq_tile_weights_decode(dev(Qw), out[:need])
+    torch.cuda.synchronize()
+    assert torch.all(out[need:] == 0xA5), "sq_tile_weights_decode wrote past its stated size"
+    return out[:need]
+
+
+@pytest.mark.parametrize("N,K", [(1, 256), (33, 512), (100, 1024), (300, 8192), (4096, 768)])
+def test_tile_weights_decode_bit_exact(oracle, N, K):
+    print(f"case tile_weights_decode N={N} K={K}", flush=True)
+    Qw = synth.random_codes(N, K, N + K)
+    got = host(run_tile_decode(Qw))
+    assert np.array_equal(got, oracle.tile_weights_decode(Qw))
+    assert np.array_equal(oracle.untile_weights_decode(got, N, K), Qw)
+
+
+@pytest.mark.parametrize("T,K,N", [(1, 256, 33), (8, 1024, 520), (32, 768, 8200), (16, 512, 10300), (31, 512, 24600),
+                                   (8, 8192, 25000), (15, 8192, 700), (5, 2304, 12000), (16, 8192, 700),
+                                   (32, 8192, 300), (20, 4096, 10300), (17, 4096, 24700), (3, 256, 31)])
+def test_gemm_decode_layout_bit_exact(oracle, T, K, N):
+    """sq_w4a4_gemm_decode on the tiled copy: accumulators equal to the oracle's, and accumulators
+    and Y equal, bit for bit, to sq_w4a4_gemm on the canonical codes; every launch shape of the
+    decode-shaped kernel, token rows in LDS and not, ragged channel tails (padded last block)."""
+    print(f"case gemm decode layout T={T} K={K} N={N}", flush=True)
+    import torch
+    import paper_2511_22316_amd as sq
+    Qx, Qw = synth.random_codes(T, K, 7 * T + K), synth.random_codes(N, K, 11 * N + K)
+    g = np.random.default_rng(T + K + N)
+    sx, sw = g.uniform(0.01, 2.0, T).astype(np.float32), g.uniform(1e-3, 1e-2, N).astype(np.float32)
+    Qt = run_tile_decode(Qw)
+    Y = torch.full((T, N + 3), -9.0, dtype=torch.float16, device="cuda")
+    acc = torch.empty((T, N), dtype=torch.int32, device="cuda")
+    sq.sq_w4a4_gemm_decode(dev(Qx), dev(sx), Qt, dev(sw), Y[:, :N], acc)
+    Y0 = torch.empty((T, N), dtype=torch.float16, device="cuda")
+    acc0 = torch.empty((T, N), dtype=torch.int32, device="cuda")
+    sq.sq_w4a4_gemm(dev(Qx), dev(sx), dev(Qw), dev(sw), Y0, acc0)
+    torch.cuda.synchronize()
+    assert torch.equal(acc, acc0) and torch.equal(Y[:, :N], Y0)
+    assert torch.all(Y[:, N:] == -9.0)
+    _, acco = oracle.gemm(Qx, sx, Qw, sw)
+    assert np.array_equal(host(acc), acco)
+
+
+def test_gemm_decode_layout_arguments_are_checked():
+    print("case gemm decode layout argument checks", flush=True)
+    import torch
+    import paper_2511_22316_amd as sq
+    assert sq.sq_decode_weights_bytes(320, 8) == 0 and sq.sq_decode_weights_bytes(256, 33) == 64 * 128
+    Qx = torch.zeros((33, 128), dtype=torch.uint8, device="cuda")
+    sx = torch.ones((33,), dtype=torch.float32, device="cuda")
+    Qt = torch.zeros((32 * 128,), dtype=torch.uint8, device="cuda")
+    sw = torch.ones((8,), dtype=torch.float32, device="cuda")
+    Y = torch.empty((33, 8), dtype=torch.float16, device="cuda")
+    with pytest.raises(sq.SQError) as e:                    # 33 tokens
+        sq.sq_w4a4_gemm_decode(Qx, sx, Qt, sw, Y)
+    assert e.value.code == 2
+    with pytest.raises(sq.SQError) as e:                    # K = 160
+        sq.sq_w4a4_gemm_decode(Qx[:4, :80].contiguous(), sx[:4], Qt, sw, Y[:4])
+    assert e.value.code == 2
+    sq.sq_w4a4_gemm_decode(Qx[:0], sx[:0], Qt, sw, Y[:0])   # no tokens: nothing enqueued
