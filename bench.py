@@ -54,8 +54,8 @@ PROFILED_TRAFFIC = {
                   "rotate_quantize": {"fetch": 17070223, "write": 4227072}},
     "mlp_down": {"gemm": {"fetch": 90426633, "write": 16777216},
                  "rotate_quantize": {"fetch": 45743178, "write": 11337728}},
-    "decode": {"gemm": {"fetch": 118380409, "write": 458752},
-               "rotate_quantize": {"fetch": 665525, "write": 33024}},
+    "decode": {"gemm": {"fetch": 118156413, "write": 458752},
+               "rotate_quantize": {"fetch": 659389, "write": 33024}},
     "large_prefill": {"gemm": {"fetch": 1414509012, "write": 469762048},
                       "rotate_quantize": {"fetch": 134738742, "write": 33816576}},
 }
@@ -106,6 +106,12 @@ class LayerBuffers:
             self.Q.append(torch.empty((T, K // 2), dtype=torch.uint8, device=dev))
             self.s.append(torch.empty((T,), dtype=torch.float32, device=dev))
             self.Y.append(torch.empty((T, N), dtype=torch.float16, device=dev))
+        # at most 32 tokens: the GEMM reads the decode layout of the codes (a second copy, made once per layer)
+        self.Qt = []
+        if T <= 32 and K % 256 == 0:
+            for i in range(self.sets):
+                self.Qt.append(torch.empty((sq.sq_decode_weights_bytes(K, N),), dtype=torch.uint8, device=dev))
+                sq.sq_tile_weights_decode(self.Qw[i], self.Qt[i])
         torch.cuda.synchronize()
 
     def rotate_quantize(self, i):
@@ -119,6 +125,12 @@ class LayerBuffers:
         self.sq.sq_rotate_quantize(self.X[i], L.giv_i, L.giv_j, L.giv_theta, self.R1, self.R2, self.Q[i], self.s[i])
 
     def gemm(self, i):
+        if self.Qt:
+            self.sq.sq_w4a4_gemm_decode(self.Q[i], self.s[i], self.Qt[i], self.sw[i], self.Y[i])
+        else:
+            self.sq.sq_w4a4_gemm(self.Q[i], self.s[i], self.Qw[i], self.sw[i], self.Y[i])
+
+    def gemm_canonical(self, i):
         self.sq.sq_w4a4_gemm(self.Q[i], self.s[i], self.Qw[i], self.sw[i], self.Y[i])
 
     def step(self, i):
@@ -260,6 +272,7 @@ def measure_layer(cfg, torch, sq, synth, steps, warmup):
     rq = kernel_time(torch, B.rotate_quantize, B.sets, steps, warmup)
     gm = kernel_time(torch, B.gemm, B.sets, steps, warmup)
     rq_plain = kernel_time(torch, B.rotate_quantize_plain, B.sets, steps, warmup)
+    gm_canonical = kernel_time(torch, B.gemm_canonical, B.sets, steps, warmup) if B.Qt else None
     single = single_k = None
     if T <= 32 and (cfg.n1, cfg.n2) in ((16, 32), (32, 32), (32, 64), (64, 64), (64, 128)):
         single = timed(torch, B.single_launch, B.sets, steps, warmup)
@@ -275,6 +288,8 @@ def measure_layer(cfg, torch, sq, synth, steps, warmup):
         "gemm_us": gm_us, "gemm_us_median": gm["median_us"], "gemm_us_min": gm["min_us"],
         "gemm_timing": gm["method"], "gemm_us_eager": gm["eager_median_us"],
         "rotate_quant_us_unprepared_entry": rq_plain["mean_us"],
+        "gemm_entry": "sq_w4a4_gemm_decode (decode layout of the weight codes)" if B.Qt else "sq_w4a4_gemm",
+        "gemm_us_canonical_layout": None if gm_canonical is None else gm_canonical["mean_us"],
         "layer_us_single_launch": None if single is None else single["median_us"],
         "single_launch_kernel_us": None if single_k is None else single_k["mean_us"],
         "rotate_quant_GBps": rq_bytes(T, K) / (rq_us * 1e-6) / 1e9,
@@ -501,7 +516,8 @@ def main() -> int:
                            "not measured in this run") if cfg.name in PROFILED_TRAFFIC else None
     timing_note = "average launch duration between HIP events on the launch stream; "
     if cfg.T <= 64:      # decode-shaped GEMM: one pass over the weights, HBM-bound
-        gemm_roofline = {"kernel": "w4a4_gemm_skinny_kernel", "bound": "hbm", "achieved": head["gemm_weight_stream_GBps"],
+        gemm_roofline = {"kernel": "w4a4_gemm_skinny_kernel" + (" on the decode layout (sq_w4a4_gemm_decode)" if cfg.T <= 32 and cfg.K % 256 == 0 else ""),
+                         "bound": "hbm", "achieved": head["gemm_weight_stream_GBps"],
                          "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": head["gemm_weight_stream_GBps"] / HBM_PEAK_GBPS,
                          "bytes_per_launch": cfg.N * cfg.K / 2.0, "launch_us": head["gemm_us"], "timing": timing_note + head["gemm_timing"],
                          "traffic": traffic("gemm"), "traffic_detail": prof.get("gemm"),
@@ -528,6 +544,7 @@ def main() -> int:
         "rotate_quant_us_min": head["rotate_quant_us_min"], "gemm_us_min": head["gemm_us_min"],
         "rotate_quant_us_eager": head["rotate_quant_us_eager"], "gemm_us_eager": head["gemm_us_eager"],
         "rotate_quant_us_unprepared_entry": head["rotate_quant_us_unprepared_entry"],
+        "gemm_entry": head["gemm_entry"], "gemm_us_canonical_layout": head["gemm_us_canonical_layout"],
         "layer_us_single_launch": head["layer_us_single_launch"],
         "roofline": gemm_roofline,
         "roofline_rotate_quant": {"kernel": "rotate_quantize_mfma_kernel", "bound": "hbm",

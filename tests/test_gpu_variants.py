@@ -349,6 +349,39 @@ def test_gemm_decode_layout_bit_exact(oracle, T, K, N):
     assert np.array_equal(host(acc), acco)
 
 
+def test_gemm_decode_layout_full_size_decode_workload(oracle):
+    """The decode workload at full size in the configuration the benchmark times (prepared rotation,
+    then sq_w4a4_gemm_decode on the tiled weights): Y equal to sq_w4a4_gemm's, sampled accumulators
+    computed one by one by the oracle."""
+    print("case gemm decode layout, decode workload at full size", flush=True)
+    import torch
+    import paper_2511_22316_amd as sq
+    cfg = synth.CONFIGS["decode"]
+    L = synth.layer(cfg)
+    T, K, N = cfg.T, cfg.K, cfg.N
+    Qw = synth.random_codes(N, K, 4242)
+    sw = np.random.default_rng(5).uniform(1e-3, 1e-2, N).astype(np.float32)
+    dR1, dR2 = dev(L.R1), dev(L.R2)
+    prepared = torch.empty((sq.sq_prepared_rotation_bytes(cfg.n1, cfg.n2),), dtype=torch.uint8, device="cuda")
+    sq.sq_prepare_rotation(dR1, dR2, prepared)
+    Qx = torch.empty((T, K // 2), dtype=torch.uint8, device="cuda")
+    sx = torch.empty((T,), dtype=torch.float32, device="cuda")
+    sq.sq_rotate_quantize_prepared(dev(L.X), L.giv_i, L.giv_j, L.giv_theta, prepared, cfg.n1, cfg.n2, Qx, sx)
+    dQw, dsw = dev(Qw), dev(sw)
+    Qt = run_tile_decode(Qw)
+    Y = torch.empty((T, N), dtype=torch.float16, device="cuda")
+    acc = torch.empty((T, N), dtype=torch.int32, device="cuda")
+    sq.sq_w4a4_gemm_decode(Qx, sx, Qt, dsw, Y, acc)
+    Y0 = torch.empty_like(Y)
+    sq.sq_w4a4_gemm(Qx, sx, dQw, dsw, Y0)
+    torch.cuda.synchronize()
+    assert torch.equal(Y, Y0)
+    hQx, hacc = host(Qx), host(acc)
+    g = np.random.default_rng(77)
+    for t, n in zip(g.integers(0, T, 200), np.concatenate([[0, N - 1, 31, 32, N - 32], g.integers(0, N, 195)])):
+        assert hacc[t, n] == oracle.gemm_acc_at(hQx, Qw, int(t), int(n))
+
+
 def test_gemm_decode_layout_arguments_are_checked():
     print("case gemm decode layout argument checks", flush=True)
     import torch
