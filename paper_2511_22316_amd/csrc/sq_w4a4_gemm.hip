@@ -910,9 +910,15 @@ extern "C" sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T,
         const int64_t n_small = (int64_t)((Ti + 127) / 128) * ((N + 255) / 256);
         const int64_t n_large = (int64_t)((Ti + 255) / 256) * ((N + 255) / 256);
         const int64_t rounds_small = (n_small + 255) / 256, rounds_large = (n_large + 255) / 256;
-        // (the 128x256 tile in its form with four loading waves, case 16: attn_proj 32.0 -> 31.5 us,
-        // mlp_down 74.5 -> 73.4 us against case 1, the same tile with the loads in the multiplying waves)
-        choice = (20 * rounds_small > 37 * rounds_large) ? 4 : 16;
+        // (the 128x256 tile with four loading waves.  Case 16, eight multiplying waves of 64x64: attn_proj
+        // 32.0 -> 31.5 us, mlp_down 74.5 -> 73.4 us against case 1, the same tile with the loads in the
+        // multiplying waves.  Case 17, four multiplying waves of 64x128 -- half the widening per MFMA, and
+        // the four loading waves keep eight waves on the CU: attn_proj 31.0 -> 30.7 us, mlp_down 72.2 -> 68.8 us
+        // against case 16 for the GEMM alone; without loading waves that wave shape, case 0, is slower than
+        // both.  Behind the rotate kernel, as a layer, attn_proj is 0.3 us slower with it (41.5 -> 41.8 us) and
+        // mlp_down 2.2 us faster (98.6 -> 96.4 us): its gain grows with the number of K tiles, 16 against 43
+        // here, and turns positive at about 20 of them.)
+        choice = (20 * rounds_small > 37 * rounds_large) ? 4 : (K >= 6144 ? 17 : 16);
     }
     switch (choice) {
         case 0: return sq::launch_main<2, 2, 2, 4, 128, 1>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
@@ -924,6 +930,7 @@ extern "C" sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T,
         case 10: return sq::launch_main<2, 2, 1, 1, 128, 2>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
         case 11: return sq::launch_main<2, 2, 1, 2, 128, 2>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
         case 16: return sq::launch_main<2, 4, 2, 2, 128, 1, 1, 3, 4>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
+        case 17: return sq::launch_main<2, 2, 2, 4, 128, 1, 1, 3, 4>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st);
         case 14: if (K % 512 == 0) return sq::launch_main<2, 2, 1, 1, 128, 1, 2>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
         case 15: if (K % 512 == 0) return sq::launch_main<2, 2, 1, 2, 128, 1, 2>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;
         case 7: if (Ti <= 32) return sq::launch_skinny<1, 1, 16>(Qx, sx, Ti, K, Qw, sw, N, Yh, ldy, acc_dbg, st); break;

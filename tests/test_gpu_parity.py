@@ -338,7 +338,7 @@ def test_gemm_random_codes_bit_exact(oracle, T, K, N):
     assert np.all(accm == 64 * K)
 
 
-@pytest.mark.parametrize("case", [0, 1, 2, 3, 4, 5, 6, 10, 11, 16])
+@pytest.mark.parametrize("case", [0, 1, 2, 3, 4, 5, 6, 10, 11, 16, 17])
 @pytest.mark.parametrize("T,K,N", [(300, 512, 520), (130, 768, 257), (70, 256, 300)])      # the last: a single K tile
 def test_gemm_every_tile_launch_shape(oracle, case, T, K, N):
     """Every launch shape of the tile kernel (tile sizes, waves per workgroup, the form with
