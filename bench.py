@@ -52,8 +52,8 @@ MIN_BLOCKS = 3
 PROFILED_TRAFFIC = {
     "attn_proj": {"gemm": {"fetch": 33809731, "write": 16777216},
                   "rotate_quantize": {"fetch": 17070223, "write": 4227072}},
-    "mlp_down": {"gemm": {"fetch": 90426633, "write": 16777216},
-                 "rotate_quantize": {"fetch": 45743178, "write": 11337728}},
+    "mlp_down": {"gemm": {"fetch": 90541107, "write": 16777216},
+                 "rotate_quantize": {"fetch": 45743076, "write": 11337728}},
     "decode": {"gemm": {"fetch": 118156413, "write": 458752},
                "rotate_quantize": {"fetch": 659389, "write": 33024}},
     "large_prefill": {"gemm": {"fetch": 1414509012, "write": 469762048},
