@@ -880,6 +880,13 @@ extern "C" sq_status sq_w4a4_gemm(const uint8_t *Qx, const float *sx, int64_t T,
     // N = 28672: 31.2 -> 28.9 us).  It needs K % 512 == 0.
     const bool two_k_groups = (K % 512) == 0;
     if (choice < 0 && Ti > 32 && Ti <= 64 && N >= 8192 && N <= 64 * 256 && two_k_groups) choice = 14;
+    // The same two tile forms win below 33 tokens as well where their tiles number 192 .. 256 (nearly one
+    // per CU) and K is long: with 24576 .. 32768 channels and K >= 8192 the 64x128 tiles with two K groups
+    // take 25.5 - 26.3 us for 1 .. 32 tokens at N = 28672 (the decode-shaped kernel 27.2 - 28.6 us up to 16
+    // tokens, 64x64 tiles 29.6 - 32.0 us from 17 on; at K = 4096 all are within 0.5 us); with 10240 .. 16384
+    // channels and 17 .. 32 tokens the 64x64 tiles with two K groups (T = 32, K = 4096, N = 14336: 10.7 -> 10.0 us).
+    if (choice < 0 && Ti <= 32 && N >= 64 * 384 && N <= 128 * 256 && two_k_groups && K >= 8192) choice = 15;
+    if (choice < 0 && Ti > 16 && Ti <= 32 && N >= 10240 && N <= 64 * 256 && two_k_groups) choice = 14;
     if (choice < 0 && Ti <= 64 && N >= 10240 && (Ti > 32 || (Ti > 16 && N >= 64 * 384))) {
         choice = (N >= 64 * 384 && Ti > 32) ? 11 : 10;
         if (choice == 11 && N <= 128 * 256 && two_k_groups) choice = 15;
