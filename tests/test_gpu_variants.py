@@ -399,3 +399,54 @@ def test_gemm_decode_layout_arguments_are_checked():
         sq.sq_w4a4_gemm_decode(Qx[:4, :80].contiguous(), sx[:4], Qt, sw, Y[:4])
     assert e.value.code == 2
     sq.sq_w4a4_gemm_decode(Qx[:0], sx[:0], Qt, sw, Y[:0])   # no tokens: nothing enqueued
+
+
+def test_decode_path_captured_in_a_graph_replays_correctly(oracle):
+    """The decode path a serving loop would record (sq_rotate_quantize_prepared, then
+    sq_w4a4_gemm_decode on the tiled weights; nothing allocates, nothing but kernel launches):
+    three replays on fresh inputs, with eager work and synchronizations in between, equal the
+    eager two calls on the canonical weights bit for bit."""
+    print("case graph capture of the decode path", flush=True)
+    import torch
+    import paper_2511_22316_amd as sq
+    cfg = synth.CONFIGS["decode"]
+    T, N = 8, 1100
+    L = synth.layer(cfg, T)
+    K = cfg.K
+    Qw_h = synth.random_codes(N, K, 99)
+    Qw, sw = dev(Qw_h), dev(np.random.default_rng(3).uniform(1e-3, 1e-2, N).astype(np.float32))
+    Qt = run_tile_decode(Qw_h)
+    R1, R2 = dev(L.R1), dev(L.R2)
+    prepared = torch.empty((sq.sq_prepared_rotation_bytes(cfg.n1, cfg.n2),), dtype=torch.uint8, device="cuda")
+    sq.sq_prepare_rotation(R1, R2, prepared)
+    X = dev(L.X)
+    Xin = torch.empty_like(X)
+    Q = torch.empty((T, K // 2), dtype=torch.uint8, device="cuda")
+    s = torch.empty((T,), dtype=torch.float32, device="cuda")
+    Y = torch.empty((T, N), dtype=torch.float16, device="cuda")
+
+    def step(stream):
+        sq.sq_rotate_quantize_prepared(Xin, L.giv_i, L.giv_j, L.giv_theta, prepared, cfg.n1, cfg.n2, Q, s, stream=stream)
+        sq.sq_w4a4_gemm_decode(Q, s, Qt, sw, Y, stream=stream)
+
+    side = torch.cuda.Stream()
+    Xin.copy_(X)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):                   # warm-up outside capture (one-time kernel attributes)
+        step(side)
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step(side)
+    for shift in (0, 3, 5):
+        Xs = torch.roll(X, shift, 0).contiguous()
+        Xin.copy_(Xs)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (Q.clone(), s.clone(), Y.clone())
+        Qe, se, Ye = torch.empty_like(Q), torch.empty_like(s), torch.empty_like(Y)
+        sq.sq_rotate_quantize(Xs, L.giv_i, L.giv_j, L.giv_theta, R1, R2, Qe, se)
+        sq.sq_w4a4_gemm(Qe, se, Qw, sw, Ye)
+        torch.cuda.synchronize()
+        assert torch.equal(got[0], Qe) and torch.equal(got[1], se) and torch.equal(got[2], Ye), f"replay with shift {shift}"
