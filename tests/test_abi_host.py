@@ -218,6 +218,57 @@ def test_gemm_argument_errors(lib):
     assert _gemm(lib, N=0, ldy=0) == 0
 
 
+def test_decode_layout_argument_errors_and_sizes(lib):
+    assert lib.sq_decode_weights_bytes(256, 33) == 64 * 128
+    assert lib.sq_decode_weights_bytes(8192, 28672) == 28672 * 4096
+    assert lib.sq_decode_weights_bytes(320, 8) == 0 and lib.sq_decode_weights_bytes(256, -1) == 0
+    assert lib.sq_decode_weights_bytes(131072, 8) == 0
+
+    def tile(K=256, N=8, Qw=FAKE, Qt=FAKE):
+        return lib.sq_tile_weights_decode(Qw, K, N, Qt, None)
+    assert tile(K=128) == 2 and tile(K=0) == 2 and tile(N=-1) == 2
+    assert tile(Qw=None) == 1 and tile(Qt=None) == 1
+    assert tile(Qw=FAKE + 8) == 4 and tile(Qt=FAKE + 4) == 4
+    assert tile(N=0) == 0
+
+    def mm(T=4, K=256, N=8, ldy=8, Qx=FAKE, sx=FAKE, Qt=FAKE, sw=FAKE, Y=FAKE):
+        return lib.sq_w4a4_gemm_decode(Qx, sx, T, K, Qt, sw, N, Y, ldy, None, None)
+    assert mm(T=33) == 2 and mm(K=128) == 2 and mm(K=288) == 2 and mm(T=-1) == 2 and mm(ldy=6) == 2
+    assert mm(Qx=None) == 1 and mm(Qt=None) == 1 and mm(Y=None) == 1 and mm(sw=None) == 1
+    assert mm(Qt=FAKE + 8) == 4 and mm(Y=FAKE + 1) == 4 and mm(sx=FAKE + 2) == 4
+    assert mm(T=0) == 0 and mm(N=0, ldy=0) == 0
+
+
+def test_variant_and_three_bit_argument_errors(lib):
+    def rq(bits=4, clip=1.0, T=0, K=64):
+        gi, gj, gt = np.asarray([1], np.int32), np.asarray([2], np.int32), np.asarray([0.1], np.float32)
+        return lib.sq_rotate_quantize_variant(FAKE, T, K, K, gi.ctypes.data, gj.ctypes.data, gt.ctypes.data, 1,
+                                              FAKE, 8, FAKE, 8, bits, clip, FAKE, FAKE, None, None)
+    assert rq() == 0 and rq(bits=3) == 0 and rq(bits=2, clip=0.5) == 0
+    assert rq(bits=1) == 2 and rq(bits=5) == 2 and rq(clip=0.0) == 2 and rq(clip=1.5) == 2 and rq(clip=float("nan")) == 2
+    assert rq(K=63) == 2
+
+    def pw(bits=3, clip=1.0, N=0, ws=FAKE):
+        gi, gj, gt = np.asarray([1], np.int32), np.asarray([2], np.int32), np.asarray([0.1], np.float32)
+        return lib.sq_prepare_weights_variant(FAKE, 64, N, max(N, 1), gi.ctypes.data, gj.ctypes.data, gt.ctypes.data, 1,
+                                              FAKE, 8, FAKE, 8, bits, clip, ws, FAKE, FAKE, None)
+    assert pw() == 0 and pw(bits=7) == 2 and pw(clip=-1.0) == 2
+
+    def pack(K=64, N=8, Q=FAKE, Q3=FAKE):
+        return lib.sq_pack_w3(Q, K, N, Q3, None)
+    assert pack(K=32) == 2 and pack(K=0) == 2 and pack(N=-1) == 2 and pack(K=262144) == 2
+    assert pack(Q=None) == 1 and pack(Q3=None) == 1 and pack(Q=FAKE + 8) == 4 and pack(Q3=FAKE + 4) == 4
+    assert pack(N=0) == 0
+
+    def mm(T=4, K=256, ldx=256, N=8, ldy=8, X=FAKE, Q3=FAKE, sw=FAKE, Y=FAKE):
+        return lib.sq_w3a16_gemm(X, T, K, ldx, Q3, sw, N, Y, ldy, None)
+    assert mm(K=320, ldx=320) == 2 and mm(K=0) == 2 and mm(T=-1) == 2 and mm(ldy=6) == 2 and mm(ldx=128) == 2
+    assert mm(T=16 * 65535 + 1) == 2
+    assert mm(X=None) == 1 and mm(Q3=None) == 1 and mm(Y=None) == 1 and mm(sw=None) == 1
+    assert mm(X=FAKE + 4) == 4 and mm(ldx=260) == 4 and mm(Q3=FAKE + 4) == 4 and mm(Y=FAKE + 1) == 4
+    assert mm(T=0) == 0 and mm(N=0, ldy=0) == 0
+
+
 def test_binding_raises_on_error(lib):
     with pytest.raises(sq.SQError) as e:
         binding._check(lib.sq_w4a4_gemm(FAKE, FAKE, 4, 48, FAKE, FAKE, 8, FAKE, 8, None, None))
