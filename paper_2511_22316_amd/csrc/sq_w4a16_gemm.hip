@@ -5,9 +5,12 @@
 //
 //   Y[t, n] = fp16( sw[n] * sum_k X[t, k] * Qw[n, k] )        fp32 accumulation
 //
-// Two kernels: a tile kernel for many tokens (w4a16_gemm_ring_kernel) and a decode-shaped one for
-// at most 32 (w4a16_gemm_skinny_kernel).  Both widen the codes to fp16 in registers, exactly, with
-// the magic-number form described at the two widening functions below.
+// Three kernels: a tile kernel for many tokens (w4a16_gemm_ring_kernel) and two decode-shaped ones,
+// for at most 32 tokens (w4a16_gemm_skinny_kernel) and for at most 16 whose rows fit in LDS
+// (w4a16_gemm_xlds_kernel).  All widen the codes to fp16 in registers, exactly, with the
+// magic-number form described at the two widening functions below.
+// sq_pack_w3 / sq_w3a16_gemm (W3A16 of the same table) live here too: the decode-shaped kernels
+// with the codes in three bits each, expanded to nibbles in registers (w3_nibbles).
 #include "sq_common.h"
 
 #include <type_traits>
