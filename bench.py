@@ -50,14 +50,14 @@ MIN_BLOCKS = 3
 # summaries profiles/w4a4_gemm_<workload>.md and profiles/rotate_quantize_<workload>.md (FETCH_SIZE
 # and WRITE_SIZE, each scaled by what the counter reads for a plain 256 MiB copy: x2.000, x1.000).
 PROFILED_TRAFFIC = {
-    "attn_proj": {"gemm": {"fetch": 33809731, "write": 16777216},
-                  "rotate_quantize": {"fetch": 17070223, "write": 4227072}},
+    "attn_proj": {"gemm": {"fetch": 33825466, "write": 16777216},
+                  "rotate_quantize": {"fetch": 17075532, "write": 4227072}},
     "mlp_down": {"gemm": {"fetch": 90541107, "write": 16777216},
                  "rotate_quantize": {"fetch": 45743076, "write": 11337728}},
     "decode": {"gemm": {"fetch": 118156413, "write": 458752},
                "rotate_quantize": {"fetch": 659389, "write": 33024}},
-    "large_prefill": {"gemm": {"fetch": 1414509012, "write": 469762048},
-                      "rotate_quantize": {"fetch": 134738742, "write": 33816576}},
+    "large_prefill": {"gemm": {"fetch": 1414240495, "write": 469762048},
+                      "rotate_quantize": {"fetch": 134742838, "write": 33816576}},
 }
 
 
